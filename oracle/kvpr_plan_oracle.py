@@ -1,0 +1,94 @@
+"""CPU oracle for KVPR's split-point scheduler.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this file.  It shares no code with the HIP library and never imports it.
+
+The scheduler (Sec. 3.2, "Determining the optimal KV cache split point") has a
+single integer unknown l, so the oracle is brute force: evaluate the cost for
+every admissible l and keep the smallest.
+
+  Eq. 6   M_X[0:l]   = b * l * h * p           bytes of activations sent first
+          M_KV[l:s'] = 2 * b * (s' - l) * h * p bytes of cache sent afterwards
+  Eq. 8   N_KV[0:l]  = 4 * b * l * h^2          flops of the recomputation
+  Eq. 9   t_recomp   = N_KV / v_gpu
+  Eq. 10  t = M_X / v_com + max(t_recomp, M_KV / v_com)
+  Eq. 11  minimise t over 0 <= l <= s'
+
+Three cost forms are provided:
+  COST_EQ10  Eq. 10 as printed: the activations and the cache share one link,
+             the activations go first (column-by-column schedule).
+  COST_ROW   Eq. 10 with its first term dropped: the paper's row-by-row case
+             (last sentence of the split-point paragraph).
+  COST_NS    max(t_recomp + M_X/v_com, M_KV/v_com): the activation copy is
+             charged only to the compute arm, as if it travelled on a second
+             link.  Not in the paper; kept because the benchmark spec
+             paraphrases the cost this way.
+
+Readings where the paper is silent: the integer problem is solved exactly by
+enumeration, scanning l upward and keeping the first strict minimum (ties go to
+the smallest l, i.e. the least GPU work); byte and flop counts are formed as
+integers and converted to float64 once; every division is one IEEE-754 double
+division.  Optional affine terms (a fixed latency per non-empty copy / GEMM)
+extend the paper's purely linear model; they default to 0.
+"""
+from __future__ import annotations
+
+COST_EQ10 = 0
+COST_NS = 1
+COST_ROW = 2
+
+
+def bytes_x(b: int, l: int, h: int, p: int) -> int:
+    """Eq. 6, first line."""
+    return b * l * h * p
+
+
+def bytes_kv(b: int, l: int, s: int, h: int, p: int) -> int:
+    """Eq. 6, second line."""
+    return 2 * b * (s - l) * h * p
+
+
+def flops_recompute(b: int, l: int, h: int) -> int:
+    """Eq. 8."""
+    return 4 * b * l * h * h
+
+
+def cost(model: int, l: int, b: int, s: int, h: int, p: int,
+         v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0) -> float:
+    """Predicted time of one layer's KV assembly at split l (seconds)."""
+    t_act = float(bytes_x(b, l, h, p)) / v_com
+    t_kv = float(bytes_kv(b, l, s, h, p)) / v_com
+    t_rc = float(flops_recompute(b, l, h)) / v_gpu          # Eq. 9
+    if l > 0:
+        t_act = t_act + lat_com
+        t_rc = t_rc + lat_gpu
+    if l < s:
+        t_kv = t_kv + lat_com
+    if model == COST_EQ10:
+        return t_act + max(t_rc, t_kv)                      # Eq. 10
+    if model == COST_ROW:
+        return max(t_rc, t_kv)
+    if model == COST_NS:
+        return max(t_rc + t_act, t_kv)
+    raise ValueError(f"unknown cost model {model}")
+
+
+def candidates(s: int, granularity: int = 1):
+    """Admissible splits: multiples of `granularity` up to s, and s itself."""
+    if granularity < 1:
+        raise ValueError("granularity must be >= 1")
+    ls = list(range(0, s + 1, granularity))
+    if ls[-1] != s:
+        ls.append(s)
+    return ls
+
+
+def plan_split(model: int, b: int, s: int, h: int, p: int, v_com: float, v_gpu: float,
+               granularity: int = 1, lat_com: float = 0.0, lat_gpu: float = 0.0):
+    """Eq. 11 by enumeration.  Returns (l*, t(l*))."""
+    best_l, best_t = -1, float("inf")
+    for l in candidates(s, granularity):
+        t = cost(model, l, b, s, h, p, v_com, v_gpu, lat_com, lat_gpu)
+        if t < best_t:
+            best_l, best_t = l, t
+    return best_l, best_t

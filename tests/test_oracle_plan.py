@@ -1,0 +1,117 @@
+"""Pins for oracle/kvpr_plan_oracle.py: the paper's Table 1, its split-point figure,
+closed forms of the piecewise-linear cost, limits and a hand-evaluated toy."""
+import json
+import math
+import os
+
+import pytest
+
+from oracle import kvpr_plan_oracle as po
+
+
+# ---- P8: size closed forms (Eq. 6, Eq. 8) against Table 1 --------------------
+def test_table1_kv_sizes_and_pcie_time(golden_dir):
+    t1 = json.load(open(os.path.join(golden_dir, "table1_kv_sizes.json")))
+    b, s, p = t1["batch"], t1["seq"], t1["elem_bytes"]
+    for row in t1["rows"]:
+        h = row["hidden"]
+        kv = po.bytes_kv(b, 0, s, h, p)
+        assert kv == row["kv_MB"] * 2 ** 20
+        assert po.bytes_x(b, s, h, p) * 2 == kv
+        # the printed PCIe latency is size / 32 GiB/s, to the printed 3 digits
+        t0 = po.cost(po.COST_EQ10, 0, b, s, h, p, 32 * 2.0 ** 30, 1e15)
+        assert abs(t0 * 1e3 - row["pcie_ms"]) < 0.05
+        assert po.cost(po.COST_ROW, 0, b, s, h, p, 32 * 2.0 ** 30, 1e15) == t0
+
+
+def test_recompute_flops_are_two_gemms():
+    # K and V projections of b*l rows: 2 GEMMs of [b*l, h] x [h, h], 2 flops per multiply-add
+    for b, l, h in [(32, 1024, 4096), (1, 7, 768), (16, 4096, 7168)]:
+        assert po.flops_recompute(b, l, h) == 2 * (2 * (b * l) * h * h)
+    assert po.flops_recompute(32, 1024, 4096) == 2199023255552
+    assert po.flops_recompute(32, 1024, 5120) == 3435973836800
+    assert po.flops_recompute(32, 1024, 7168) == 6734508720128
+
+
+# ---- P7: hand-evaluated toy ----------------------------------------------------
+def _toy():
+    # per position: activation copy 1 s, KV copy 2 s, recompute 1 s  (b=h=1... use b*h*p = 1 byte units)
+    # b=1,h=1,p=1: M_X = l, M_KV = 2(s-l), N = 4l ; v_com = 1 B/s, v_gpu = 4 flop/s
+    return dict(b=1, s=9, h=1, p=1, v_com=1.0, v_gpu=4.0)
+
+
+def test_toy_cost_curves():
+    k = _toy()
+    e10 = [po.cost(po.COST_EQ10, l, **k) for l in range(10)]
+    ns = [po.cost(po.COST_NS, l, **k) for l in range(10)]
+    row = [po.cost(po.COST_ROW, l, **k) for l in range(10)]
+    # by hand: t_act=l, t_kv=2(9-l), t_rc=l
+    assert e10 == [18, 17, 16, 15, 14, 13, 12, 14, 16, 18]
+    assert ns == [18, 16, 14, 12, 10, 10, 12, 14, 16, 18]
+    assert row == [18, 16, 14, 12, 10, 8, 6, 7, 8, 9]
+    assert po.plan_split(po.COST_EQ10, **k) == (6, 12.0)
+    assert po.plan_split(po.COST_NS, **k) == (4, 10.0)        # tie 4/5 -> smallest
+    assert po.plan_split(po.COST_ROW, **k) == (6, 6.0)
+
+
+def test_limits():
+    kw = dict(b=32, s=1024, h=4096, p=2, v_com=50e9)
+    assert po.plan_split(po.COST_EQ10, v_gpu=1e30, **kw)[0] == 1024     # free compute: recompute everything
+    assert po.plan_split(po.COST_ROW, v_gpu=1e30, **kw)[0] == 1024
+    assert po.plan_split(po.COST_EQ10, v_gpu=1e3, **kw)[0] == 0         # no compute: transfer everything
+    l, t = po.plan_split(po.COST_EQ10, v_gpu=1e3, **kw)
+    assert t == po.bytes_kv(32, 0, 1024, 4096, 2) / 50e9
+
+
+# ---- P6: closed form of the real-valued optimum ---------------------------------
+def _lx(model, s, h, p, v_com, v_gpu):
+    rho = 2.0 * h * v_com / (p * v_gpu)
+    return s / ((1.5 if model == po.COST_NS else 1.0) + rho)
+
+
+@pytest.mark.parametrize("model", [po.COST_EQ10, po.COST_ROW, po.COST_NS])
+@pytest.mark.parametrize("b,s,h,v_com,v_gpu", [
+    (32, 1024, 4096, 57e9, 1.2e15), (1, 128, 768, 20e9, 3e13), (16, 4096, 7168, 55e9, 9e14),
+    (4, 37, 64, 1e9, 5e11), (2, 1000, 5120, 32e9, 312e12)])
+def test_argmin_brackets_closed_form(model, b, s, h, v_com, v_gpu):
+    l, t = po.plan_split(model, b, s, h, 2, v_com, v_gpu)
+    lx = _lx(model, s, h, 2, v_com, v_gpu)
+    assert l in (math.floor(lx), math.ceil(lx))
+    # brute-force property: nothing beats it, and it is the first minimum
+    ts = [po.cost(model, k, b, s, h, 2, v_com, v_gpu) for k in range(s + 1)]
+    assert t == min(ts) and l == ts.index(min(ts))
+    # proportionality: l*/s' is (nearly) constant as the sequence grows
+    l2, _ = po.plan_split(model, b, 2 * s, h, 2, v_com, v_gpu)
+    assert abs(l2 - 2 * lx) <= 1.0
+
+
+def test_paper_split_point_figure(golden_dir):
+    fig = json.load(open(os.path.join(golden_dir, "fig_split_points.json")))
+    fit = json.load(open(os.path.join(golden_dir, "fig_split_ratio.json")))
+    v_com = fit["v_com_bytes_per_s"]
+    v_gpu = fit["ratio_flop_per_byte_mid"] * v_com
+    got = [po.plan_split(po.COST_EQ10, fig["batch"], fig["prompt"] + i, fig["hidden"], fig["elem_bytes"], v_com, v_gpu)[0]
+           for i in fig["tokens_generated"]]
+    assert got == fig["split_l"]
+    # the batch size cancels out of the argmin (every term of Eq. 10 is linear in b)
+    got1 = [po.plan_split(po.COST_EQ10, 1, fig["prompt"] + i, fig["hidden"], fig["elem_bytes"], v_com, v_gpu)[0]
+            for i in fig["tokens_generated"]]
+    assert got1 == fig["split_l"]
+    # plausibility of the fitted constants for the paper's machine: ~25 GB/s PCIe 4 and ~250 TFLOP/s
+    assert 200e12 < v_gpu < 312e12
+
+
+def test_granularity_and_latency_terms():
+    kw = dict(b=32, s=1000, h=4096, p=2, v_com=57e9, v_gpu=1.2e15)
+    l1, t1 = po.plan_split(po.COST_EQ10, **kw)
+    l8, t8 = po.plan_split(po.COST_EQ10, granularity=8, **kw)
+    assert l8 % 8 == 0 and abs(l8 - l1) < 8 and t8 >= t1
+    assert po.candidates(10, 4) == [0, 4, 8, 10]
+    assert po.candidates(8, 4) == [0, 4, 8]
+    # a fixed latency on each non-empty copy / GEMM: l=0 pays one copy, l=s pays one copy and the GEMM
+    t0 = po.cost(po.COST_EQ10, 0, lat_com=1e-3, lat_gpu=5e-4, **kw)
+    assert t0 == po.bytes_kv(32, 0, 1000, 4096, 2) / 57e9 + 1e-3
+    ts = po.cost(po.COST_EQ10, 1000, lat_com=1e-3, lat_gpu=5e-4, **kw)
+    assert ts == (po.bytes_x(32, 1000, 4096, 2) / 57e9 + 1e-3) + (po.flops_recompute(32, 1000, 4096) / 1.2e15 + 5e-4)
+    with pytest.raises(ValueError):
+        po.candidates(5, 0)
