@@ -1,0 +1,196 @@
+/*
+ * kvpr.h - C ABI of libkvpr: KVPR's per-layer decode path on one AMD MI355X (gfx950).
+ *
+ * KVPR ("KV cache partial recomputation", Sec. 3) keeps every layer's KV cache and
+ * attention-input activations in pinned host memory.  For a split point l the GPU
+ * recomputes K/V of the first l positions from their activations (Eq. 7) while the
+ * cache of the remaining positions streams host->device; both halves land in one
+ * device buffer, the decode token's K/V row is appended (Eq. 5) and exact decode
+ * attention (Eq. 2) runs over all s+1 positions.  A profiler measures the link and
+ * GEMM rates, a scheduler picks l* by minimising the cost model (Eq. 10, Eq. 11).
+ *
+ * Conventions
+ *   - Every function returns int: 0 = KVPR_OK, negative = error.  Nothing throws or
+ *     aborts across this boundary.  kvpr_last_error() returns the text of the last
+ *     error raised on the calling thread.  Out-parameters are written only on success.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host
+ *     addresses.  The caller owns every pointer it passes in and the compute stream.
+ *     The context owns the pinned host store, its copy/store streams, events, the
+ *     device staging buffers for X / KV and the attention workspace; kvpr_destroy
+ *     frees them.
+ *   - Calls enqueue work and return without waiting for the GPU, except where a
+ *     timing struct is requested or the text says "synchronises".
+ *   - A context must be used from one host thread at a time.
+ *   - dtype is IEEE float16 for all tensors; accumulation is float32.
+ *
+ * Layouts (token-major, row-major, innermost index contiguous)
+ *   X   [seq, batch, hidden]        attention-input activations (the tensor that multiplies W)
+ *   KV  [seq, batch, 2*hidden]      a row is [K(hidden) | V(hidden)]; head i = columns [i*d, (i+1)*d) of each half
+ *   W*  [out_features, in_features] (in_features contiguous): y = x . W^T + b, i.e. the paper's  y = x . W  with W stored transposed
+ *   wqkv [3*hidden, hidden] = rows of Wq^T, then Wk^T, then Wv^T;  bqkv [3*hidden]
+ * With this layout X[0:l] is one contiguous [l*batch, hidden] GEMM operand, the GEMM
+ * output is rows [0,l) of the device KV buffer, and KV[l:s] is one contiguous copy.
+ */
+#ifndef KVPR_H
+#define KVPR_H
+
+#include <stdint.h>
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVPR_OK        0
+#define KVPR_E_INVAL  -1   /* null pointer, bad enum, inconsistent description        */
+#define KVPR_E_RANGE  -2   /* index / size outside the allowed range                  */
+#define KVPR_E_NOMEM  -3   /* host or device allocation failed                        */
+#define KVPR_E_HIP    -4   /* a HIP runtime call failed; text in kvpr_last_error()    */
+#define KVPR_E_STATE  -5   /* call not valid in the current state (e.g. rows unwritten) */
+
+#define KVPR_F16 1
+
+/* Cost forms for the scheduler.  EQ10 is the paper's Eq. 10 (activations and cache
+ * share one link, activations first).  ROW is Eq. 10 without its first term (the
+ * paper's row-by-row case).  NS charges the activation copy to the compute arm only:
+ * max(t_recomp + M_X/v_com, M_KV/v_com); it is not in the paper. */
+#define KVPR_COST_EQ10 0
+#define KVPR_COST_NS   1
+#define KVPR_COST_ROW  2
+
+/* debug flags for kvpr_set_debug */
+#define KVPR_DEBUG_SYNC   1  /* synchronise every stream after every enqueue             */
+#define KVPR_DEBUG_POISON 2  /* fill the device KV/X buffers with float16 NaN before each layer */
+
+typedef struct kvpr_ctx kvpr_ctx;
+
+/* User configuration (Sec. 3.1): model shape, batch and the longest sequence. */
+typedef struct {
+    int32_t n_layers;   /* >= 1                                                          */
+    int32_t hidden;     /* h; multiple of 64                                             */
+    int32_t n_heads;    /* hidden == n_heads * head_dim                                  */
+    int32_t head_dim;   /* 64 or 128                                                     */
+    int32_t ffn_dim;    /* 0 = attention block only (kvpr_decode_step then unavailable)  */
+    int32_t batch;      /* b >= 1                                                        */
+    int32_t max_seq;    /* rows per layer in the host store and device buffers; a decode at seq cached positions needs seq + 1 <= max_seq */
+    int32_t dtype;      /* KVPR_F16                                                      */
+} kvpr_model_desc;
+
+/* Profiler output (Sec. 3.1 "profiler module"): the two constants of Eq. 9 / Eq. 10
+ * plus figures that are only reported. */
+typedef struct {
+    double h2d_bytes_per_s;      /* v_com: pinned host->device rate at the full-KV copy size */
+    double gemm_flops_per_s;     /* v_gpu: recompute GEMM rate at M = batch*seq              */
+    double h2d_latency_s;        /* optional fixed cost per non-empty copy (0 = paper's linear model) */
+    double gemm_latency_s;       /* optional fixed cost per non-empty GEMM (0 = paper's linear model) */
+    double d2h_bytes_per_s;      /* reported only */
+    double attn_bytes_per_s;     /* reported only: decode attention's KV read rate           */
+    double h2d_peak_bytes_per_s; /* reported only: best rate over a 64 KiB .. 1 GiB sweep    */
+} kvpr_profile_t;
+
+/* Device pointers to one layer's parameters.  FFN / LayerNorm members may be null when ffn_dim == 0. */
+typedef struct {
+    const void *wqkv, *bqkv;   /* [3h, h], [3h]                       (Eq. 1)  */
+    const void *wo, *bo;       /* [h, h], [h]                         (Eq. 3)  */
+    const void *ln1_g, *ln1_b; /* [h] LayerNorm before attention               */
+    const void *w1, *b1;       /* [ffn, h], [ffn]                     (Eq. 4)  */
+    const void *w2, *b2;       /* [h, ffn], [h]                                */
+    const void *ln2_g, *ln2_b; /* [h] LayerNorm before the FFN                 */
+} kvpr_layer_weights;
+
+/* Per-layer timing, milliseconds from HIP events (same categories as the paper's
+ * runtime breakdown figure: load-activation, load-cache, compute, store). */
+typedef struct {
+    float ms_act_copy;   /* H2D of X[0:l]                                              */
+    float ms_kv_copy;    /* H2D of KV[l:s]                                             */
+    float ms_recompute;  /* recompute GEMM (Eq. 7)                                     */
+    float ms_proj;       /* new-token q/k/v projection (Eq. 1, Eq. 5)                  */
+    float ms_attn;       /* decode attention (Eq. 2)                                   */
+    float ms_out;        /* output projection (Eq. 3)                                  */
+    float ms_store;      /* D2H of the new X / KV rows                                 */
+    float ms_assemble;   /* first enqueue -> both KV halves resident: what Eq. 10 models */
+    float ms_total;      /* first enqueue -> output projection and store-back done     */
+    double t_bound_s;    /* cost-model prediction for the split used (0 if no profile) */
+    int32_t split;       /* the split l actually used                                   */
+    int32_t reserved;
+} kvpr_layer_timing;
+
+const char* kvpr_last_error(void);
+
+/* Create a context for `desc`.  compute_stream is a hipStream_t (may be null = the
+ * null stream) owned by the caller; all kernels are launched on it.  Allocates the
+ * pinned host store: n_layers * max_seq * batch * 3*hidden * 2 bytes, and device
+ * staging buffers for min(n_layers, 2) layers.  KVPR_E_NOMEM if that fails. */
+int kvpr_create(const kvpr_model_desc* desc, void* compute_stream, kvpr_ctx** out);
+int kvpr_destroy(kvpr_ctx* ctx);
+int kvpr_set_debug(kvpr_ctx* ctx, int flags);
+int kvpr_set_profile(kvpr_ctx* ctx, const kvpr_profile_t* prof, int cost_model, int granularity);
+
+/* Host store (Sec. 3.3 "pinned memory").  Copies rows [t0, t1) of `layer` from
+ * ordinary host memory; x_host is [t1-t0, batch, hidden], kv_host [t1-t0, batch, 2*hidden];
+ * either may be null to leave that array untouched. */
+int kvpr_store_write(kvpr_ctx* ctx, int layer, int t0, int t1, const void* x_host, const void* kv_host);
+/* Borrowed pointers to a layer's pinned arrays X[max_seq,batch,hidden] and KV[max_seq,batch,2*hidden]. */
+int kvpr_store_ptrs(kvpr_ctx* ctx, int layer, void** x_host, void** kv_host);
+/* Stand-in for prefill: computes KV[0:seq] of `layer` from the stored X[0:seq] on the
+ * GPU (Eq. 1 for K and V) and writes it into the host store.  Synchronises. */
+int kvpr_store_prefill_kv(kvpr_ctx* ctx, int layer, int seq, const kvpr_layer_weights* w);
+
+/* Profiler (Sec. 3.1): measures on this machine, for this ctx's hidden size, the pinned
+ * H2D rate at the size of a full KV copy of [seq, batch] and the recompute GEMM rate at
+ * M = batch*seq (median of 5 after warm-up).  Synchronises.  batch*seq must not exceed
+ * the context's batch*max_seq. */
+int kvpr_profile(kvpr_ctx* ctx, int batch, int seq, kvpr_profile_t* out);
+
+/* Scheduler (Sec. 3.2, Eq. 6-11).  Pure host arithmetic, no context.  Evaluates the
+ * cost for every l in {0, g, 2g, ...} U {seq} (g = granularity >= 1) in ascending order
+ * and returns the first strict minimum.  Byte / flop counts are formed in int64 and
+ * converted to double once; each rate enters through one double division. */
+int kvpr_plan_split(const kvpr_profile_t* prof, int cost_model, int batch, int seq, int hidden,
+                    int elem_bytes, int granularity, int32_t* l_star, double* t_pred);
+/* The cost model itself at one split (Eq. 10 or a variant). */
+int kvpr_cost(const kvpr_profile_t* prof, int cost_model, int split, int batch, int seq, int hidden,
+              int elem_bytes, double* t_pred);
+
+/* One decode step of one attention layer (Sec. 3.2 row-by-row pipeline with partial
+ * recomputation; Eq. 1, 2, 3, 5, 7).  `seq` = cached positions s already in the host
+ * store; split in [0, seq], or -1 to use the plan from kvpr_set_profile.
+ * x_new_dev [batch, hidden] is the decode token's attention input; out_dev [batch, hidden]
+ * receives z . Wo^T + bo.  Side effects: rows `seq` of the layer's host X and KV are
+ * written (store-back).  If timing is non-null the call synchronises and fills it. */
+int kvpr_layer_decode(kvpr_ctx* ctx, int layer, int seq, int split, const kvpr_layer_weights* w,
+                      const void* x_new_dev, void* out_dev, kvpr_layer_timing* timing);
+
+/* One decode step through all n_layers OPT-style decoder layers (pre-LayerNorm,
+ * attention block, residual, LayerNorm, ReLU FFN (Eq. 4), residual), with the next
+ * layer's transfers prefetched into the other device buffer while this layer computes
+ * (Sec. 4 "Implementation": double buffering across decoder layers).
+ * x_in_dev / x_out_dev [batch, hidden] hidden states; splits_in [n_layers] or null (= plan). */
+int kvpr_decode_step(kvpr_ctx* ctx, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
+                     void* x_out_dev, const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_layer);
+
+/* ---- individual kernels, exposed for parity tests and roofline measurement ---- */
+
+/* C[M, N] (row stride ldc halfs) = A[M, K] . W[N, K]^T + bias[N]   (Eq. 7 when W = [Wk^T ; Wv^T]).
+ * float16 in, float32 accumulate on MFMA, float16 out.  K % 64 == 0, N % 8 == 0, ldc >= N, ldc % 4 == 0.
+ * bias may be null.  M == 0 is a no-op.  stream is a hipStream_t. */
+int kvpr_recompute_gemm(const void* a_dev, const void* w_dev, const void* bias_dev, void* c_dev,
+                        int64_t M, int N, int K, int64_t ldc, void* stream);
+
+/* Exact decode attention (Eq. 2): q_dev float32 [batch, hidden] (unscaled), kv_dev float16
+ * [S, batch, 2*hidden], z_dev float16 [batch, hidden].  ws_dev is scratch of at least
+ * kvpr_attention_workspace_bytes(batch, hidden, n_heads, S) bytes.  S >= 1. */
+int kvpr_decode_attention(const void* q_dev, const void* kv_dev, void* z_dev, void* ws_dev,
+                          int S, int batch, int hidden, int n_heads, void* stream);
+size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S);
+
+/* y[M, N] = x[M, K] . W[N, K]^T + bias for small M (the decode token's projections).
+ * out_f32_cols: the first out_f32_cols columns are written as float32 to y32_dev [M, out_f32_cols]
+ * (used for q), the remaining N - out_f32_cols columns as float16 to y16_dev with row stride ld16. */
+int kvpr_token_gemm(const void* x_dev, const void* w_dev, const void* bias_dev, void* y32_dev, void* y16_dev,
+                    int M, int N, int K, int out_f32_cols, int64_t ld16, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVPR_H */

@@ -1,0 +1,233 @@
+// Exact decode attention for gfx950 (Eq. 2): one query per sequence over S positions of a
+// token-major float16 KV buffer  kv[S, batch, 2h]  (row = [K(h) | V(h)], head i = columns [i*d, (i+1)*d)).
+//
+// The kernel is bound by the single pass over KV in HBM (about 1 flop per byte), so everything is
+// arranged around 16-byte lane loads of contiguous 1 KiB wave segments:
+//   - a workgroup owns (sequence n, a group of 512 columns, a range of positions); lane L of every
+//     wave owns columns [512*cg + 8L, +8), i.e. 8 consecutive halfs of one head, for both K and V;
+//   - the 4 waves of a workgroup take interleaved runs of UNROLL positions, so 2*UNROLL independent
+//     1 KiB loads are in flight per wave;
+//   - q.k is a lane-local 8-term dot product followed by an add-butterfly over the d/8 lanes of the
+//     head with DPP row operations (no LDS, no ds_bpermute);
+//   - softmax is the usual running (max, sum) recurrence in float32 with exp2 and q pre-scaled by
+//     log2(e)/sqrt(d); the rescale is applied once per UNROLL positions;
+//   - waves are merged through LDS, position ranges ("splits") through a float32 workspace and a
+//     small combine kernel.
+#include "kvpr_internal.h"
+#include <math.h>
+
+namespace kvpr {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+constexpr int ATT_THREADS = 256;
+constexpr int ATT_WAVES = ATT_THREADS / 64;
+constexpr int COLS_PER_GROUP = 64 * 8;   // columns one wave covers
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_xchg_add(float v) {
+    const int o = __builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true);
+    return v + __int_as_float(o);
+}
+
+// sum over the D/8 consecutive lanes that hold one head; every lane of the group gets the sum
+template <int D>
+__device__ __forceinline__ float head_sum(float v) {
+    v = dpp_xchg_add<0xB1>(v);     // quad_perm [1,0,3,2]
+    v = dpp_xchg_add<0x4E>(v);     // quad_perm [2,3,0,1]
+    v = dpp_xchg_add<0x141>(v);    // row_half_mirror: 8 lanes
+    if (D == 128) v = dpp_xchg_add<0x140>(v);   // row_mirror: 16 lanes
+    return v;
+}
+
+template <int D, int UNROLL>
+__global__ __launch_bounds__(ATT_THREADS) void attention_partial(
+    const float* __restrict__ q, const _Float16* __restrict__ kv, float* __restrict__ ws_acc,
+    float* __restrict__ ws_ml, _Float16* __restrict__ z, int S, int batch, int h, int chunk, int splits,
+    float scale_log2) {
+    const int cg = blockIdx.x, n = blockIdx.y, sp = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = cg * COLS_PER_GROUP + lane * 8;
+    const bool active = col < h;
+    const int ccol = active ? col : 0;            // inactive lanes shadow column 0 and never store
+    const int64_t row_stride = (int64_t)batch * 2 * h;
+    const _Float16* kbase = kv + (int64_t)n * 2 * h + ccol;
+    const _Float16* vbase = kbase + h;
+
+    float qf[8];
+    {
+        const float4 q0 = *reinterpret_cast<const float4*>(q + (int64_t)n * h + ccol);
+        const float4 q1 = *reinterpret_cast<const float4*>(q + (int64_t)n * h + ccol + 4);
+        qf[0] = q0.x * scale_log2; qf[1] = q0.y * scale_log2; qf[2] = q0.z * scale_log2; qf[3] = q0.w * scale_log2;
+        qf[4] = q1.x * scale_log2; qf[5] = q1.y * scale_log2; qf[6] = q1.z * scale_log2; qf[7] = q1.w * scale_log2;
+    }
+
+    const int j0 = sp * chunk;
+    const int j1 = min(S, j0 + chunk);
+
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    for (int j = j0 + wave * UNROLL; j < j1; j += ATT_WAVES * UNROLL) {
+        half8 kf[UNROLL], vf[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int jj = min(j + u, j1 - 1);    // clamp: tail slots re-read the last valid row and are masked below
+            kf[u] = *reinterpret_cast<const half8*>(kbase + jj * row_stride);
+            vf[u] = *reinterpret_cast<const half8*>(vbase + jj * row_stride);
+        }
+        float sc[UNROLL];
+        float m_new = m_run;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d = fmaf((float)kf[u][e], qf[e], d);
+            d = head_sum<D>(d);
+            sc[u] = (j + u < j1) ? d : -INFINITY;
+            m_new = fmaxf(m_new, sc[u]);
+        }
+        const float rescale = exp2f(m_run - m_new);   // first round: exp2(-inf) = 0
+        l_run *= rescale;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= rescale;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const float p = exp2f(sc[u] - m_new);
+            l_run += p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)vf[u][e], acc[e]);
+        }
+        m_run = m_new;
+    }
+
+    // ---- merge the 4 waves (wave 0 always has at least one position) ----
+    __shared__ float sm[ATT_WAVES][10][64];
+    sm[wave][0][lane] = m_run;
+    sm[wave][1][lane] = l_run;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sm[wave][2 + e][lane] = acc[e];
+    __syncthreads();
+    if (wave != 0) return;
+    float m_tot = m_run;
+#pragma unroll
+    for (int w = 1; w < ATT_WAVES; ++w) m_tot = fmaxf(m_tot, sm[w][0][lane]);
+    float l_tot = 0.f;
+    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < ATT_WAVES; ++w) {
+        const float mw = sm[w][0][lane];
+        const float wt = (mw == -INFINITY) ? 0.f : exp2f(mw - m_tot);
+        l_tot += sm[w][1][lane] * wt;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] += sm[w][2 + e][lane] * wt;
+    }
+    if (!active) return;
+    if (splits == 1) {
+        const float inv = 1.f / l_tot;
+        half8 out;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = (_Float16)(o[e] * inv);
+        *reinterpret_cast<half8*>(z + (int64_t)n * h + col) = out;
+    } else {
+        float* a = ws_acc + ((int64_t)sp * batch + n) * h + col;
+        *reinterpret_cast<float4*>(a) = make_float4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<float4*>(a + 4) = make_float4(o[4], o[5], o[6], o[7]);
+        float* ml = ws_ml + (((int64_t)sp * batch + n) * (h / 8) + col / 8) * 2;
+        *reinterpret_cast<float2*>(ml) = make_float2(m_tot, l_tot);
+    }
+}
+
+// one thread per 8 columns: merge the per-split partials
+__global__ __launch_bounds__(256) void attention_combine(const float* __restrict__ ws_acc,
+                                                         const float* __restrict__ ws_ml,
+                                                         _Float16* __restrict__ z, int batch, int h, int splits) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int chunks = h / 8;
+    if (t >= (int64_t)batch * chunks) return;
+    const int n = (int)(t / chunks), c = (int)(t % chunks);
+    float m_tot = -INFINITY;
+    for (int sp = 0; sp < splits; ++sp) m_tot = fmaxf(m_tot, ws_ml[(((int64_t)sp * batch + n) * chunks + c) * 2]);
+    float l_tot = 0.f;
+    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < splits; ++sp) {
+        const float* ml = ws_ml + (((int64_t)sp * batch + n) * chunks + c) * 2;
+        const float wt = (ml[0] == -INFINITY) ? 0.f : exp2f(ml[0] - m_tot);
+        l_tot += ml[1] * wt;
+        const float* a = ws_acc + ((int64_t)sp * batch + n) * h + c * 8;
+        const float4 a0 = *reinterpret_cast<const float4*>(a), a1 = *reinterpret_cast<const float4*>(a + 4);
+        o[0] += a0.x * wt; o[1] += a0.y * wt; o[2] += a0.z * wt; o[3] += a0.w * wt;
+        o[4] += a1.x * wt; o[5] += a1.y * wt; o[6] += a1.z * wt; o[7] += a1.w * wt;
+    }
+    const float inv = 1.f / l_tot;
+    half8 out;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = (_Float16)(o[e] * inv);
+    *reinterpret_cast<half8*>(z + (int64_t)n * h + c * 8) = out;
+}
+
+int g_attn_target_blocks = 2048;
+int g_attn_force_splits = 0;
+
+struct SplitPlan { int chunk, splits; };
+SplitPlan plan_splits(int batch, int hidden, int S) {
+    const int groups = (hidden + COLS_PER_GROUP - 1) / COLS_PER_GROUP;
+    int64_t base = (int64_t)groups * batch;
+    int want = g_attn_force_splits > 0 ? g_attn_force_splits : (int)((g_attn_target_blocks + base - 1) / base);
+    const int max_splits = (S + 63) / 64;              // keep at least 64 positions per workgroup
+    if (g_attn_force_splits <= 0 && want > max_splits) want = max_splits;
+    if (want < 1) want = 1;
+    if (want > S) want = S;
+    const int chunk = (S + want - 1) / want;
+    return {chunk, (S + chunk - 1) / chunk};           // no empty split
+}
+
+}  // namespace
+
+size_t attention_workspace_bytes(int batch, int hidden, int n_heads, int S) {
+    (void)n_heads;
+    // upper bound over any split choice plan_splits can make for this shape (splits <= S, capped)
+    int64_t splits = S < 1 ? 1 : S;
+    if (splits > 512) splits = 512;
+    return (size_t)(splits * batch * (int64_t)hidden * 4 + splits * batch * (int64_t)(hidden / 8) * 8);
+}
+
+int launch_attention(const void* q, const void* kv, void* z, void* ws, int S, int batch, int hidden, int n_heads,
+                     hipStream_t st) {
+    const int d = hidden / n_heads;
+    SplitPlan sp = plan_splits(batch, hidden, S);
+    if (sp.splits > 512) {                            // workspace bound above
+        sp.chunk = (S + 511) / 512;
+        sp.splits = (S + sp.chunk - 1) / sp.chunk;
+    }
+    const int groups = (hidden + COLS_PER_GROUP - 1) / COLS_PER_GROUP;
+    float* ws_acc = (float*)ws;
+    float* ws_ml = ws_acc + (int64_t)sp.splits * batch * hidden;
+    const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)d));
+    dim3 grid(groups, batch, sp.splits);
+    if (d == 128)
+        hipLaunchKernelGGL((attention_partial<128, 4>), grid, dim3(ATT_THREADS), 0, st, (const float*)q,
+                           (const _Float16*)kv, ws_acc, ws_ml, (_Float16*)z, S, batch, hidden, sp.chunk, sp.splits,
+                           scale_log2);
+    else
+        hipLaunchKernelGGL((attention_partial<64, 4>), grid, dim3(ATT_THREADS), 0, st, (const float*)q,
+                           (const _Float16*)kv, ws_acc, ws_ml, (_Float16*)z, S, batch, hidden, sp.chunk, sp.splits,
+                           scale_log2);
+    KVPR_HIP(hipGetLastError());
+    if (sp.splits > 1) {
+        const int64_t threads = (int64_t)batch * (hidden / 8);
+        hipLaunchKernelGGL(attention_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ws_acc, ws_ml,
+                           (_Float16*)z, batch, hidden, sp.splits);
+        KVPR_HIP(hipGetLastError());
+    }
+    return KVPR_OK;
+}
+
+}  // namespace kvpr
+
+extern "C" int kvpr_debug_set_attention_splits(int force_splits, int target_blocks) {
+    kvpr::g_attn_force_splits = force_splits;
+    if (target_blocks > 0) kvpr::g_attn_target_blocks = target_blocks;
+    return KVPR_OK;
+}

@@ -1,0 +1,594 @@
+// Runtime module (Sec. 3.3): pinned host store, copy / store streams, event-fenced overlap of
+// transfer and recomputation, profiler, per-layer decode and the layer-pipelined decode step.
+#include "kvpr_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace kvpr {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+}  // namespace kvpr
+
+using kvpr::fail;
+
+namespace {
+
+typedef _Float16 half;
+
+// events bracketing each category of one layer (timing enabled)
+struct LayerEvents {
+    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, a0, a1, o1, s0, s1, end;
+    hipEvent_t* all() { return &start; }
+    static constexpr int count = 14;
+};
+
+}  // namespace
+
+struct kvpr_ctx {
+    kvpr_model_desc d{};
+    hipStream_t compute = nullptr, copy = nullptr, store = nullptr;
+    std::vector<half*> hx, hkv;          // pinned, per layer
+    std::vector<int> x_rows, kv_rows;    // contiguous prefix of rows known to hold data
+    int nbuf = 0;
+    half* dx[2] = {nullptr, nullptr};
+    half* dkv[2] = {nullptr, nullptr};
+    float* q32 = nullptr;
+    half* z16 = nullptr;
+    void* attn_ws = nullptr;
+    // hidden-state scratch of the full decoder layer
+    half *hid = nullptr, *xn = nullptr, *attn_out = nullptr, *ffn1 = nullptr, *ffn2 = nullptr;
+    // fences (timing disabled)
+    hipEvent_t ev_x[2]{}, ev_kv[2]{}, ev_free[2]{}, ev_proj = nullptr, ev_store = nullptr, ev_begin = nullptr;
+    bool free_recorded[2] = {false, false};
+    std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
+    kvpr_profile_t prof{};
+    bool have_prof = false;
+    int cost_model = KVPR_COST_EQ10, granularity = 1;
+    int debug = 0;
+
+    size_t x_row_halfs() const { return (size_t)d.batch * d.hidden; }
+    size_t kv_row_halfs() const { return (size_t)d.batch * 2 * d.hidden; }
+};
+
+namespace {
+
+int debug_sync(kvpr_ctx* c) {
+    if (c->debug & KVPR_DEBUG_SYNC) {
+        KVPR_HIP(hipStreamSynchronize(c->copy));
+        KVPR_HIP(hipStreamSynchronize(c->compute));
+        KVPR_HIP(hipStreamSynchronize(c->store));
+    }
+    return KVPR_OK;
+}
+
+int ensure_timing_events(kvpr_ctx* c, int slots) {
+    while ((int)c->tev.size() < slots) {
+        LayerEvents le{};
+        for (int i = 0; i < LayerEvents::count; ++i) KVPR_HIP(hipEventCreate(&le.all()[i]));
+        c->tev.push_back(le);
+    }
+    return KVPR_OK;
+}
+
+int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn) {
+    if (!w) return fail(KVPR_E_INVAL, "weights are null");
+    if (!w->wqkv || !w->wo) return fail(KVPR_E_INVAL, "wqkv / wo must not be null");
+    if (need_ffn && (!w->w1 || !w->w2 || !w->ln1_g || !w->ln1_b || !w->ln2_g || !w->ln2_b))
+        return fail(KVPR_E_INVAL, "FFN / LayerNorm weights must not be null for a full decoder layer");
+    (void)c;
+    return KVPR_OK;
+}
+
+int resolve_split(kvpr_ctx* c, int seq, int split, int32_t* out) {
+    if (split == -1) {
+        if (!c->have_prof) return fail(KVPR_E_STATE, "split = -1 needs kvpr_set_profile first");
+        return kvpr_plan_split(&c->prof, c->cost_model, c->d.batch, seq, c->d.hidden, 2, c->granularity, out, nullptr);
+    }
+    if (split < 0 || split > seq) return fail(KVPR_E_RANGE, "split %d outside [0, %d]", split, seq);
+    *out = split;
+    return KVPR_OK;
+}
+
+// Enqueue one attention layer's decode on the three streams.  ev may be null (no timing).
+int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weights* w, const half* x_new, half* out,
+                  int buf, LayerEvents* ev, bool fence_copy_to_start) {
+    const int b = c->d.batch, h = c->d.hidden;
+    const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
+    half* dkv = c->dkv[buf];
+    half* dx = c->dx[buf];
+
+    if (ev) KVPR_HIP(hipEventRecord(ev->start, c->compute));
+    if (c->debug & KVPR_DEBUG_POISON) {
+        if (int rc = kvpr::launch_fill_u16(dkv, (size_t)(seq + 1) * kr, 0x7E00, c->compute)) return rc;
+        if (int rc = kvpr::launch_fill_u16(dx, (size_t)seq * xr, 0x7E00, c->compute)) return rc;
+    }
+    if (fence_copy_to_start || (c->debug & KVPR_DEBUG_POISON)) {
+        KVPR_HIP(hipEventRecord(c->ev_begin, c->compute));
+        KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_begin, 0));
+    }
+
+    // ---- copy stream: activations first, then the rest of the cache (the order Eq. 10 assumes) ----
+    if (c->free_recorded[buf]) KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_free[buf], 0));
+    if (ev) KVPR_HIP(hipEventRecord(ev->c0, c->copy));
+    if (l > 0)
+        KVPR_HIP(hipMemcpyAsync(dx, c->hx[layer], (size_t)l * xr * sizeof(half), hipMemcpyHostToDevice, c->copy));
+    KVPR_HIP(hipEventRecord(c->ev_x[buf], c->copy));
+    if (ev) KVPR_HIP(hipEventRecord(ev->c_x, c->copy));
+    if (l < seq)
+        KVPR_HIP(hipMemcpyAsync(dkv + (size_t)l * kr, c->hkv[layer] + (size_t)l * kr,
+                                (size_t)(seq - l) * kr * sizeof(half), hipMemcpyHostToDevice, c->copy));
+    KVPR_HIP(hipEventRecord(c->ev_kv[buf], c->copy));
+    if (ev) KVPR_HIP(hipEventRecord(ev->c_kv, c->copy));
+    if (int rc = debug_sync(c)) return rc;
+
+    // ---- compute stream: new token's q (float32) and k|v row `seq` of the device cache (Eq. 1, Eq. 5) ----
+    if (ev) KVPR_HIP(hipEventRecord(ev->p0, c->compute));
+    if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->q32, dkv + (size_t)seq * kr, b, 3 * h, h, h,
+                                               2 * (int64_t)h, 0, c->compute))
+        return rc;
+    KVPR_HIP(hipEventRecord(c->ev_proj, c->compute));
+    if (ev) KVPR_HIP(hipEventRecord(ev->p1, c->compute));
+
+    // ---- store stream: write the new rows back to the host store ----
+    KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_proj, 0));
+    if (ev) KVPR_HIP(hipEventRecord(ev->s0, c->store));
+    KVPR_HIP(hipMemcpyAsync(c->hkv[layer] + (size_t)seq * kr, dkv + (size_t)seq * kr, kr * sizeof(half),
+                            hipMemcpyDeviceToHost, c->store));
+    KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xr, x_new, xr * sizeof(half), hipMemcpyDeviceToHost,
+                            c->store));
+    KVPR_HIP(hipEventRecord(c->ev_store, c->store));
+    if (ev) KVPR_HIP(hipEventRecord(ev->s1, c->store));
+    if (int rc = debug_sync(c)) return rc;
+
+    // ---- recompute rows [0, l) as soon as their activations have landed (Eq. 7) ----
+    KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_x[buf], 0));
+    if (ev) KVPR_HIP(hipEventRecord(ev->r0, c->compute));
+    if (l > 0) {
+        const half* wkv = (const half*)w->wqkv + (size_t)h * h;
+        const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
+        if (int rc = kvpr::launch_gemm(dx, wkv, bkv, dkv, (int64_t)l * b, 2 * h, h, 2 * (int64_t)h, c->compute))
+            return rc;
+    }
+    if (ev) KVPR_HIP(hipEventRecord(ev->r1, c->compute));
+    if (int rc = debug_sync(c)) return rc;
+
+    // ---- merge = wait for the transferred rows; then attention over all seq+1 rows (Eq. 2) ----
+    KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_kv[buf], 0));
+    if (ev) KVPR_HIP(hipEventRecord(ev->a0, c->compute));
+    if (int rc = kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, seq + 1, b, h, c->d.n_heads, c->compute))
+        return rc;
+    KVPR_HIP(hipEventRecord(c->ev_free[buf], c->compute));
+    c->free_recorded[buf] = true;
+    if (ev) KVPR_HIP(hipEventRecord(ev->a1, c->compute));
+
+    // ---- output projection (Eq. 3) ----
+    if (int rc = kvpr::launch_token_gemm_flags(c->z16, w->wo, w->bo, nullptr, out, b, h, h, 0, h, 0, c->compute))
+        return rc;
+    if (ev) KVPR_HIP(hipEventRecord(ev->o1, c->compute));
+    KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_store, 0));
+    if (ev) KVPR_HIP(hipEventRecord(ev->end, c->compute));
+    if (int rc = debug_sync(c)) return rc;
+
+    if (c->x_rows[layer] == seq) c->x_rows[layer] = seq + 1;
+    if (c->kv_rows[layer] == seq) c->kv_rows[layer] = seq + 1;
+    return KVPR_OK;
+}
+
+int read_timing(kvpr_ctx* c, LayerEvents* ev, int seq, int l, kvpr_layer_timing* t) {
+    auto ms = [&](hipEvent_t a, hipEvent_t b, float* out) -> int {
+        KVPR_HIP(hipEventElapsedTime(out, a, b));
+        return KVPR_OK;
+    };
+    kvpr_layer_timing r{};
+    float to_gemm = 0.f, to_kv = 0.f;
+    if (int rc = ms(ev->c0, ev->c_x, &r.ms_act_copy)) return rc;
+    if (int rc = ms(ev->c_x, ev->c_kv, &r.ms_kv_copy)) return rc;
+    if (int rc = ms(ev->r0, ev->r1, &r.ms_recompute)) return rc;
+    if (int rc = ms(ev->p0, ev->p1, &r.ms_proj)) return rc;
+    if (int rc = ms(ev->a0, ev->a1, &r.ms_attn)) return rc;
+    if (int rc = ms(ev->a1, ev->o1, &r.ms_out)) return rc;
+    if (int rc = ms(ev->s0, ev->s1, &r.ms_store)) return rc;
+    if (int rc = ms(ev->start, ev->r1, &to_gemm)) return rc;
+    if (int rc = ms(ev->start, ev->c_kv, &to_kv)) return rc;
+    if (int rc = ms(ev->start, ev->end, &r.ms_total)) return rc;
+    r.ms_assemble = std::max(to_gemm, to_kv);
+    r.split = l;
+    if (c->have_prof) {
+        if (int rc = kvpr_cost(&c->prof, c->cost_model, l, c->d.batch, seq, c->d.hidden, 2, &r.t_bound_s)) return rc;
+    }
+    *t = r;
+    return KVPR_OK;
+}
+
+int check_decode_args(kvpr_ctx* c, int layer, int seq) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (seq < 0 || seq + 1 > c->d.max_seq)
+        return fail(KVPR_E_RANGE, "seq %d: need 0 <= seq and seq + 1 <= max_seq = %d", seq, c->d.max_seq);
+    return KVPR_OK;
+}
+
+int check_rows(kvpr_ctx* c, int layer, int seq, int l) {
+    if (c->x_rows[layer] < l)
+        return fail(KVPR_E_STATE, "layer %d: activations of rows [%d, %d) were never written to the host store", layer,
+                    c->x_rows[layer], l);
+    if (c->kv_rows[layer] < seq && l < seq)
+        return fail(KVPR_E_STATE, "layer %d: cache rows [%d, %d) were never written to the host store", layer,
+                    c->kv_rows[layer], seq);
+    return KVPR_OK;
+}
+
+void destroy_impl(kvpr_ctx* c) {
+    if (!c) return;
+    if (c->copy) (void)hipStreamSynchronize(c->copy);
+    if (c->store) (void)hipStreamSynchronize(c->store);
+    (void)hipStreamSynchronize(c->compute);
+    for (auto p : c->hx) if (p) (void)hipHostFree(p);
+    for (auto p : c->hkv) if (p) (void)hipHostFree(p);
+    for (int i = 0; i < 2; ++i) {
+        if (c->dx[i]) (void)hipFree(c->dx[i]);
+        if (c->dkv[i]) (void)hipFree(c->dkv[i]);
+        if (c->ev_x[i]) (void)hipEventDestroy(c->ev_x[i]);
+        if (c->ev_kv[i]) (void)hipEventDestroy(c->ev_kv[i]);
+        if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
+    }
+    void* dev[] = {c->q32, c->z16, c->attn_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2};
+    for (void* p : dev) if (p) (void)hipFree(p);
+    hipEvent_t evs[] = {c->ev_proj, c->ev_store, c->ev_begin};
+    for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
+    for (auto& le : c->tev)
+        for (int i = 0; i < LayerEvents::count; ++i) (void)hipEventDestroy(le.all()[i]);
+    if (c->copy) (void)hipStreamDestroy(c->copy);
+    if (c->store) (void)hipStreamDestroy(c->store);
+    delete c;
+}
+
+}  // namespace
+
+extern "C" const char* kvpr_last_error(void) { return kvpr::g_err; }
+
+extern "C" int kvpr_create(const kvpr_model_desc* d, void* compute_stream, kvpr_ctx** out) {
+    if (!d || !out) return fail(KVPR_E_INVAL, "desc / out is null");
+    if (d->dtype != KVPR_F16) return fail(KVPR_E_INVAL, "only KVPR_F16 is supported");
+    if (d->n_layers < 1 || d->batch < 1 || d->max_seq < 1) return fail(KVPR_E_RANGE, "n_layers, batch, max_seq must be >= 1");
+    if (d->batch > 64) return fail(KVPR_E_RANGE, "batch %d > 64 is not supported by the token GEMM", d->batch);
+    if (d->head_dim != 64 && d->head_dim != 128) return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
+    if (d->n_heads < 1 || d->hidden != d->n_heads * d->head_dim)
+        return fail(KVPR_E_INVAL, "hidden (%d) != n_heads (%d) * head_dim (%d)", d->hidden, d->n_heads, d->head_dim);
+    if (d->hidden % 128) return fail(KVPR_E_INVAL, "hidden must be a multiple of 128");
+    if (d->ffn_dim < 0 || d->ffn_dim % 128) return fail(KVPR_E_INVAL, "ffn_dim must be 0 or a multiple of 128");
+
+    kvpr_ctx* c = new (std::nothrow) kvpr_ctx;
+    if (!c) return fail(KVPR_E_NOMEM, "out of host memory");
+    c->d = *d;
+    c->compute = (hipStream_t)compute_stream;
+    c->nbuf = d->n_layers > 1 ? 2 : 1;
+    const size_t x_bytes = (size_t)d->max_seq * c->x_row_halfs() * sizeof(half);
+    const size_t kv_bytes = 2 * x_bytes;
+    auto bail = [&](int code, const char* what, hipError_t e) {
+        int rc = fail(code, "%s: %s", what, hipGetErrorString(e));
+        char keep[sizeof kvpr::g_err];
+        memcpy(keep, kvpr::g_err, sizeof keep);
+        destroy_impl(c);
+        memcpy(kvpr::g_err, keep, sizeof keep);
+        return rc;
+    };
+    hipError_t e;
+    if ((e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking)) != hipSuccess) return bail(KVPR_E_HIP, "copy stream", e);
+    if ((e = hipStreamCreateWithFlags(&c->store, hipStreamNonBlocking)) != hipSuccess) return bail(KVPR_E_HIP, "store stream", e);
+    c->hx.assign(d->n_layers, nullptr);
+    c->hkv.assign(d->n_layers, nullptr);
+    c->x_rows.assign(d->n_layers, 0);
+    c->kv_rows.assign(d->n_layers, 0);
+    for (int i = 0; i < d->n_layers; ++i) {
+        if ((e = hipHostMalloc((void**)&c->hx[i], x_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned X store", e);
+        if ((e = hipHostMalloc((void**)&c->hkv[i], kv_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned KV store", e);
+    }
+    for (int i = 0; i < c->nbuf; ++i) {
+        if ((e = hipMalloc((void**)&c->dx[i], x_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "device X buffer", e);
+        if ((e = hipMalloc((void**)&c->dkv[i], kv_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "device KV buffer", e);
+    }
+    for (int i = 0; i < 2; ++i) {
+        if ((e = hipEventCreateWithFlags(&c->ev_x[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+        if ((e = hipEventCreateWithFlags(&c->ev_kv[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+        if ((e = hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+    }
+    if ((e = hipEventCreateWithFlags(&c->ev_proj, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+    if ((e = hipEventCreateWithFlags(&c->ev_store, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+    if ((e = hipEventCreateWithFlags(&c->ev_begin, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+    const size_t bh = (size_t)d->batch * d->hidden;
+    if ((e = hipMalloc((void**)&c->q32, bh * sizeof(float))) != hipSuccess) return bail(KVPR_E_NOMEM, "q buffer", e);
+    if ((e = hipMalloc((void**)&c->z16, bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "z buffer", e);
+    if ((e = hipMalloc(&c->attn_ws, kvpr::attention_workspace_bytes(d->batch, d->hidden, d->n_heads, d->max_seq))) != hipSuccess)
+        return bail(KVPR_E_NOMEM, "attention workspace", e);
+    if (d->ffn_dim > 0) {
+        half** bufs[] = {&c->hid, &c->xn, &c->attn_out, &c->ffn2};
+        for (half** p : bufs)
+            if ((e = hipMalloc((void**)p, bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "hidden-state buffer", e);
+        if ((e = hipMalloc((void**)&c->ffn1, (size_t)d->batch * d->ffn_dim * sizeof(half))) != hipSuccess)
+            return bail(KVPR_E_NOMEM, "FFN buffer", e);
+    }
+    *out = c;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_destroy(kvpr_ctx* c) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    destroy_impl(c);
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_set_debug(kvpr_ctx* c, int flags) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (flags & ~(KVPR_DEBUG_SYNC | KVPR_DEBUG_POISON)) return fail(KVPR_E_INVAL, "unknown debug flags 0x%x", flags);
+    c->debug = flags;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_set_profile(kvpr_ctx* c, const kvpr_profile_t* p, int cost_model, int granularity) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    int32_t l;
+    // validates the profile, the model and the granularity
+    if (int rc = kvpr_plan_split(p, cost_model, c->d.batch, 1, c->d.hidden, 2, granularity, &l, nullptr)) return rc;
+    c->prof = *p;
+    c->cost_model = cost_model;
+    c->granularity = granularity;
+    c->have_prof = true;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_store_write(kvpr_ctx* c, int layer, int t0, int t1, const void* x_host, const void* kv_host) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (t0 < 0 || t1 < t0 || t1 > c->d.max_seq) return fail(KVPR_E_RANGE, "rows [%d, %d) outside [0, %d]", t0, t1, c->d.max_seq);
+    // the copy/store streams may still be touching the store
+    KVPR_HIP(hipStreamSynchronize(c->copy));
+    KVPR_HIP(hipStreamSynchronize(c->store));
+    const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
+    if (x_host) {
+        memcpy(c->hx[layer] + (size_t)t0 * xr, x_host, (size_t)(t1 - t0) * xr * sizeof(half));
+        if (t0 <= c->x_rows[layer]) c->x_rows[layer] = std::max(c->x_rows[layer], t1);
+    }
+    if (kv_host) {
+        memcpy(c->hkv[layer] + (size_t)t0 * kr, kv_host, (size_t)(t1 - t0) * kr * sizeof(half));
+        if (t0 <= c->kv_rows[layer]) c->kv_rows[layer] = std::max(c->kv_rows[layer], t1);
+    }
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_store_ptrs(kvpr_ctx* c, int layer, void** x_host, void** kv_host) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (x_host) *x_host = c->hx[layer];
+    if (kv_host) *kv_host = c->hkv[layer];
+    // the caller may now write any row directly: treat all rows as holding data
+    c->x_rows[layer] = c->d.max_seq;
+    c->kv_rows[layer] = c->d.max_seq;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_store_prefill_kv(kvpr_ctx* c, int layer, int seq, const kvpr_layer_weights* w) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (seq < 0 || seq > c->d.max_seq) return fail(KVPR_E_RANGE, "seq %d outside [0, %d]", seq, c->d.max_seq);
+    if (int rc = check_weights(c, w, false)) return rc;
+    if (c->x_rows[layer] < seq) return fail(KVPR_E_STATE, "layer %d: only %d activation rows written", layer, c->x_rows[layer]);
+    if (seq == 0) return KVPR_OK;
+    const int h = c->d.hidden;
+    const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
+    KVPR_HIP(hipDeviceSynchronize());
+    KVPR_HIP(hipMemcpyAsync(c->dx[0], c->hx[layer], (size_t)seq * xr * sizeof(half), hipMemcpyHostToDevice, c->compute));
+    const half* wkv = (const half*)w->wqkv + (size_t)h * h;
+    const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
+    if (int rc = kvpr::launch_gemm(c->dx[0], wkv, bkv, c->dkv[0], (int64_t)seq * c->d.batch, 2 * h, h, 2 * (int64_t)h, c->compute))
+        return rc;
+    KVPR_HIP(hipMemcpyAsync(c->hkv[layer], c->dkv[0], (size_t)seq * kr * sizeof(half), hipMemcpyDeviceToHost, c->compute));
+    KVPR_HIP(hipStreamSynchronize(c->compute));
+    c->kv_rows[layer] = std::max(c->kv_rows[layer], seq);
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_layer_decode(kvpr_ctx* c, int layer, int seq, int split, const kvpr_layer_weights* w,
+                                 const void* x_new_dev, void* out_dev, kvpr_layer_timing* timing) {
+    if (int rc = check_decode_args(c, layer, seq)) return rc;
+    if (int rc = check_weights(c, w, false)) return rc;
+    if (!x_new_dev || !out_dev) return fail(KVPR_E_INVAL, "x_new_dev / out_dev is null");
+    int32_t l;
+    if (int rc = resolve_split(c, seq, split, &l)) return rc;
+    if (int rc = check_rows(c, layer, seq, l)) return rc;
+    LayerEvents* ev = nullptr;
+    if (timing) {
+        if (int rc = ensure_timing_events(c, 1)) return rc;
+        ev = &c->tev[0];
+    }
+    const int buf = layer % c->nbuf;
+    if (int rc = enqueue_layer(c, layer, seq, l, w, (const half*)x_new_dev, (half*)out_dev, buf, ev, true)) return rc;
+    if (timing) {
+        KVPR_HIP(hipStreamSynchronize(c->compute));
+        KVPR_HIP(hipStreamSynchronize(c->copy));
+        KVPR_HIP(hipStreamSynchronize(c->store));
+        return read_timing(c, ev, seq, l, timing);
+    }
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
+                                void* x_out_dev, const int32_t* splits_in, int32_t* splits_out,
+                                kvpr_layer_timing* per_layer) {
+    if (int rc = check_decode_args(c, 0, seq)) return rc;
+    if (c->d.ffn_dim <= 0) return fail(KVPR_E_STATE, "kvpr_decode_step needs ffn_dim > 0");
+    if (!layers || !x_in_dev || !x_out_dev) return fail(KVPR_E_INVAL, "layers / x_in_dev / x_out_dev is null");
+    const int L = c->d.n_layers, b = c->d.batch, h = c->d.hidden, f = c->d.ffn_dim;
+    std::vector<int32_t> ls(L);
+    for (int i = 0; i < L; ++i) {
+        if (int rc = check_weights(c, &layers[i], true)) return rc;
+        if (int rc = resolve_split(c, seq, splits_in ? splits_in[i] : -1, &ls[i])) return rc;
+        if (int rc = check_rows(c, i, seq, ls[i])) return rc;
+    }
+    if (per_layer)
+        if (int rc = ensure_timing_events(c, L)) return rc;
+    const size_t bh = (size_t)b * h;
+    const half* hid_in = (const half*)x_in_dev;
+    for (int i = 0; i < L; ++i) {
+        const kvpr_layer_weights* w = &layers[i];
+        half* hid_out = (i == L - 1) ? (half*)x_out_dev : c->hid;
+        // pre-LayerNorm -> attention block -> residual
+        if (int rc = kvpr::launch_layernorm(hid_in, w->ln1_g, w->ln1_b, c->xn, b, h, c->compute)) return rc;
+        if (int rc = enqueue_layer(c, i, seq, ls[i], w, c->xn, c->attn_out, i % c->nbuf, per_layer ? &c->tev[i] : nullptr, false))
+            return rc;
+        if (int rc = kvpr::launch_add(hid_in, c->attn_out, c->ffn2, bh, c->compute)) return rc;      // ffn2 = residual stream
+        // LayerNorm -> FFN (Eq. 4, ReLU) -> residual
+        if (int rc = kvpr::launch_layernorm(c->ffn2, w->ln2_g, w->ln2_b, c->xn, b, h, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, w->b1, nullptr, c->ffn1, b, f, h, 0, f, 1, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->ffn1, w->w2, w->b2, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
+        if (int rc = kvpr::launch_add(c->ffn2, c->attn_out, hid_out, bh, c->compute)) return rc;
+        hid_in = hid_out;
+    }
+    if (splits_out) std::copy(ls.begin(), ls.end(), splits_out);
+    if (per_layer) {
+        KVPR_HIP(hipStreamSynchronize(c->compute));
+        KVPR_HIP(hipStreamSynchronize(c->copy));
+        KVPR_HIP(hipStreamSynchronize(c->store));
+        for (int i = 0; i < L; ++i)
+            if (int rc = read_timing(c, &c->tev[i], seq, ls[i], &per_layer[i])) return rc;
+    }
+    return KVPR_OK;
+}
+
+// ---- individual kernels ----
+extern "C" int kvpr_recompute_gemm(const void* a, const void* w, const void* bias, void* cdev, int64_t M, int N, int K,
+                                   int64_t ldc, void* stream) {
+    if (M < 0 || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%lld N=%d K=%d out of range", (long long)M, N, K);
+    if (K % 64 || N % 8 || ldc < N || ldc % 4) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 4 == 0");
+    if (M == 0) return KVPR_OK;
+    if (!a || !w || !cdev) return fail(KVPR_E_INVAL, "a / w / c is null");
+    return kvpr::launch_gemm(a, w, bias, cdev, M, N, K, ldc, (hipStream_t)stream);
+}
+
+extern "C" size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S) {
+    if (batch < 1 || hidden < 1 || S < 1) return 0;
+    return kvpr::attention_workspace_bytes(batch, hidden, n_heads, S);
+}
+
+extern "C" int kvpr_decode_attention(const void* q, const void* kv, void* z, void* ws, int S, int batch, int hidden,
+                                     int n_heads, void* stream) {
+    if (S < 1 || batch < 1 || n_heads < 1) return fail(KVPR_E_RANGE, "S=%d batch=%d n_heads=%d out of range", S, batch, n_heads);
+    if (hidden % n_heads || (hidden / n_heads != 64 && hidden / n_heads != 128))
+        return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
+    if (!q || !kv || !z || !ws) return fail(KVPR_E_INVAL, "q / kv / z / ws is null");
+    return kvpr::launch_attention(q, kv, z, ws, S, batch, hidden, n_heads, (hipStream_t)stream);
+}
+
+extern "C" int kvpr_token_gemm(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
+                               int out_f32_cols, int64_t ld16, void* stream) {
+    if (M < 1 || M > 64 || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%d (1..64) N=%d K=%d out of range", M, N, K);
+    if (K % 128) return fail(KVPR_E_INVAL, "K must be a multiple of 128");
+    if (out_f32_cols < 0 || out_f32_cols > N) return fail(KVPR_E_RANGE, "out_f32_cols outside [0, N]");
+    if (!x || !w || (out_f32_cols > 0 && !y32) || (out_f32_cols < N && !y16)) return fail(KVPR_E_INVAL, "null pointer");
+    if (out_f32_cols < N && ld16 < N - out_f32_cols) return fail(KVPR_E_INVAL, "ld16 too small");
+    return kvpr::launch_token_gemm_flags(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, 0, (hipStream_t)stream);
+}
+
+// ---- profiler (Sec. 3.1) ----
+namespace {
+
+template <class F>
+int time_median(hipStream_t st, int reps, F fn, double* seconds) {
+    hipEvent_t e0, e1;
+    KVPR_HIP(hipEventCreate(&e0));
+    KVPR_HIP(hipEventCreate(&e1));
+    int rc = fn();                                   // warm-up
+    if (rc == KVPR_OK && hipStreamSynchronize(st) != hipSuccess) rc = fail(KVPR_E_HIP, "profiler warm-up failed");
+    std::vector<float> ms(reps);
+    for (int r = 0; r < reps && rc == KVPR_OK; ++r) {
+        if (hipEventRecord(e0, st) != hipSuccess) { rc = fail(KVPR_E_HIP, "event record failed"); break; }
+        rc = fn();
+        if (rc != KVPR_OK) break;
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms[r], e0, e1) != hipSuccess)
+            rc = fail(KVPR_E_HIP, "profiler timing failed");
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != KVPR_OK) return rc;
+    std::sort(ms.begin(), ms.end());
+    *seconds = (double)ms[reps / 2] * 1e-3;
+    return KVPR_OK;
+}
+
+}  // namespace
+
+extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out) {
+    if (!c || !out) return fail(KVPR_E_INVAL, "ctx / out is null");
+    if (batch < 1 || seq < 1) return fail(KVPR_E_RANGE, "batch and seq must be >= 1");
+    const int64_t rows = (int64_t)batch * seq;
+    if (rows > (int64_t)c->d.batch * (c->d.max_seq - 1))
+        return fail(KVPR_E_RANGE, "batch*seq = %lld exceeds the context's batch*(max_seq-1)", (long long)rows);
+    const int h = c->d.hidden;
+    const size_t kv_bytes = (size_t)rows * 2 * h * sizeof(half);
+    const size_t cap_bytes = (size_t)c->d.max_seq * c->kv_row_halfs() * sizeof(half);
+    KVPR_HIP(hipDeviceSynchronize());
+    kvpr_profile_t p{};
+    double t = 0;
+    half* hkv = c->hkv[0];
+    half* dkv = c->dkv[0];
+
+    // v_com: one pinned copy of the size of the whole cache of [seq, batch]
+    if (int rc = time_median(c->copy, 5, [&]() -> int {
+            KVPR_HIP(hipMemcpyAsync(dkv, hkv, kv_bytes, hipMemcpyHostToDevice, c->copy));
+            return KVPR_OK; }, &t)) return rc;
+    p.h2d_bytes_per_s = (double)kv_bytes / t;
+    // d2h: the same bytes back to where they came from (the store keeps its contents)
+    if (int rc = time_median(c->store, 3, [&]() -> int {
+            KVPR_HIP(hipMemcpyAsync(hkv, dkv, kv_bytes, hipMemcpyDeviceToHost, c->store));
+            return KVPR_OK; }, &t)) return rc;
+    p.d2h_bytes_per_s = (double)kv_bytes / t;
+    // best H2D rate over a size sweep
+    p.h2d_peak_bytes_per_s = p.h2d_bytes_per_s;
+    for (size_t sz = (size_t)64 << 10; sz <= std::min(cap_bytes, (size_t)1 << 30); sz *= 4) {
+        if (int rc = time_median(c->copy, 5, [&]() -> int {
+                KVPR_HIP(hipMemcpyAsync(dkv, hkv, sz, hipMemcpyHostToDevice, c->copy));
+                return KVPR_OK; }, &t)) return rc;
+        p.h2d_peak_bytes_per_s = std::max(p.h2d_peak_bytes_per_s, (double)sz / t);
+    }
+    KVPR_HIP(hipDeviceSynchronize());
+
+    // v_gpu: the recompute GEMM at M = batch*seq on random operands
+    half* wtmp = nullptr;
+    if (hipMalloc((void**)&wtmp, (size_t)2 * h * h * sizeof(half)) != hipSuccess)
+        return fail(KVPR_E_NOMEM, "profiler weight buffer");
+    int rc = kvpr::launch_fill_random(wtmp, (size_t)2 * h * h, 0.035f, 1u, c->compute);
+    if (!rc) rc = kvpr::launch_fill_random(c->dx[0], (size_t)rows * h, 1.7f, 2u, c->compute);
+    if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
+            return kvpr::launch_gemm(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->compute); }, &t);
+    if (!rc) p.gemm_flops_per_s = 4.0 * (double)rows * h * h / t;
+    // attention read rate over the cache just produced (context batch, S = rows / batch positions)
+    const int S = (int)(rows / c->d.batch);
+    if (!rc && S >= 1) {
+        rc = kvpr::launch_fill_random(c->z16, (size_t)c->d.batch * h, 1.0f, 3u, c->compute);   // any finite q source
+        if (!rc) rc = hipMemsetAsync(c->q32, 0, (size_t)c->d.batch * h * sizeof(float), c->compute) == hipSuccess
+                          ? KVPR_OK : fail(KVPR_E_HIP, "memset failed");
+        if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
+                return kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, c->d.batch, h, c->d.n_heads, c->compute); }, &t);
+        if (!rc) p.attn_bytes_per_s = (double)S * c->d.batch * 2 * h * sizeof(half) / t;
+    }
+    (void)hipDeviceSynchronize();
+    (void)hipFree(wtmp);
+    if (rc) return rc;
+    *out = p;
+    return KVPR_OK;
+}

@@ -1,0 +1,114 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header
+declares, the planner agrees bit for bit with the oracle, and bad arguments are refused
+before anything touches the GPU."""
+import os
+import re
+
+import pytest
+
+from oracle import kvpr_plan_oracle as po
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def k():
+    import paper_2411_17089_amd as k
+    return k
+
+
+def test_library_exports_every_declared_symbol(k):
+    header = open(os.path.join(ROOT, "include", "kvpr.h")).read()
+    declared = set(re.findall(r"\b(kvpr_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(k.EXPORTS), (declared ^ set(k.EXPORTS))
+    for name in declared:
+        assert hasattr(k.lib, name), name
+
+
+MODELS = [(po.COST_EQ10, "KVPR_COST_EQ10"), (po.COST_NS, "KVPR_COST_NS"), (po.COST_ROW, "KVPR_COST_ROW")]
+
+
+@pytest.mark.parametrize("model,cname", MODELS)
+def test_planner_bit_exact_against_oracle(k, model, cname):
+    assert getattr(k, cname) == model
+    cases = []
+    for b in (1, 16, 32, 64):
+        for s in (0, 1, 7, 128, 1000, 1024, 4096):
+            for h in (768, 4096, 7168):
+                for v_com, v_gpu in ((57.3e9, 1.31e15), (32 * 2.0 ** 30, 2.5e14), (1.0, 4.0), (3.3e10, 7.77e14)):
+                    cases.append((b, s, h, v_com, v_gpu))
+    for b, s, h, v_com, v_gpu in cases:
+        prof = k.make_profile(v_com, v_gpu)
+        for g in (1, 8):
+            want = po.plan_split(model, b, s, h, 2, v_com, v_gpu, granularity=g)
+            got = k.kvpr_plan_split(prof, model, b, s, h, 2, g)
+            assert got == want, (b, s, h, v_com, v_gpu, g)
+        for l in {0, s // 3, s}:
+            assert k.kvpr_cost(prof, model, l, b, s, h, 2) == po.cost(model, l, b, s, h, 2, v_com, v_gpu)
+
+
+def test_planner_ties_and_latency_terms(k):
+    prof = k.make_profile(1.0, 4.0)
+    assert k.kvpr_plan_split(prof, k.KVPR_COST_NS, 1, 9, 1, 1, 1) == (4, 10.0)     # tie 4/5 -> smallest
+    prof = k.make_profile(57e9, 1.2e15, 1e-3, 5e-4)
+    for s in (100, 1024):
+        want = po.plan_split(po.COST_EQ10, 32, s, 4096, 2, 57e9, 1.2e15, 1, 1e-3, 5e-4)
+        assert k.kvpr_plan_split(prof, k.KVPR_COST_EQ10, 32, s, 4096, 2, 1) == want
+        for l in (0, 1, s):
+            assert k.kvpr_cost(prof, 0, l, 32, s, 4096, 2) == po.cost(0, l, 32, s, 4096, 2, 57e9, 1.2e15, 1e-3, 5e-4)
+
+
+def test_planner_rejects_bad_arguments(k):
+    good = k.make_profile(1e9, 1e12)
+    for prof in (k.make_profile(0.0, 1e12), k.make_profile(1e9, -1.0), k.make_profile(float("nan"), 1e12),
+                 k.make_profile(1e9, float("inf")), k.make_profile(1e9, 1e12, -1.0, 0.0)):
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_plan_split(prof, 0, 1, 8, 64, 2, 1)
+        assert e.value.code == k.KVPR_E_INVAL
+    for args in ((7, 1, 8, 64, 2, 1),):
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_plan_split(good, *args)
+        assert e.value.code == k.KVPR_E_INVAL
+    for args in ((0, 0, 8, 64, 2, 1), (0, 1, -1, 64, 2, 1), (0, 1, 8, 64, 2, 0), (0, 1, 8, 0, 2, 1)):
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_plan_split(good, *args)
+        assert e.value.code == k.KVPR_E_RANGE
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_cost(good, 0, 9, 1, 8, 64, 2)
+    assert e.value.code == k.KVPR_E_RANGE
+    assert "split" in k.kvpr_last_error()
+
+
+def test_kernel_entry_points_validate_before_touching_the_gpu(k):
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_recompute_gemm(1, 1, None, 1, 5, 64, 100, 64, stream=0)       # K % 64
+    assert e.value.code == k.KVPR_E_INVAL
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_recompute_gemm(1, 1, None, 1, -1, 64, 64, 64, stream=0)
+    assert e.value.code == k.KVPR_E_RANGE
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_decode_attention(1, 1, 1, 1, 4, 1, 96, 1, stream=0)            # head_dim 96
+    assert e.value.code == k.KVPR_E_INVAL
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_decode_attention(1, 1, 1, 1, 0, 1, 128, 1, stream=0)           # S = 0
+    assert e.value.code == k.KVPR_E_RANGE
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_token_gemm(1, 1, None, 1, 1, 65, 64, 128, 0, 64, stream=0)     # M > 64
+    assert e.value.code == k.KVPR_E_RANGE
+    assert k.kvpr_attention_workspace_bytes(32, 4096, 32, 1025) > 0
+
+
+def test_create_rejects_bad_descriptions(k):
+    bad = [dict(hidden=768, n_heads=12, head_dim=32), dict(hidden=768, n_heads=11, head_dim=64),
+           dict(hidden=96 * 2, n_heads=2, head_dim=96), dict(dtype=7), dict(ffn_dim=100)]
+    base = dict(n_layers=1, hidden=768, n_heads=12, head_dim=64, ffn_dim=0, batch=1, max_seq=16, dtype=k.KVPR_F16)
+    for upd in bad:
+        kw = dict(base, **upd)
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_create(stream=0, **kw)
+        assert e.value.code == k.KVPR_E_INVAL, upd
+    for upd in (dict(batch=0), dict(n_layers=0), dict(max_seq=0), dict(batch=65)):
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_create(stream=0, **dict(base, **upd))
+        assert e.value.code == k.KVPR_E_RANGE, upd
