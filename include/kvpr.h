@@ -161,6 +161,13 @@ int kvpr_cost(const kvpr_profile_t* prof, int cost_model, int split, int batch, 
 int kvpr_layer_decode(kvpr_ctx* ctx, int layer, int seq, int split, const kvpr_layer_weights* w,
                       const void* x_new_dev, void* out_dev, kvpr_layer_timing* timing);
 
+/* As kvpr_layer_decode, but records HIP events around every category into timing slot
+ * `slot` (0 .. 4095) and does not wait; kvpr_timing_read waits for that slot's events and
+ * converts them.  Lets a timed loop stay asynchronous. */
+int kvpr_layer_decode_timed(kvpr_ctx* ctx, int layer, int seq, int split, const kvpr_layer_weights* w,
+                            const void* x_new_dev, void* out_dev, int slot);
+int kvpr_timing_read(kvpr_ctx* ctx, int slot, kvpr_layer_timing* timing);
+
 /* One decode step through all n_layers OPT-style decoder layers (pre-LayerNorm,
  * attention block, residual, LayerNorm, ReLU FFN (Eq. 4), residual), with the next
  * layer's transfers prefetched into the other device buffer while this layer computes

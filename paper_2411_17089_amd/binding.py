@@ -9,6 +9,10 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+# torch ships its own HIP runtime; load it first so that libkvpr.so binds to the same runtime
+# instance that owns torch's device memory and streams (two runtimes in one process do not mix).
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvpr.so")
 
@@ -68,6 +72,8 @@ _SIGS = {
     "kvpr_plan_split": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "kvpr_cost": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_double)]),
     "kvpr_layer_decode": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(kvpr_layer_timing)]),
+    "kvpr_layer_decode_timed": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, _i]),
+    "kvpr_timing_read": (_i, [_vp, _i, C.POINTER(kvpr_layer_timing)]),
     "kvpr_decode_step": (_i, [_vp, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(kvpr_layer_timing)]),
     "kvpr_recompute_gemm": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp]),
     "kvpr_decode_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
@@ -100,7 +106,6 @@ def _ptr(t):
 
 def _stream(stream):
     if stream is None:
-        import torch
         return torch.cuda.current_stream().cuda_stream
     return getattr(stream, "cuda_stream", stream)
 
@@ -176,6 +181,16 @@ def kvpr_layer_decode(ctx, layer, seq, split, weights, x_new_dev, out_dev, timin
     t = kvpr_layer_timing() if timing else None
     _check(lib.kvpr_layer_decode(ctx, layer, seq, split, C.byref(weights), _ptr(x_new_dev), _ptr(out_dev),
                                  C.byref(t) if timing else None))
+    return t
+
+
+def kvpr_layer_decode_timed(ctx, layer, seq, split, weights, x_new_dev, out_dev, slot):
+    _check(lib.kvpr_layer_decode_timed(ctx, layer, seq, split, C.byref(weights), _ptr(x_new_dev), _ptr(out_dev), slot))
+
+
+def kvpr_timing_read(ctx, slot) -> kvpr_layer_timing:
+    t = kvpr_layer_timing()
+    _check(lib.kvpr_timing_read(ctx, slot, C.byref(t)))
     return t
 
 

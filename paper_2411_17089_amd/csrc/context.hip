@@ -32,6 +32,7 @@ typedef _Float16 half;
 // events bracketing each category of one layer (timing enabled)
 struct LayerEvents {
     hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, a0, a1, o1, s0, s1, end;
+    int seq = -1, split = -1;            // what the slot last recorded
     hipEvent_t* all() { return &start; }
     static constexpr int count = 14;
 };
@@ -111,7 +112,11 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     half* dkv = c->dkv[buf];
     half* dx = c->dx[buf];
 
-    if (ev) KVPR_HIP(hipEventRecord(ev->start, c->compute));
+    if (ev) {
+        ev->seq = seq;
+        ev->split = l;
+        KVPR_HIP(hipEventRecord(ev->start, c->compute));
+    }
     if (c->debug & KVPR_DEBUG_POISON) {
         if (int rc = kvpr::launch_fill_u16(dkv, (size_t)(seq + 1) * kr, 0x7E00, c->compute)) return rc;
         if (int rc = kvpr::launch_fill_u16(dx, (size_t)seq * xr, 0x7E00, c->compute)) return rc;
@@ -424,6 +429,30 @@ extern "C" int kvpr_layer_decode(kvpr_ctx* c, int layer, int seq, int split, con
         return read_timing(c, ev, seq, l, timing);
     }
     return KVPR_OK;
+}
+
+extern "C" int kvpr_layer_decode_timed(kvpr_ctx* c, int layer, int seq, int split, const kvpr_layer_weights* w,
+                                       const void* x_new_dev, void* out_dev, int slot) {
+    if (int rc = check_decode_args(c, layer, seq)) return rc;
+    if (int rc = check_weights(c, w, false)) return rc;
+    if (!x_new_dev || !out_dev) return fail(KVPR_E_INVAL, "x_new_dev / out_dev is null");
+    if (slot < 0 || slot >= 4096) return fail(KVPR_E_RANGE, "timing slot %d outside [0, 4096)", slot);
+    int32_t l;
+    if (int rc = resolve_split(c, seq, split, &l)) return rc;
+    if (int rc = check_rows(c, layer, seq, l)) return rc;
+    if (int rc = ensure_timing_events(c, slot + 1)) return rc;
+    return enqueue_layer(c, layer, seq, l, w, (const half*)x_new_dev, (half*)out_dev, layer % c->nbuf, &c->tev[slot], true);
+}
+
+extern "C" int kvpr_timing_read(kvpr_ctx* c, int slot, kvpr_layer_timing* timing) {
+    if (!c || !timing) return fail(KVPR_E_INVAL, "ctx / timing is null");
+    if (slot < 0 || slot >= (int)c->tev.size() || c->tev[slot].seq < 0)
+        return fail(KVPR_E_STATE, "timing slot %d holds no recording", slot);
+    LayerEvents* ev = &c->tev[slot];
+    KVPR_HIP(hipEventSynchronize(ev->end));
+    KVPR_HIP(hipEventSynchronize(ev->c_kv));
+    KVPR_HIP(hipEventSynchronize(ev->s1));
+    return read_timing(c, ev, ev->seq, ev->split, timing);
 }
 
 extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
