@@ -3,17 +3,25 @@
 // A = X[0:l] flattened to [l*batch, hidden], W = [Wk^T ; Wv^T] ([2h, h], K contiguous), C = rows
 // [0, l) of the device KV buffer (row stride ldc = 2h), so the result needs no copy or merge pass.
 //
-// Design (MI355X): one workgroup owns a BM x BN tile of C and walks K in steps of 64.  Both operand
-// tiles are K-contiguous, staged through LDS as 128-byte rows whose 16-byte chunks are XOR-swizzled
-// by the row index so that the ds_read_b128 of 32 consecutive rows is bank-conflict free.  Waves
-// hold (BM/WM) x (BN/WN) sub-tiles as 32x32 accumulators of v_mfma_f32_32x32x16_f16.  The MFMA is
-// issued "transposed" (W rows feed the instruction's row operand, X rows its column operand) so
-// that each lane ends up with 4 consecutive output columns per accumulator quad and writes 8-byte
-// pieces of a C row.  LDS is double-buffered: global loads for step k+1 are in flight while the
-// MFMAs of step k run, one barrier per step.  Workgroup ids are remapped so that the workgroups an
-// XCD runs concurrently (ids equal mod 8) form a compact block of tiles sharing A/W panels in that
-// XCD's L2.
+// Design (MI355X):
+//  * One workgroup owns a BM x BN tile of C (256 x 256 by default, 8 waves as 4 x 2) and walks K in
+//    stages of 32.  A stage is (BM + BN) rows of 64 bytes in LDS; NSTAGE = 4 stages form a ring.
+//  * Stages are filled by direct global->LDS DMA (global_load_lds_dwordx4): no staging registers, no
+//    ds_write.  A wave-load covers 16 rows x 64 B; the 16-byte chunks of a row are XOR-swizzled by
+//    (row/4)%4 on the global-address side so that the ds_read_b128 of 16 consecutive rows touches 16
+//    different bank groups (measured: SQ_LDS_BANK_CONFLICT = 0).
+//  * The loop is software-pipelined by hand: the workgroup barrier sits between two MFMA groups, each
+//    group covers the LDS latency of the next operand fragments and the issue of the refill DMA, and
+//    the wait before the barrier is a counted vmcnt (the NSTAGE-2 younger stages stay in flight).
+//  * v_mfma_f32_32x32x16_f16 is issued "transposed" (W rows feed the instruction's row operand, X
+//    rows its column operand) so a lane owns 4 consecutive output columns per accumulator quad.
+//  * Epilogue: bias + conversion in registers, C tile staged through LDS, global stores of whole
+//    512-byte row pieces (the direct 8-byte stores of the first version cost ~15 % of the kernel).
+//  * Workgroup ids are remapped so that the workgroups an XCD runs concurrently (ids equal mod 8)
+//    form a compact block of tiles sharing A/W panels in that XCD's L2.
+//  * Tail rows in M / N are clamped on load (they re-read the last valid row) and skipped on store.
 #include "kvpr_internal.h"
+#include <type_traits>
 
 namespace kvpr {
 namespace {
@@ -21,26 +29,34 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
-constexpr int BK = 64;          // halfs per K step = one 128-byte LDS row
-constexpr int ROW_BYTES = 128;
+constexpr int BK = 32;          // halfs per stage
+constexpr int ROW_BYTES = 64;   // one LDS row of a stage
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+template <int VM, int LGKM0>
+__device__ __forceinline__ void wait_counts() {
+    // vmcnt(VM) [bits 3:0 and 15:14], expcnt untouched (7), lgkmcnt(0) if LGKM0 else untouched (15)
+    __builtin_amdgcn_s_waitcnt((VM & 15) | ((VM >> 4) << 14) | 0x0070 | (LGKM0 ? 0 : 0x0F00));
+}
 
-template <int BM, int BN, int WM, int WN, int GROUP_M>
+template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     const _Float16* __restrict__ A, const _Float16* __restrict__ W, const _Float16* __restrict__ bias,
     _Float16* __restrict__ C, int64_t M, int N, int K, int64_t ldc, int tiles_m, int tiles_n, int tiles_per_xcd) {
-    constexpr int NT = WM * WN * 64;
-    constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
-    constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wave
-    constexpr int A_CHUNKS = BM * 8 / NT, W_CHUNKS = BN * 8 / NT;
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
+    constexpr int NW = WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int BLOCKS = (BM + BN) / 16;
+    constexpr int LOADS = BLOCKS / NW;
+    static_assert(BLOCKS % NW == 0, "tile/waves mismatch");
+    static_assert(NSTAGE >= 3 && NSTAGE <= 4, "ring depth");
     constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+    constexpr int NMFMA = TM * TN, NFRAG = TM + TN;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
-    // ---- which tile: XCD-aware, grouped raster ----
     const int pid = blockIdx.x;
     const int logical = (pid & 7) * tiles_per_xcd + (pid >> 3);
     if (logical >= tiles_m * tiles_n) return;
@@ -56,54 +72,49 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- global -> register staging: chunk q covers row q/8, 16-byte chunk q%8 of a tile ----
-    const _Float16* a_src[A_CHUNKS];
-    const _Float16* w_src[W_CHUNKS];
-    int a_dst[A_CHUNKS], w_dst[W_CHUNKS];
+    // wave-load i of this wave fills stage rows [16*blk, 16*blk+16) (A rows first, then W rows); lane L
+    // lands at row 16*blk + L/4, physical chunk L%4, and therefore fetches logical chunk (L%4)^((row/4)%4)
+    const _Float16* src[LOADS];
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-        const int q = tid + i * NT, row = q >> 3, c = q & 7;
-        int64_t gr = m0 + row;
-        if (gr > M - 1) gr = M - 1;                                  // clamp: tail rows re-read the last row
-        a_src[i] = A + gr * K + c * 8;
-        a_dst[i] = row * ROW_BYTES + swz(row, c) * 16;
+    for (int i = 0; i < LOADS; ++i) {
+        const int blk = wave + i * NW;
+        const int row = blk * 16 + (lane >> 2);
+        const int pc = lane & 3;
+        if (blk * 16 < BM) {
+            int64_t gr = m0 + row;
+            if (gr > M - 1) gr = M - 1;
+            src[i] = A + gr * K + ((pc ^ ((row >> 2) & 3)) << 3);
+        } else {
+            const int wr = row - BM;
+            int gr = n0 + wr;
+            if (gr > N - 1) gr = N - 1;
+            src[i] = W + (int64_t)gr * K + ((pc ^ ((wr >> 2) & 3)) << 3);
+        }
     }
+    auto issue_loads = [&](int kt) {
+        unsigned char* base = lds + (kt % NSTAGE) * STAGE_BYTES + wave * 1024;
 #pragma unroll
-    for (int i = 0; i < W_CHUNKS; ++i) {
-        const int q = tid + i * NT, row = q >> 3, c = q & 7;
-        int gr = n0 + row;
-        if (gr > N - 1) gr = N - 1;
-        w_src[i] = W + (int64_t)gr * K + c * 8;
-        w_dst[i] = BM * ROW_BYTES + row * ROW_BYTES + swz(row, c) * 16;
-    }
-
-    half8 a_reg[A_CHUNKS], w_reg[W_CHUNKS];
-    auto load_global = [&](int kt) {
-        const int koff = kt * BK;
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = *reinterpret_cast<const half8*>(a_src[i] + koff);
-#pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) w_reg[i] = *reinterpret_cast<const half8*>(w_src[i] + koff);
-    };
-    auto store_lds = [&](int buf) {
-        unsigned char* base = lds + buf * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<half8*>(base + a_dst[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) *reinterpret_cast<half8*>(base + w_dst[i]) = w_reg[i];
+        for (int i = 0; i < LOADS; ++i)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src[i] + kt * BK), (lds_ptr_t)(base + i * NW * 1024), 16, 0, 0);
     };
 
-    // ---- per-lane LDS read offsets of the MFMA fragments ----
-    // lane supplies row (lane % 32) of a 32-row fragment and the 8 halfs of k-chunk (2*kk + lane/32)
     const int frow = lane & 31, fhalf = lane >> 5;
-    int a_row[TM], w_row[TN];
+    int a_off[TM][2], w_off[TN][2];
 #pragma unroll
-    for (int t = 0; t < TM; ++t) a_row[t] = wm * WTM + t * 32 + frow;
+    for (int t = 0; t < TM; ++t) {
+        const int r = wm * WTM + t * 32 + frow;
 #pragma unroll
-    for (int t = 0; t < TN; ++t) w_row[t] = wn * WTN + t * 32 + frow;
+        for (int kk = 0; kk < 2; ++kk) a_off[t][kk] = r * ROW_BYTES + (((kk * 2 + fhalf) ^ ((r >> 2) & 3)) << 4);
+    }
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        const int r = wn * WTN + t * 32 + frow;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) w_off[t][kk] = BM * ROW_BYTES + r * ROW_BYTES + (((kk * 2 + fhalf) ^ ((r >> 2) & 3)) << 4);
+    }
 
     floatx16 acc[TN][TM];
 #pragma unroll
@@ -113,69 +124,115 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    half8 af0[TM], wf0[TN], af1[TM], wf1[TN];
+    auto load_frags = [&](int kt, int kk, half8* af, half8* wf) {
+        const unsigned char* st = lds + (kt % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+        for (int t = 0; t < TM; ++t) af[t] = *reinterpret_cast<const half8*>(st + a_off[t][kk]);
+#pragma unroll
+        for (int t = 0; t < TN; ++t) wf[t] = *reinterpret_cast<const half8*>(st + w_off[t][kk]);
+    };
+    auto mfma_group = [&](const half8* af, const half8* wf) {
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], af[j], acc[i][j], 0, 0, 0);
+    };
     const int KT = K / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
+#pragma unroll
+    for (int d = 0; d < NSTAGE; ++d)
+        if (d < KT) issue_loads(d);
+    if (KT >= NSTAGE) wait_counts<(NSTAGE - 1) * LOADS, 0>();
+    else wait_counts<0, 0>();
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, af0, wf0);
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) load_global(kt + 1);
-        const unsigned char* sa = lds + (kt & 1) * STAGE_BYTES;
-        const unsigned char* sw = sa + BM * ROW_BYTES;
+    // one ring step: consumes stage kt, leaves the fragments of k-step 0 of stage kt+1 in (af0, wf0)
+    auto step = [&](int kt, auto refill) {
+        // phase A: fetch the fragments of k-step 1 of this stage while the MFMAs of k-step 0 run
+        load_frags(kt, 1, af1, wf1);
+        mfma_group(af0, wf0);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            half8 af[TM], wf[TN];
-            const int c = kk * 2 + fhalf;
-#pragma unroll
-            for (int t = 0; t < TM; ++t)
-                af[t] = *reinterpret_cast<const half8*>(sa + a_row[t] * ROW_BYTES + swz(a_row[t], c) * 16);
-#pragma unroll
-            for (int t = 0; t < TN; ++t)
-                wf[t] = *reinterpret_cast<const half8*>(sw + w_row[t] * ROW_BYTES + swz(w_row[t], c) * 16);
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], af[j], acc[i][j], 0, 0, 0);
+        for (int x = 0; x < NFRAG; ++x) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        if (more) store_lds((kt + 1) & 1);
-        __syncthreads();
-    }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // this wave's reads of stage kt are complete (lgkmcnt 0) and stage kt+1 has landed: in the
+        // steady state the NSTAGE-2 stages issued after it may still be in flight
+        if (decltype(refill)::value) wait_counts<(NSTAGE - 2) * LOADS, 1>();
+        else wait_counts<0, 1>();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        // phase B: refill the slot just freed, fetch k-step 0 of the next stage, run k-step 1 of this one
+        if (decltype(refill)::value) issue_loads(kt + NSTAGE);
+        load_frags(kt + 1, 0, af0, wf0);
+        mfma_group(af1, wf1);
+#pragma unroll
+        for (int x = 0; x < NFRAG; ++x) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt < KT - NSTAGE; ++kt) step(kt, std::true_type{});
+    for (; kt < KT - 1; ++kt) step(kt, std::false_type{});
+    load_frags(kt, 1, af1, wf1);
+    mfma_group(af0, wf0);
+    mfma_group(af1, wf1);
 
-    // ---- epilogue: accumulator register r of tile (i, j) holds
-    //      n = n0 + wn*WTN + i*32 + 8*(r/4) + 4*(lane/32) + r%4,   m = m0 + wm*WTM + j*32 + lane%32
+    // ---- epilogue: bias + float16 conversion in registers, then through LDS so that every global
+    //      store instruction writes whole 512-byte pieces of C rows (accumulator register r of tile
+    //      (i, j) holds n = 32*i + 8*(r/4) + 4*(lane/32) + r%4, m = 32*j + lane%32 of the wave tile).
+    //      Rows are padded by 16 bytes: the 8-byte writes of 32 consecutive rows then spread over all banks.
+    constexpr int CROW = BN * 2 + 16;
+    __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): this wave's operand reads are done
+    __builtin_amdgcn_s_barrier();                  // ... and everybody else's: the stages can be overwritten
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int n = n0 + wn * WTN + i * 32 + 8 * g + 4 * fhalf;
-            if (n >= N) continue;                    // N % 4 == 0 is required, so a quad is all in or all out
+            const int nl = wn * WTN + i * 32 + 8 * g + 4 * fhalf;
             float bv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (bias) {
-                const half4 b4 = *reinterpret_cast<const half4*>(bias + n);
+            if (bias && n0 + nl < N) {
+                const half4 b4 = *reinterpret_cast<const half4*>(bias + n0 + nl);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) bv[e] = (float)b4[e];
             }
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
-                const int64_t m = m0 + wm * WTM + j * 32 + frow;
-                if (m >= M) continue;
+                const int ml = wm * WTM + j * 32 + frow;
                 half4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (_Float16)(acc[i][j][g * 4 + e] + bv[e]);
-                *reinterpret_cast<half4*>(C + m * ldc + n) = o;
+                *reinterpret_cast<half4*>(lds + ml * CROW + nl * 2) = o;
             }
         }
     }
+    __syncthreads();
+    constexpr int CHUNKS_PER_ROW = BN / 8;         // 16-byte pieces
+    constexpr int NT = NW * 64;
+#pragma unroll 4
+    for (int q = tid; q < BM * CHUNKS_PER_ROW; q += NT) {
+        const int ml = q / CHUNKS_PER_ROW, cc = q % CHUNKS_PER_ROW;
+        const int64_t m = m0 + ml;
+        const int n = n0 + cc * 8;
+        if (m < M && n < N)
+            *reinterpret_cast<half8*>(C + m * ldc + n) = *reinterpret_cast<const half8*>(lds + ml * CROW + cc * 16);
+    }
 }
 
-template <int BM, int BN, int WM, int WN, int GROUP_M>
-int launch_variant(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
-                   hipStream_t st) {
-    auto kern = gemm_bias_f16<BM, BN, WM, WN, GROUP_M>;
-    constexpr int lds_bytes = 2 * (BM + BN) * ROW_BYTES;
-    static bool configured = false;   // per process; attribute is per function, device 0 only is used
+template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M>
+int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
+                hipStream_t st) {
+    auto kern = gemm_bias_f16<BM, BN, WM, WN, NSTAGE, GROUP_M>;
+    constexpr int stage_bytes = NSTAGE * (BM + BN) * ROW_BYTES, c_bytes = BM * (BN * 2 + 16);
+    constexpr int lds_bytes = stage_bytes > c_bytes ? stage_bytes : c_bytes;
+    static bool configured = false;   // per process and instantiation (one device is used)
     if (!configured) {
         KVPR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      lds_bytes));
@@ -198,11 +255,11 @@ int g_gemm_variant = 0;
 int launch_gemm(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
                 hipStream_t st) {
     if (M == 0) return KVPR_OK;
-    switch (g_gemm_variant) {
-        case 1: return launch_variant<256, 256, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
-        case 2: return launch_variant<128, 128, 2, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
-        case 3: return launch_variant<256, 128, 2, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
-        default: return launch_variant<256, 256, 2, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
+    switch (g_gemm_variant) {   // variants other than 0 exist for tests and tuning sweeps
+        case 1: return launch_tile<256, 256, 2, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
+        case 2: return launch_tile<256, 128, 2, 2, 3, 8>(a, w, bias, c, M, N, K, ldc, st);
+        case 3: return launch_tile<128, 128, 2, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
+        default: return launch_tile<256, 256, 4, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
     }
 }
 
