@@ -63,7 +63,8 @@ def main():
     ap.add_argument("--seq", type=int, default=1024)
     ap.add_argument("--split", type=int, default=-1, help="-1 = scheduler's l*")
     ap.add_argument("--cost-model", default="eq10", choices=["eq10", "ns", "row"])
-    ap.add_argument("--granularity", type=int, default=8)
+    ap.add_argument("--granularity", type=int, default=64,
+                    help="l is restricted to multiples of this: 64 positions x batch 32 = 8 GEMM tile rows = a whole number of 256-workgroup rounds at hidden 4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
     args = ap.parse_args()
