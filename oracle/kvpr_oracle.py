@@ -215,3 +215,34 @@ def layer_norm(x, g, beta, eps: float = 1e-5) -> np.ndarray:
 def ffn(o, W1, b1, W2, b2) -> np.ndarray:
     """Eq. 4 with sigma = ReLU (OPT) and biases."""
     return project(np.maximum(project(o, W1, b1), 0.0), W2, b2)
+
+
+def decoder_stack_decode(layers, x_in, splits, stored=None, kv_round: str = "fp16", act_round: str = "fp16"):
+    """One decode token through a stack of OPT-style decoder layers (Sec. 4 "Implementation":
+    row-by-row schedule, one batch, layer after layer).
+
+    Each entry of `layers` holds the attention parameters and X of kvpr_inputs.make_layer plus the
+    FFN / LayerNorm parameters of kvpr_inputs.make_ffn.  Per layer:
+        xn = LN1(x);  o = attention block at split l on (X, stored KV, x_new = xn);  x = x + o;
+        x = x + FFN(LN2(x))                                                      (Eq. 4, ReLU)
+    act_round="fp16" rounds every activation tensor the runtime keeps in float16 (xn, o, the
+    residual sums, the FFN hidden and output) at the point where it is stored; all arithmetic
+    in between is float64.  Returns the final hidden state and the per-layer (xn, new K|V row).
+    """
+    rnd = round_fp16 if act_round == "fp16" else _f64
+    x = _f64(x_in)
+    trace = []
+    for i, L in enumerate(layers):
+        xn = rnd(layer_norm(x, L["ln1_g"], L["ln1_b"]))
+        att = dict(L)
+        att["x_new"] = xn
+        kv_st = stored[i] if stored is not None else None
+        r = layer_decode(att, splits[i], kv_st, kv_round)
+        o = rnd(r["o"])
+        x = rnd(x + o)
+        xn2 = rnd(layer_norm(x, L["ln2_g"], L["ln2_b"]))
+        f1 = rnd(np.maximum(project(xn2, L["W1"], L["b1"]), 0.0))
+        f2 = rnd(project(f1, L["W2"], L["b2"]))
+        x = rnd(x + f2)
+        trace.append({"xn": xn, "kv_new": r["kv"][-1]})
+    return x, trace
