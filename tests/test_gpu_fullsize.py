@@ -1,0 +1,80 @@
+"""Parity at the bench's full size and launch configuration (OPT-6.7B-shaped layer, batch 32,
+context 1024): the oracle recomputes whole sequences one by one for a sample of the batch, and
+sampled rows of the recomputed cache."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import kvpr_inputs
+from oracle import kvpr_oracle as ko
+from kvpr_testlib import rel_err, rel_err_rms, upload_layer
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def k():
+    import paper_2411_17089_amd as k
+    return k
+
+
+@pytest.fixture(scope="module")
+def rig(k):
+    b, s, (h, H, d) = 32, 1024, kvpr_inputs.SHAPES["opt-6.7b"]
+    layer = kvpr_inputs.make_layer(0, b, s, h, H)
+    dv = upload_layer(layer)
+    w = k.make_weights(wqkv=dv["wqkv"], bqkv=dv["bqkv"], wo=dv["wo"], bo=dv["bo"])
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2)
+    k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
+    k.kvpr_store_prefill_kv(ctx, 0, s, w)                      # as bench.py does
+    out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+    yield dict(k=k, ctx=ctx, layer=layer, dv=dv, w=w, out=out, b=b, s=s, h=h, H=H)
+    k.kvpr_destroy(ctx)
+
+
+def _host_kv(rig):
+    _, kvp = rig["k"].kvpr_store_ptrs(rig["ctx"], 0)
+    n = (rig["s"] + 1) * rig["b"] * 2 * rig["h"]
+    return np.ctypeslib.as_array(ctypes.cast(kvp, ctypes.POINTER(ctypes.c_uint16)), (n,)).view(np.float16).reshape(
+        rig["s"] + 1, rig["b"], 2 * rig["h"])
+
+
+def test_prefilled_cache_rows_match_oracle(rig):
+    """Sampled rows of the cache the GPU GEMM produced at M = 32768 (every tile row range is hit)."""
+    L, kv = rig["layer"], _host_kv(rig)
+    rng = np.random.default_rng(0)
+    js = sorted(set(rng.integers(0, rig["s"], 24).tolist()) | {0, rig["s"] - 1})
+    for j in js:
+        ref = ko.round_fp16(ko.recompute_kv(L["X"][j:j + 1], L["Wk"], L["Wv"], L["bk"], L["bv"]))[0]
+        got = kv[j].astype(np.float64)
+        assert rel_err(got, ref) <= 1e-3, j
+        assert np.mean(got != ref) < 0.05, j
+
+
+@pytest.mark.parametrize("split", [832, 0, 256, 512, 768, 1024])
+def test_full_size_layer_decode_sampled_sequences(rig, split):
+    k, L = rig["k"], rig["layer"]
+    print(f"full-size layer decode split={split}", flush=True)
+    k.kvpr_layer_decode(rig["ctx"], 0, rig["s"], split, rig["w"], rig["dv"]["x_new"], rig["out"])
+    torch.cuda.synchronize()
+    got = rig["out"].cpu().numpy()
+    assert np.isfinite(got).all()
+    for n in (0, 13, 31):                                         # whole sequences, one by one
+        sub = dict(L)
+        sub["X"] = np.ascontiguousarray(L["X"][:, n:n + 1])
+        sub["x_new"] = L["x_new"][n:n + 1]
+        ref = ko.layer_decode(sub, 0)["o"]                         # oracle's own cache for that sequence
+        assert rel_err(got[n:n + 1], ref) <= 3e-3, (split, n)
+        assert rel_err_rms(got[n:n + 1], ref) <= 1e-2, (split, n)
+
+
+def test_full_size_split_invariance(rig):
+    k = rig["k"]
+    outs = []
+    for split in (0, 832, 1024):
+        k.kvpr_layer_decode(rig["ctx"], 0, rig["s"], split, rig["w"], rig["dv"]["x_new"], rig["out"])
+        torch.cuda.synchronize()
+        outs.append(rig["out"].cpu().numpy().copy())
+    assert rel_err(outs[1], outs[0]) <= 2e-3 and rel_err(outs[2], outs[0]) <= 2e-3
