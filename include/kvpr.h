@@ -57,6 +57,9 @@ extern "C" {
 #define KVPR_COST_EQ10 0
 #define KVPR_COST_NS   1
 #define KVPR_COST_ROW  2
+/* Extension (not in the paper): steady state of the layer pipeline, where the next layer's
+ * transfers overlap this layer's compute: max((M_X + M_KV)/v_com, t_recomp). */
+#define KVPR_COST_PIPE 3
 
 /* debug flags for kvpr_set_debug */
 #define KVPR_DEBUG_SYNC   1  /* synchronise every stream after every enqueue             */
@@ -175,6 +178,13 @@ int kvpr_timing_read(kvpr_ctx* ctx, int slot, kvpr_layer_timing* timing);
  * x_in_dev / x_out_dev [batch, hidden] hidden states; splits_in [n_layers] or null (= plan). */
 int kvpr_decode_step(kvpr_ctx* ctx, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
                      void* x_out_dev, const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_layer);
+
+/* Greedy sampling step of the row-by-row schedule: logits = hidden . W_lm^T in float32
+ * (logits_dev: scratch [batch, vocab] float32), tokens_dev[n] = argmax over the vocabulary (lowest
+ * index on ties), and, if emb_dev is non-null, x_next_dev[n] = emb_dev[tokens_dev[n]] (float16
+ * [vocab, hidden] table).  hidden_dev float16 [batch, hidden], w_lm_dev float16 [vocab, hidden]. */
+int kvpr_greedy_next(const void* hidden_dev, const void* w_lm_dev, const void* emb_dev, int batch, int hidden,
+                     int vocab, void* logits_dev, int32_t* tokens_dev, void* x_next_dev, void* stream);
 
 /* ---- individual kernels, exposed for parity tests and roofline measurement ---- */
 

@@ -246,3 +246,11 @@ def decoder_stack_decode(layers, x_in, splits, stored=None, kv_round: str = "fp1
         x = rnd(x + f2)
         trace.append({"xn": xn, "kv_new": r["kv"][-1]})
     return x, trace
+
+
+def greedy_next(hidden, W_lm, emb=None):
+    """Greedy sampling: logits = hidden . W_lm (W_lm [h, vocab]), token = first argmax,
+    next input = embedding row.  Returns (tokens, logits, x_next or None)."""
+    logits = project(hidden, W_lm)
+    tokens = np.argmax(logits, axis=-1)
+    return tokens, logits, (None if emb is None else _f64(emb)[tokens])

@@ -23,6 +23,9 @@ Three cost forms are provided:
              charged only to the compute arm, as if it travelled on a second
              link.  Not in the paper; kept because the benchmark spec
              paraphrases the cost this way.
+  COST_PIPE  max((M_X + M_KV)/v_com, t_recomp): steady state when the next layer's
+             transfers overlap this layer's compute (double buffering across layers,
+             Sec. 4 "Implementation").  An extension: the paper does not model it.
 
 Readings where the paper is silent: the integer problem is solved exactly by
 enumeration, scanning l upward and keeping the first strict minimum (ties go to
@@ -36,6 +39,7 @@ from __future__ import annotations
 COST_EQ10 = 0
 COST_NS = 1
 COST_ROW = 2
+COST_PIPE = 3
 
 
 def bytes_x(b: int, l: int, h: int, p: int) -> int:
@@ -70,6 +74,8 @@ def cost(model: int, l: int, b: int, s: int, h: int, p: int,
         return max(t_rc, t_kv)
     if model == COST_NS:
         return max(t_rc + t_act, t_kv)
+    if model == COST_PIPE:
+        return max(t_act + t_kv, t_rc)
     raise ValueError(f"unknown cost model {model}")
 
 

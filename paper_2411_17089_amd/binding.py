@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkvpr.so")
 
 KVPR_OK, KVPR_E_INVAL, KVPR_E_RANGE, KVPR_E_NOMEM, KVPR_E_HIP, KVPR_E_STATE = 0, -1, -2, -3, -4, -5
 KVPR_F16 = 1
-KVPR_COST_EQ10, KVPR_COST_NS, KVPR_COST_ROW = 0, 1, 2
+KVPR_COST_EQ10, KVPR_COST_NS, KVPR_COST_ROW, KVPR_COST_PIPE = 0, 1, 2, 3
 KVPR_DEBUG_SYNC, KVPR_DEBUG_POISON = 1, 2
 
 
@@ -75,6 +75,7 @@ _SIGS = {
     "kvpr_layer_decode_timed": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, _i]),
     "kvpr_timing_read": (_i, [_vp, _i, C.POINTER(kvpr_layer_timing)]),
     "kvpr_decode_step": (_i, [_vp, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(kvpr_layer_timing)]),
+    "kvpr_greedy_next": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "kvpr_recompute_gemm": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp]),
     "kvpr_decode_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "kvpr_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
@@ -202,6 +203,11 @@ def kvpr_decode_step(ctx, seq, layer_weights, x_in_dev, x_out_dev, splits=None, 
     tim = (kvpr_layer_timing * n)() if timing else None
     _check(lib.kvpr_decode_step(ctx, seq, arr, _ptr(x_in_dev), _ptr(x_out_dev), sin, sout, tim))
     return list(sout), (list(tim) if timing else None)
+
+
+def kvpr_greedy_next(hidden_dev, w_lm_dev, emb_dev, batch, hidden, vocab, logits_dev, tokens_dev, x_next_dev, stream=None):
+    _check(lib.kvpr_greedy_next(_ptr(hidden_dev), _ptr(w_lm_dev), _ptr(emb_dev), batch, hidden, vocab, _ptr(logits_dev),
+                                _ptr(tokens_dev), _ptr(x_next_dev), _stream(stream)))
 
 
 def kvpr_recompute_gemm(a_dev, w_dev, bias_dev, c_dev, M, N, K, ldc, stream=None):

@@ -498,6 +498,19 @@ extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* 
     return KVPR_OK;
 }
 
+extern "C" int kvpr_greedy_next(const void* hidden_dev, const void* w_lm_dev, const void* emb_dev, int batch, int hidden,
+                                int vocab, void* logits_dev, int32_t* tokens_dev, void* x_next_dev, void* stream) {
+    if (batch < 1 || batch > 64 || hidden < 1 || vocab < 1) return fail(KVPR_E_RANGE, "batch=%d (1..64) hidden=%d vocab=%d out of range", batch, hidden, vocab);
+    if (hidden % 128) return fail(KVPR_E_INVAL, "hidden must be a multiple of 128");
+    if (!hidden_dev || !w_lm_dev || !logits_dev || !tokens_dev) return fail(KVPR_E_INVAL, "null pointer");
+    if ((emb_dev == nullptr) != (x_next_dev == nullptr)) return fail(KVPR_E_INVAL, "emb_dev and x_next_dev go together");
+    hipStream_t st = (hipStream_t)stream;
+    if (int rc = kvpr::launch_token_gemm_flags(hidden_dev, w_lm_dev, nullptr, logits_dev, nullptr, batch, vocab, hidden, vocab, 0, 0, st)) return rc;
+    if (int rc = kvpr::launch_argmax_rows((const float*)logits_dev, batch, vocab, tokens_dev, st)) return rc;
+    if (emb_dev) return kvpr::launch_gather_rows(emb_dev, tokens_dev, x_next_dev, batch, hidden, st);
+    return KVPR_OK;
+}
+
 // ---- individual kernels ----
 extern "C" int kvpr_recompute_gemm(const void* a, const void* w, const void* bias, void* cdev, int64_t M, int N, int K,
                                    int64_t ldc, void* stream) {

@@ -1,5 +1,6 @@
 // Small memory-bound helpers around the attention block: LayerNorm, residual add, pattern fill.
 #include "kvpr_internal.h"
+#include <math.h>
 
 namespace kvpr {
 namespace {
@@ -55,7 +56,50 @@ __global__ void add_kernel(const _Float16* __restrict__ a, const _Float16* __res
     if (i < n) y[i] = (_Float16)((float)a[i] + (float)b[i]);
 }
 
+// greedy sampling: one workgroup per row, lowest index wins ties
+__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ logits, int N, int32_t* __restrict__ out) {
+    const float* row = logits + (int64_t)blockIdx.x * N;
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < N; i += 256) {
+        const float v = row[i];
+        if (v > best) { best = v; bi = i; }            // i ascends per thread: first maximum is kept
+    }
+    __shared__ float sv[256];
+    __shared__ int si[256];
+    sv[threadIdx.x] = best;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            const float v = sv[threadIdx.x + o];
+            const int j = si[threadIdx.x + o];
+            if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && j < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = j; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = si[0];
+}
+
+__global__ void gather_rows_kernel(const _Float16* __restrict__ table, const int32_t* __restrict__ idx,
+                                   _Float16* __restrict__ out, int h) {
+    const _Float16* src = table + (int64_t)idx[blockIdx.x] * h;
+    for (int i = threadIdx.x; i < h; i += blockDim.x) out[(int64_t)blockIdx.x * h + i] = src[i];
+}
+
 }  // namespace
+
+int launch_argmax_rows(const float* logits, int M, int N, int32_t* out, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(256), 0, st, logits, N, out);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+int launch_gather_rows(const void* table, const int32_t* idx, void* out, int M, int h, hipStream_t st) {
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(M), dim3(256), 0, st, (const _Float16*)table, idx, (_Float16*)out, h);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
 
 int launch_fill_u16(void* p, size_t n_halfs, uint16_t pattern, hipStream_t st) {
     if (n_halfs == 0) return KVPR_OK;

@@ -31,6 +31,8 @@ int launch_token_gemm_flags(const void* x, const void* w, const void* bias, void
 int launch_fill_u16(void* p, size_t n_halfs, uint16_t pattern, hipStream_t st);
 int launch_fill_random(void* p, size_t n_halfs, float scale, uint32_t seed, hipStream_t st);
 int launch_layernorm(const void* x, const void* g, const void* b, void* y, int rows, int h, hipStream_t st);
+int launch_argmax_rows(const float* logits, int M, int N, int32_t* out, hipStream_t st);
+int launch_gather_rows(const void* table, const int32_t* idx, void* out, int M, int h, hipStream_t st);
 int launch_add(const void* a, const void* b, void* y, size_t n, hipStream_t st);
 
 }  // namespace kvpr

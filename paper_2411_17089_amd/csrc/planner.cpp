@@ -15,7 +15,7 @@ bool lat_ok(double v) { return std::isfinite(v) && v >= 0.0; }
 
 int check(const kvpr_profile_t* p, int model, int batch, int seq, int hidden, int elem_bytes) {
     if (!p) return kvpr::fail(KVPR_E_INVAL, "profile is null");
-    if (model != KVPR_COST_EQ10 && model != KVPR_COST_NS && model != KVPR_COST_ROW)
+    if (model != KVPR_COST_EQ10 && model != KVPR_COST_NS && model != KVPR_COST_ROW && model != KVPR_COST_PIPE)
         return kvpr::fail(KVPR_E_INVAL, "unknown cost model %d", model);
     if (batch < 1 || seq < 0 || hidden < 1 || elem_bytes < 1)
         return kvpr::fail(KVPR_E_RANGE, "batch=%d seq=%d hidden=%d elem_bytes=%d out of range", batch, seq, hidden,
@@ -49,6 +49,10 @@ double cost_at(const kvpr_profile_t* p, int model, int64_t l, int64_t b, int64_t
         case KVPR_COST_NS: {
             const double arm = t_rc + t_act;
             return arm > t_kv ? arm : t_kv;
+        }
+        case KVPR_COST_PIPE: {
+            const double link = t_act + t_kv;
+            return link > t_rc ? link : t_rc;
         }
         default: return t_act + (t_rc > t_kv ? t_rc : t_kv);
     }

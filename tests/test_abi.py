@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol(k):
         assert hasattr(k.lib, name), name
 
 
-MODELS = [(po.COST_EQ10, "KVPR_COST_EQ10"), (po.COST_NS, "KVPR_COST_NS"), (po.COST_ROW, "KVPR_COST_ROW")]
+MODELS = [(po.COST_EQ10, "KVPR_COST_EQ10"), (po.COST_NS, "KVPR_COST_NS"), (po.COST_ROW, "KVPR_COST_ROW"),
+          (po.COST_PIPE, "KVPR_COST_PIPE")]
 
 
 @pytest.mark.parametrize("model,cname", MODELS)

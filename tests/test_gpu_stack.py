@@ -127,3 +127,35 @@ def test_decode_step_needs_ffn(k):
         assert e.value.code == k.KVPR_E_STATE
     finally:
         k.kvpr_destroy(ctx)
+
+
+def test_greedy_next_matches_oracle(k):
+    b, h, vocab = 5, 256, 1000 + 7
+    rng = np.random.default_rng(21)
+    hidden = rng.standard_normal((b, h)).astype(np.float16)
+    W_lm = (rng.standard_normal((h, vocab)) * 0.05).astype(np.float16)
+    emb = rng.standard_normal((vocab, h)).astype(np.float16)
+    logits = torch.empty((b, vocab), dtype=torch.float32, device="cuda")
+    tokens = torch.empty((b,), dtype=torch.int32, device="cuda")
+    x_next = torch.empty((b, h), dtype=torch.float16, device="cuda")
+    k.kvpr_greedy_next(dev(hidden), dev(W_lm.T), dev(emb), b, h, vocab, logits, tokens, x_next)
+    torch.cuda.synchronize()
+    want_tok, want_logits, want_x = ko.greedy_next(hidden, W_lm, emb)
+    got_logits = logits.cpu().numpy()
+    assert rel_err(got_logits, want_logits) <= 1e-5
+    got_tok = tokens.cpu().numpy()
+    for n in range(b):
+        # the argmax is unique unless the top two float64 logits are closer than the float32 error
+        top2 = np.sort(want_logits[n])[-2:]
+        if top2[1] - top2[0] > 1e-4 * abs(top2[1]):
+            assert got_tok[n] == want_tok[n], n
+        assert got_logits[n, got_tok[n]] == got_logits[n].max()
+        assert np.array_equal(x_next.cpu().numpy()[n], emb[got_tok[n]])
+    # ties go to the lowest index
+    flat = torch.zeros((2, 128), dtype=torch.float16, device="cuda")
+    wz = torch.zeros((300, 128), dtype=torch.float16, device="cuda")
+    lg = torch.empty((2, 300), dtype=torch.float32, device="cuda")
+    tk = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    k.kvpr_greedy_next(flat, wz, None, 2, 128, 300, lg, tk, None)
+    torch.cuda.synchronize()
+    assert tk.cpu().tolist() == [0, 0]

@@ -54,6 +54,16 @@ def test_toy_cost_curves():
     assert po.plan_split(po.COST_ROW, **k) == (6, 6.0)
 
 
+def test_pipelined_extension_toy():
+    # link = l + 2(9-l) = 18 - l, recompute = l: max crosses at l = 9
+    k = _toy()
+    assert [po.cost(po.COST_PIPE, l, **k) for l in range(10)] == [18, 17, 16, 15, 14, 13, 12, 11, 10, 9]
+    assert po.plan_split(po.COST_PIPE, **k) == (9, 9.0)
+    k["v_gpu"] = 1.0                                   # recompute 4 s per position: 18 - l meets 4l at l = 3.6
+    assert [po.cost(po.COST_PIPE, l, **k) for l in (3, 4)] == [15, 16]
+    assert po.plan_split(po.COST_PIPE, **k) == (3, 15.0)
+
+
 def test_limits():
     kw = dict(b=32, s=1024, h=4096, p=2, v_com=50e9)
     assert po.plan_split(po.COST_EQ10, v_gpu=1e30, **kw)[0] == 1024     # free compute: recompute everything
