@@ -129,6 +129,53 @@ def run_stack(args):
     print(json.dumps(result))
 
 
+def run_kernels(args):
+    """Standalone launches of the path's kernels at the bench shape, for rocprofv3 counter runs:
+    a plain device copy of known size (reference for scaling FETCH_SIZE / WRITE_SIZE), the recompute
+    GEMM at M = split*batch, decode attention over seq+1 positions, and the two token GEMMs."""
+    import torch
+    import kvpr_inputs
+    import paper_2411_17089_amd as k
+    h, H, d = kvpr_inputs.SHAPES[args.model]
+    b, s = args.batch, args.seq
+    split = args.split if args.split >= 0 else 832
+    torch.manual_seed(0)
+    M = split * b
+    A = torch.randn((M, h), device="cuda", dtype=torch.float16)
+    W = (torch.randn((3 * h, h), device="cuda") * 0.02).half()
+    bias = (torch.randn((3 * h,), device="cuda") * 0.01).half()
+    kv = torch.empty((s + 1, b, 2 * h), device="cuda", dtype=torch.float16)
+    kv.normal_()
+    q = torch.randn((b, h), device="cuda", dtype=torch.float32)
+    z = torch.empty((b, h), device="cuda", dtype=torch.float16)
+    x = torch.randn((b, h), device="cuda", dtype=torch.float16)
+    y16 = torch.empty((b, 2 * h), device="cuda", dtype=torch.float16)
+    ws = torch.empty(k.kvpr_attention_workspace_bytes(b, h, H, s + 1), dtype=torch.uint8, device="cuda")
+    src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    src.fill_(1)
+    dst = torch.empty_like(src)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+    def timed(name, fn):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(args.steps):
+            e0, e1 = ev(), ev()
+            e0.record(); fn(); e1.record(); e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        out[name] = median(ts)
+    timed("copy_512MiB_ms", lambda: dst.copy_(src))
+    timed("recompute_gemm_ms", lambda: k.kvpr_recompute_gemm(A, W[h:], bias[h:], kv, M, 2 * h, h, 2 * h))
+    timed("attention_ms", lambda: k.kvpr_decode_attention(q, kv, z, ws, s + 1, b, h, H))
+    timed("token_gemm_qkv_ms", lambda: k.kvpr_token_gemm(x, W, bias, q, y16, b, 3 * h, h, h, 2 * h))
+    timed("token_gemm_out_ms", lambda: k.kvpr_token_gemm(x, W, bias, None, y16, b, h, h, 0, h))
+    out["recompute_gemm_TFLOPs"] = 4.0 * M * h * h / out["recompute_gemm_ms"] / 1e9
+    out["attention_GBps"] = 2.0 * b * (s + 1) * h * 2 / out["attention_ms"] / 1e6
+    out["shape"] = {"model": args.model, "batch": b, "seq": s, "split": split, "M": M, "N": 2 * h, "K": h}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +187,7 @@ def main():
     ap.add_argument("--split", type=int, default=-1, help="-1 = scheduler's l*")
     ap.add_argument("--cost-model", default="eq10", choices=["eq10", "ns", "row", "pipe"])
     ap.add_argument("--stack", action="store_true", help="layer-pipelined decode of a whole stack instead of one layer")
+    ap.add_argument("--kernels", action="store_true", help="launch each kernel of the path standalone (for rocprofv3 --pmc runs)")
     ap.add_argument("--layers", type=int, default=40)
     ap.add_argument("--gen", type=int, default=32)
     ap.add_argument("--no-greedy", action="store_true", help="(stack mode, diagnostics) skip the LM head / argmax / embedding step")
@@ -161,6 +209,8 @@ def main():
         sys.exit(1)
     if args.stack:
         return run_stack(args)
+    if args.kernels:
+        return run_kernels(args)
     h, H, d = kvpr_inputs.SHAPES[args.model]
     b, s = args.batch, args.seq
     cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
@@ -204,10 +254,16 @@ def main():
     attn_gbps = attn_bytes / (ms_attn * 1e-3) / 1e9
     h2d_gbps = h2d_bytes / ((ms_act + ms_kv) * 1e-3) / 1e9
 
-    traffic = None
+    # HBM-side bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a
+    # known-size copy); only valid for the shape and split they were taken at
+    traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"recompute_gemm/{args.model}/b{b}/s{s}")
+        traffic_detail = json.load(open(tpath)).get(f"recompute_gemm/{args.model}/b{b}/s{s}")
+        if traffic_detail and traffic_detail.get("split") == split:
+            traffic = traffic_detail["total_bytes"]
+        else:
+            traffic_detail = None
 
     result = {
         "metric": "decode_layer_tokens_per_s_at_optimal_split",
@@ -231,7 +287,7 @@ def main():
                     "attn_GBps": prof.attn_bytes_per_s / 1e9},
         "roofline": {"kernel": "gemm_bias_f16 (recompute GEMM)", "bound": "mfma", "achieved": gemm_tflops,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
-                     "traffic": traffic, "flops_per_launch": gemm_flops, "avg_ms": ms_gemm},
+                     "traffic": traffic, "traffic_detail": traffic_detail, "flops_per_launch": gemm_flops, "avg_ms": ms_gemm},
         "roofline_attention": {"kernel": "attention_partial (+combine)", "bound": "hbm", "achieved": attn_gbps,
                                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": attn_gbps / PEAK_HBM_GBPS,
                                "bytes_per_launch": attn_bytes, "avg_ms": ms_attn},
