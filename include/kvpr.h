@@ -155,6 +155,18 @@ int kvpr_plan_split(const kvpr_profile_t* prof, int cost_model, int batch, int s
 int kvpr_cost(const kvpr_profile_t* prof, int cost_model, int split, int batch, int seq, int hidden,
               int elem_bytes, double* t_pred);
 
+/* Extension (not in the paper): the activation copy X[0:l] is cut into `chunks` equal parts
+ * (1..32; 1 = the paper's schedule) and the recomputation of part j starts as soon as part j has
+ * landed, while the later parts and then the cache are still on the link.  Results are unchanged.
+ * kvpr_cost_chunked / kvpr_plan_split_chunked are Eq. 10 / Eq. 11 for that schedule: with
+ * t_act, t_kv, t_rc as in Eq. 10, part j's GEMM starts at max(j*t_act/chunks, end of part j-1)
+ * and takes t_rc/chunks; t = max(end of the last GEMM, t_act + t_kv).  chunks = 1 gives Eq. 10. */
+int kvpr_set_chunks(kvpr_ctx* ctx, int chunks);
+int kvpr_cost_chunked(const kvpr_profile_t* prof, int chunks, int split, int batch, int seq, int hidden,
+                      int elem_bytes, double* t_pred);
+int kvpr_plan_split_chunked(const kvpr_profile_t* prof, int chunks, int batch, int seq, int hidden,
+                            int elem_bytes, int granularity, int32_t* l_star, double* t_pred);
+
 /* One decode step of one attention layer (Sec. 3.2 row-by-row pipeline with partial
  * recomputation; Eq. 1, 2, 3, 5, 7).  `seq` = cached positions s already in the host
  * store; split in [0, seq], or -1 to use the plan from kvpr_set_profile.

@@ -98,3 +98,36 @@ def plan_split(model: int, b: int, s: int, h: int, p: int, v_com: float, v_gpu: 
         if t < best_t:
             best_l, best_t = l, t
     return best_l, best_t
+
+
+# --------------------------------------------------------------------------
+# Extension (not in the paper): chunked activation copy.  X[0:l] travels as
+# `chunks` equal parts; the GEMM of part j starts when part j has landed and
+# part j-1 has been recomputed; the cache follows X on the same link.
+# chunks = 1 is Eq. 10.
+# --------------------------------------------------------------------------
+def cost_chunked(chunks: int, l: int, b: int, s: int, h: int, p: int, v_com: float, v_gpu: float,
+                 lat_com: float = 0.0, lat_gpu: float = 0.0) -> float:
+    t_act = float(bytes_x(b, l, h, p)) / v_com
+    t_kv = float(bytes_kv(b, l, s, h, p)) / v_com
+    t_rc = float(flops_recompute(b, l, h)) / v_gpu
+    if l < s:
+        t_kv = t_kv + lat_com
+    done = 0.0
+    if l > 0:
+        for j in range(1, chunks + 1):
+            landed = t_act * float(j) / float(chunks) + lat_com
+            start = landed if landed > done else done
+            done = start + (t_rc / float(chunks) + lat_gpu)
+    link = ((t_act + lat_com) if l > 0 else 0.0) + t_kv
+    return done if done > link else link
+
+
+def plan_split_chunked(chunks: int, b: int, s: int, h: int, p: int, v_com: float, v_gpu: float,
+                       granularity: int = 1, lat_com: float = 0.0, lat_gpu: float = 0.0):
+    best_l, best_t = -1, float("inf")
+    for l in candidates(s, granularity):
+        t = cost_chunked(chunks, l, b, s, h, p, v_com, v_gpu, lat_com, lat_gpu)
+        if t < best_t:
+            best_l, best_t = l, t
+    return best_l, best_t

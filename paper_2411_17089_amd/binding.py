@@ -71,6 +71,9 @@ _SIGS = {
     "kvpr_profile": (_i, [_vp, _i, _i, C.POINTER(kvpr_profile_t)]),
     "kvpr_plan_split": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "kvpr_cost": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_double)]),
+    "kvpr_set_chunks": (_i, [_vp, _i]),
+    "kvpr_cost_chunked": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_double)]),
+    "kvpr_plan_split_chunked": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "kvpr_layer_decode": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(kvpr_layer_timing)]),
     "kvpr_layer_decode_timed": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, _i]),
     "kvpr_timing_read": (_i, [_vp, _i, C.POINTER(kvpr_layer_timing)]),
@@ -168,6 +171,22 @@ def kvpr_cost(prof, cost_model, split, batch, seq, hidden, elem_bytes=2):
     t = C.c_double()
     _check(lib.kvpr_cost(C.byref(prof), cost_model, split, batch, seq, hidden, elem_bytes, C.byref(t)))
     return t.value
+
+
+def kvpr_set_chunks(ctx, chunks):
+    _check(lib.kvpr_set_chunks(ctx, chunks))
+
+
+def kvpr_cost_chunked(prof, chunks, split, batch, seq, hidden, elem_bytes=2):
+    t = C.c_double()
+    _check(lib.kvpr_cost_chunked(C.byref(prof), chunks, split, batch, seq, hidden, elem_bytes, C.byref(t)))
+    return t.value
+
+
+def kvpr_plan_split_chunked(prof, chunks, batch, seq, hidden, elem_bytes=2, granularity=1):
+    l, t = C.c_int32(), C.c_double()
+    _check(lib.kvpr_plan_split_chunked(C.byref(prof), chunks, batch, seq, hidden, elem_bytes, granularity, C.byref(l), C.byref(t)))
+    return l.value, t.value
 
 
 def make_weights(**tensors) -> kvpr_layer_weights:

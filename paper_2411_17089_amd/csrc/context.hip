@@ -54,6 +54,9 @@ struct kvpr_ctx {
     half *hid = nullptr, *xn = nullptr, *attn_out = nullptr, *ffn1 = nullptr, *ffn2 = nullptr;
     // fences (timing disabled)
     hipEvent_t ev_x[2]{}, ev_kv[2]{}, ev_free[2]{}, ev_proj = nullptr, ev_store = nullptr, ev_begin = nullptr;
+    static constexpr int kMaxChunks = 32;
+    hipEvent_t ev_chunk[2][kMaxChunks]{};   // per device buffer: "activation chunk j has landed"
+    int chunks = 1;                          // 1 = the paper's schedule: all of X[0:l], then one GEMM
     bool free_recorded[2] = {false, false};
     std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
     kvpr_profile_t prof{};
@@ -97,6 +100,8 @@ int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn)
 int resolve_split(kvpr_ctx* c, int seq, int split, int32_t* out) {
     if (split == -1) {
         if (!c->have_prof) return fail(KVPR_E_STATE, "split = -1 needs kvpr_set_profile first");
+        if (c->chunks > 1 && c->cost_model == KVPR_COST_EQ10)
+            return kvpr_plan_split_chunked(&c->prof, c->chunks, c->d.batch, seq, c->d.hidden, 2, c->granularity, out, nullptr);
         return kvpr_plan_split(&c->prof, c->cost_model, c->d.batch, seq, c->d.hidden, 2, c->granularity, out, nullptr);
     }
     if (split < 0 || split > seq) return fail(KVPR_E_RANGE, "split %d outside [0, %d]", split, seq);
@@ -129,8 +134,17 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     // ---- copy stream: activations first, then the rest of the cache (the order Eq. 10 assumes) ----
     if (c->free_recorded[buf]) KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_free[buf], 0));
     if (ev) KVPR_HIP(hipEventRecord(ev->c0, c->copy));
-    if (l > 0)
-        KVPR_HIP(hipMemcpyAsync(dx, c->hx[layer], (size_t)l * xr * sizeof(half), hipMemcpyHostToDevice, c->copy));
+    // chunk boundaries: equal parts of [0, l) rounded down to multiples of 8 positions (whole GEMM tile rows
+    // at batch 32); a single chunk is the paper's schedule
+    int nchunk = (l > 0) ? std::min(c->chunks, std::max(1, l / 8)) : 0;
+    int bound[kvpr_ctx::kMaxChunks + 1];
+    for (int j = 0; j <= nchunk; ++j) bound[j] = (j == nchunk) ? l : (int)((int64_t)l * j / nchunk) / 8 * 8;
+    for (int j = 0; j < nchunk; ++j) {
+        if (bound[j + 1] > bound[j])
+            KVPR_HIP(hipMemcpyAsync(dx + (size_t)bound[j] * xr, c->hx[layer] + (size_t)bound[j] * xr,
+                                    (size_t)(bound[j + 1] - bound[j]) * xr * sizeof(half), hipMemcpyHostToDevice, c->copy));
+        if (nchunk > 1) KVPR_HIP(hipEventRecord(c->ev_chunk[buf][j], c->copy));
+    }
     KVPR_HIP(hipEventRecord(c->ev_x[buf], c->copy));
     if (ev) KVPR_HIP(hipEventRecord(ev->c_x, c->copy));
     if (l < seq)
@@ -160,13 +174,19 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     if (int rc = debug_sync(c)) return rc;
 
     // ---- recompute rows [0, l) as soon as their activations have landed (Eq. 7) ----
-    KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_x[buf], 0));
+    if (nchunk <= 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_x[buf], 0));
     if (ev) KVPR_HIP(hipEventRecord(ev->r0, c->compute));
     if (l > 0) {
         const half* wkv = (const half*)w->wqkv + (size_t)h * h;
         const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
-        if (int rc = kvpr::launch_gemm(dx, wkv, bkv, dkv, (int64_t)l * b, 2 * h, h, 2 * (int64_t)h, c->compute))
-            return rc;
+        for (int j = 0; j < nchunk; ++j) {
+            // with several chunks the GEMM of chunk j runs while chunks j+1.. and the cache are still on the link
+            if (nchunk > 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_chunk[buf][j], 0));
+            const int64_t rows = (int64_t)(bound[j + 1] - bound[j]) * b;
+            if (int rc = kvpr::launch_gemm(dx + (size_t)bound[j] * xr, wkv, bkv, dkv + (size_t)bound[j] * kr, rows, 2 * h, h,
+                                           2 * (int64_t)h, c->compute))
+                return rc;
+        }
     }
     if (ev) KVPR_HIP(hipEventRecord(ev->r1, c->compute));
     if (int rc = debug_sync(c)) return rc;
@@ -213,7 +233,11 @@ int read_timing(kvpr_ctx* c, LayerEvents* ev, int seq, int l, kvpr_layer_timing*
     r.ms_assemble = std::max(to_gemm, to_kv);
     r.split = l;
     if (c->have_prof) {
-        if (int rc = kvpr_cost(&c->prof, c->cost_model, l, c->d.batch, seq, c->d.hidden, 2, &r.t_bound_s)) return rc;
+        if (c->chunks > 1 && c->cost_model == KVPR_COST_EQ10) {
+            if (int rc = kvpr_cost_chunked(&c->prof, c->chunks, l, c->d.batch, seq, c->d.hidden, 2, &r.t_bound_s)) return rc;
+        } else if (int rc = kvpr_cost(&c->prof, c->cost_model, l, c->d.batch, seq, c->d.hidden, 2, &r.t_bound_s)) {
+            return rc;
+        }
     }
     *t = r;
     return KVPR_OK;
@@ -250,6 +274,7 @@ void destroy_impl(kvpr_ctx* c) {
         if (c->ev_x[i]) (void)hipEventDestroy(c->ev_x[i]);
         if (c->ev_kv[i]) (void)hipEventDestroy(c->ev_kv[i]);
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
+        for (hipEvent_t e : c->ev_chunk[i]) if (e) (void)hipEventDestroy(e);
     }
     void* dev[] = {c->q32, c->z16, c->attn_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2};
     for (void* p : dev) if (p) (void)hipFree(p);
@@ -311,6 +336,8 @@ extern "C" int kvpr_create(const kvpr_model_desc* d, void* compute_stream, kvpr_
         if ((e = hipEventCreateWithFlags(&c->ev_x[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
         if ((e = hipEventCreateWithFlags(&c->ev_kv[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
         if ((e = hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+        for (int j = 0; j < kvpr_ctx::kMaxChunks; ++j)
+            if ((e = hipEventCreateWithFlags(&c->ev_chunk[i][j], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
     }
     if ((e = hipEventCreateWithFlags(&c->ev_proj, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
     if ((e = hipEventCreateWithFlags(&c->ev_store, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
@@ -341,6 +368,13 @@ extern "C" int kvpr_set_debug(kvpr_ctx* c, int flags) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
     if (flags & ~(KVPR_DEBUG_SYNC | KVPR_DEBUG_POISON)) return fail(KVPR_E_INVAL, "unknown debug flags 0x%x", flags);
     c->debug = flags;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_set_chunks(kvpr_ctx* c, int chunks) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (chunks < 1 || chunks > kvpr_ctx::kMaxChunks) return fail(KVPR_E_RANGE, "chunks %d outside [1, %d]", chunks, kvpr_ctx::kMaxChunks);
+    c->chunks = chunks;
     return KVPR_OK;
 }
 

@@ -60,6 +60,24 @@ def test_planner_ties_and_latency_terms(k):
             assert k.kvpr_cost(prof, 0, l, 32, s, 4096, 2) == po.cost(0, l, 32, s, 4096, 2, 57e9, 1.2e15, 1e-3, 5e-4)
 
 
+def test_chunked_planner_bit_exact_against_oracle(k):
+    for b, s, h, v_com, v_gpu in [(32, 1024, 4096, 57.3e9, 1.05e15), (1, 128, 768, 20e9, 3e13), (16, 4096, 7168, 55e9, 9e14),
+                                  (4, 37, 256, 1e9, 5e11)]:
+        for lat in ((0.0, 0.0), (2e-5, 1e-5)):
+            prof = k.make_profile(v_com, v_gpu, *lat)
+            for chunks in (1, 2, 5, 8, 32):
+                for g in (1, 8):
+                    want = po.plan_split_chunked(chunks, b, s, h, 2, v_com, v_gpu, g, *lat)
+                    assert k.kvpr_plan_split_chunked(prof, chunks, b, s, h, 2, g) == want
+                for l in {0, 1, s // 2, s}:
+                    assert k.kvpr_cost_chunked(prof, chunks, l, b, s, h, 2) == po.cost_chunked(chunks, l, b, s, h, 2, v_com, v_gpu, *lat)
+            for l in {0, s // 3, s}:
+                assert k.kvpr_cost_chunked(prof, 1, l, b, s, h, 2) == k.kvpr_cost(prof, k.KVPR_COST_EQ10, l, b, s, h, 2)
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_plan_split_chunked(k.make_profile(1e9, 1e12), 0, 1, 8, 64, 2, 1)
+    assert e.value.code == k.KVPR_E_RANGE
+
+
 def test_planner_rejects_bad_arguments(k):
     good = k.make_profile(1e9, 1e12)
     for prof in (k.make_profile(0.0, 1e12), k.make_profile(1e9, -1.0), k.make_profile(float("nan"), 1e12),

@@ -193,3 +193,34 @@ def test_prefill_helper_matches_oracle_cache(k):
         assert np.mean(kv_host[:50].astype(np.float64) != rig.stored) < 0.05
     finally:
         rig.close()
+
+
+def test_chunked_activation_copy_gives_identical_results(k):
+    """Extension: X[0:l] copied in parts with the GEMM of each part started as it lands.  Row results of
+    the GEMM do not depend on how rows are grouped into launches, so outputs must be bit-identical."""
+    rig = Rig(k, 12, 32, 200, 512, 4)
+    try:
+        for l in (0, 5, 64, 133, 200):
+            base, _ = rig.decode(l)
+            for chunks in (2, 3, 8, 32):
+                k.kvpr_set_chunks(rig.ctx, chunks)
+                k.kvpr_set_debug(rig.ctx, k.KVPR_DEBUG_POISON)
+                o, t = rig.decode(l, timing=True)
+                assert np.array_equal(o, base), (l, chunks)
+                assert t.split == l
+                k.kvpr_set_debug(rig.ctx, 0)
+                k.kvpr_set_chunks(rig.ctx, 1)
+        ref = ko.layer_decode(rig.layer, 0, rig.stored)["o"]
+        assert rel_err(base, ref) <= TIGHT
+        with pytest.raises(k.KvprError):
+            k.kvpr_set_chunks(rig.ctx, 33)
+        # planned split follows the chunked model when chunks > 1
+        prof = k.make_profile(50e9, 4e14)
+        k.kvpr_set_profile(rig.ctx, prof, k.KVPR_COST_EQ10, 8)
+        k.kvpr_set_chunks(rig.ctx, 4)
+        o, t = rig.decode(-1, timing=True)
+        want_l, want_t = k.kvpr_plan_split_chunked(prof, 4, 32, 200, 512, 2, 8)
+        assert t.split == want_l and t.t_bound_s == k.kvpr_cost_chunked(prof, 4, want_l, 32, 200, 512, 2)
+        assert rel_err(o, ref) <= TIGHT
+    finally:
+        rig.close()

@@ -125,3 +125,24 @@ def test_granularity_and_latency_terms():
     assert ts == (po.bytes_x(32, 1000, 4096, 2) / 57e9 + 1e-3) + (po.flops_recompute(32, 1000, 4096) / 1.2e15 + 5e-4)
     with pytest.raises(ValueError):
         po.candidates(5, 0)
+
+
+# ---- extension: chunked activation copy -------------------------------------------
+def test_chunked_cost_reduces_to_eq10_and_hand_values():
+    k = _toy()                                          # t_act = l, t_kv = 2(9-l), t_rc = l
+    for l in range(10):
+        assert po.cost_chunked(1, l, **k) == po.cost(po.COST_EQ10, l, **k)
+    # l = 8, 4 parts: parts land at 2,4,6,8; each GEMM takes 2 -> ends 4,6,8,10; link = 8 + 2 = 10
+    assert po.cost_chunked(4, 8, **k) == 10.0
+    # l = 9, 3 parts: land 3,6,9; GEMM 3 each -> 6,9,12; link 9 -> 12
+    assert po.cost_chunked(3, 9, **k) == 12.0
+    # GEMM faster than the link (v_gpu x4): l = 8, 4 parts: GEMM 0.5 each -> last ends 8.5; link 10
+    k2 = dict(k, v_gpu=16.0)
+    assert po.cost_chunked(4, 8, **k2) == 10.0
+    assert po.cost_chunked(4, 9, **k2) == 9.0 + 9.0 / 4 / 4
+    # more parts never hurt, and the limit is the link time plus nothing
+    real = dict(b=32, s=1024, h=4096, p=2, v_com=57e9, v_gpu=1.0e15)
+    ts = [po.plan_split_chunked(c, **real)[1] for c in (1, 2, 4, 8, 16, 32)]
+    assert all(a >= b for a, b in zip(ts, ts[1:]))
+    assert ts[0] == po.plan_split(po.COST_EQ10, **real)[1]
+    assert ts[-1] >= po.bytes_x(32, 1024, 4096, 2) / 57e9
