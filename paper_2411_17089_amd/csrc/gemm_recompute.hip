@@ -222,7 +222,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
         const int64_t m = m0 + ml;
         const int n = n0 + cc * 8;
         if (m < M && n < N)
-            *reinterpret_cast<half8*>(C + m * ldc + n) = *reinterpret_cast<const half8*>(lds + ml * CROW + cc * 16);
+            __builtin_nontemporal_store(*reinterpret_cast<const half8*>(lds + ml * CROW + cc * 16),
+                                        reinterpret_cast<half8*>(C + m * ldc + n));   // C is not re-read here: keep it out of L2
     }
 }
 
