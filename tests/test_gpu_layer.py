@@ -224,3 +224,32 @@ def test_chunked_activation_copy_gives_identical_results(k):
         assert rel_err(o, ref) <= TIGHT
     finally:
         rig.close()
+
+
+def test_batch_64_and_head_dim_64(k):
+    """Largest supported batch (four 16-row MFMA tiles in the token GEMM) with 64-wide heads."""
+    rig = Rig(k, 13, 64, 24, 256, 4)
+    try:
+        ref = ko.layer_decode(rig.layer, 0, rig.stored)["o"]
+        for l in (0, 11, 24):
+            o, _ = rig.decode(l)
+            assert rel_err(o, ref) <= TIGHT, l
+    finally:
+        rig.close()
+
+
+def test_profile_reports_sane_rates(k):
+    ctx = k.kvpr_create(1, 1024, 8, 128, 0, 8, 300)
+    try:
+        p = k.kvpr_profile(ctx, 8, 256)
+        assert 1e9 < p.h2d_bytes_per_s < 1e11 and 1e9 < p.d2h_bytes_per_s < 1e11
+        assert p.h2d_peak_bytes_per_s >= p.h2d_bytes_per_s * 0.999
+        assert 1e12 < p.gemm_flops_per_s < 2.6e15
+        assert 1e10 < p.attn_bytes_per_s < 8.5e12
+        assert p.h2d_latency_s == 0.0 and p.gemm_latency_s == 0.0
+        k.kvpr_set_profile(ctx, p, k.KVPR_COST_EQ10, 1)
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_profile(ctx, 8, 300)                      # batch*seq beyond the context
+        assert e.value.code == k.KVPR_E_RANGE
+    finally:
+        k.kvpr_destroy(ctx)
