@@ -2,17 +2,21 @@
 // q/k/v projection of Eq. 1 / Eq. 5, the output projection of Eq. 3, the FFN of Eq. 4).
 //
 // With so few rows the operation reads every weight once and is bound by HBM, so the kernel is a
-// weight streamer:
-//   - a workgroup owns 16 output features (16 rows of W) and all M rows of x; its waves split K in
-//     interleaved slabs of 128 columns, so the workgroup as a whole walks contiguous memory;
-//   - lanes read W straight from global memory into v_mfma_f32_16x16x32_f16 operand registers with
-//     non-temporal 16-byte loads (each weight is used once); in the instruction's own operand layout
-//     (lane = row r, k-chunk c) one load instruction covers 16 rows x one whole 64-byte segment, so
-//     every fetched segment is fully used (a lane-contiguous k permutation was 4x worse: each
-//     instruction then touched 64 segments for 16 bytes each);
-//   - x is tiny (M*K halfs) and comes from L2;
-//   - UNROLL slabs are loaded before their MFMAs are issued, so 4*UNROLL independent 1 KiB loads are
-//     in flight per wave; the per-wave partial 16 x 16 tiles are summed through LDS;
+// weight streamer built around v_mfma_f32_16x16x32_f16 (W rows feed the row operand, x rows the
+// column operand):
+//   - a workgroup owns TPW tiles of 16 output features and all M rows of x; TPW is chosen so that the
+//     grid is about one workgroup per CU.  Its 8 waves split K in interleaved slabs of 128 columns,
+//     so the workgroup as a whole walks contiguous memory;
+//   - lanes read W straight from global memory into MFMA operand registers with non-temporal
+//     16-byte loads (each weight is used once).  In the instruction's own operand layout (lane = row
+//     r, k-chunk c) one load instruction covers 16 rows x one whole 64-byte segment, so every fetched
+//     segment is fully used (a lane-contiguous k permutation was 4x worse: each instruction then
+//     touched 64 segments for 16 bytes each);
+//   - x is tiny (M*K halfs) and comes from L2; one x fragment is reused for the TPW weight tiles, so
+//     the L2->CU traffic for x stays below the HBM traffic for W (with one tile per workgroup it was
+//     twice the weight bytes and capped the kernel at 2.2 TB/s);
+//   - all 4*TPW weight loads of a slab are issued before its MFMAs; per-wave partial tiles are summed
+//     through LDS;
 //   - the epilogue adds the bias, optionally applies ReLU and writes float32 for the first
 //     `out_f32_cols` features (q) and float16 for the rest (k|v row of the cache, o, FFN).
 #include "kvpr_internal.h"
@@ -24,66 +28,70 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int SLAB = 128;   // K columns per wave step: 4 MFMA k-steps of 32
+constexpr int TG_WAVES = 8;
 
-template <int WAVES, int MT, int UNROLL>
-__global__ __launch_bounds__(WAVES * 64) void token_gemm(const _Float16* __restrict__ x,
-                                                         const _Float16* __restrict__ W,
-                                                         const _Float16* __restrict__ bias, float* __restrict__ y32,
-                                                         _Float16* __restrict__ y16, int M, int N, int K,
-                                                         int out_f32_cols, int64_t ld16, int relu) {
+template <int MT, int TPW>
+__global__ __launch_bounds__(TG_WAVES * 64) void token_gemm(const _Float16* __restrict__ x,
+                                                            const _Float16* __restrict__ W,
+                                                            const _Float16* __restrict__ bias,
+                                                            float* __restrict__ y32, _Float16* __restrict__ y16,
+                                                            int M, int N, int K, int out_f32_cols, int64_t ld16,
+                                                            int relu) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, c = lane >> 4;
-    const int n0 = blockIdx.x * 16;
-    const _Float16* wp = W + (int64_t)min(n0 + r, N - 1) * K + c * 8;
+    const int n0 = blockIdx.x * (16 * TPW);
+    const _Float16* wp[TPW];
+#pragma unroll
+    for (int p = 0; p < TPW; ++p) wp[p] = W + (int64_t)min(n0 + p * 16 + r, N - 1) * K + c * 8;
     const _Float16* xp[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) xp[t] = x + (int64_t)min(t * 16 + r, M - 1) * K + c * 8;
 
-    floatx4 acc[MT];
+    floatx4 acc[TPW][MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < TPW; ++p)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[p][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int slabs = K / SLAB;
-    for (int s = wave; s < slabs; s += WAVES * UNROLL) {
-        half8 wf[UNROLL][4];
+    for (int s = wave; s < slabs; s += TG_WAVES) {
+        const int k0 = s * SLAB;
+        half8 wf[TPW][4], xf[MT][4];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int k0 = min(s + u * WAVES, slabs - 1) * SLAB;      // clamped slots are skipped below
+        for (int p = 0; p < TPW; ++p)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                wf[u][j] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(wp + k0 + j * 32));
-        }
+                wf[p][j] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(wp[p] + k0 + j * 32));
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            if (s + u * WAVES >= slabs) break;
-            const int k0 = (s + u * WAVES) * SLAB;
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                half8 xf[4];
+            for (int j = 0; j < 4; ++j) xf[t][j] = *reinterpret_cast<const half8*>(xp[t] + k0 + j * 32);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) xf[j] = *reinterpret_cast<const half8*>(xp[t] + k0 + j * 32);
+        for (int p = 0; p < TPW; ++p)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[u][j], xf[j], acc[t], 0, 0, 0);
-            }
-        }
+                    acc[p][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[p][j], xf[t][j], acc[p][t], 0, 0, 0);
     }
 
-    // ---- sum the waves' partial tiles: element i of tile t in lane L is
-    //      n = n0 + 4*(L/16) + i,  m = 16*t + L%16
-    __shared__ float red[WAVES][MT * 4][64];
+    // ---- sum the waves' partial tiles: element i of (tile p, m-tile t) in lane L is
+    //      n = n0 + 16*p + 4*(L/16) + i,  m = 16*t + L%16
+    __shared__ float red[TG_WAVES][TPW * MT * 4][64];
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int p = 0; p < TPW; ++p)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) red[wave][t * 4 + i][lane] = acc[t][i];
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[wave][(p * MT + t) * 4 + i][lane] = acc[p][t][i];
     __syncthreads();
-    for (int e = threadIdx.x; e < MT * 4 * 64; e += WAVES * 64) {
-        const int ti = e >> 6, ln = e & 63;
+    for (int e = threadIdx.x; e < TPW * MT * 4 * 64; e += TG_WAVES * 64) {
+        const int row = e >> 6, ln = e & 63;
         float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) v += red[w][ti][ln];
-        const int t = ti >> 2, i = ti & 3;
-        const int n = n0 + 4 * (ln >> 4) + i;
+        for (int w = 0; w < TG_WAVES; ++w) v += red[w][row][ln];
+        const int p = row / (MT * 4), t = (row / 4) % MT, i = row & 3;
+        const int n = n0 + 16 * p + 4 * (ln >> 4) + i;
         const int m = 16 * t + (ln & 15);
         if (n >= N || m >= M) continue;
         if (bias) v += (float)bias[n];
@@ -95,31 +103,33 @@ __global__ __launch_bounds__(WAVES * 64) void token_gemm(const _Float16* __restr
     }
 }
 
-int g_token_cfg = 0;
+int g_token_tpw = 0;   // 0 = choose from N; tests and sweeps can force 1..8
 
-template <int WAVES, int MT, int UNROLL>
+template <int MT, int TPW>
 int launch_t(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
              int out_f32_cols, int64_t ld16, int relu, hipStream_t st) {
-    const unsigned grid = (unsigned)((N + 15) / 16);
-    hipLaunchKernelGGL((token_gemm<WAVES, MT, UNROLL>), dim3(grid), dim3(WAVES * 64), 0, st, (const _Float16*)x,
+    const unsigned grid = (unsigned)((N + 16 * TPW - 1) / (16 * TPW));
+    hipLaunchKernelGGL((token_gemm<MT, TPW>), dim3(grid), dim3(TG_WAVES * 64), 0, st, (const _Float16*)x,
                        (const _Float16*)w, (const _Float16*)bias, (float*)y32, (_Float16*)y16, M, N, K, out_f32_cols,
                        ld16, relu);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }
 
+// tiles per workgroup: about one workgroup per CU (256), bounded by the LDS reduction buffer
+// (TPW * MT <= 8 keeps it at 64 KiB) and by the accumulator registers
 template <int MT>
 int launch_mt(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
               int out_f32_cols, int64_t ld16, int relu, hipStream_t st) {
-    switch (g_token_cfg) {
-        case 1: return launch_t<4, MT, 4>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-        case 2: return launch_t<8, MT, 4>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-        case 3: return launch_t<4, MT, 2>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-        case 4: return launch_t<8, MT, 2>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-        case 5: return launch_t<16, MT, 2>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-        case 6: return launch_t<2, MT, 4>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-        default: return launch_t<8, MT, 2>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);   // best overall in sweeps
-    }
+    const int tiles = (N + 15) / 16;
+    int tpw = g_token_tpw > 0 ? g_token_tpw : (tiles + 255) / 256;
+    const int cap = 8 / MT;
+    if (tpw > cap) tpw = cap;
+    if (tpw >= 8) return launch_t<MT, (8 / MT >= 8 ? 8 : 1)>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+    if (tpw >= 4) return launch_t<MT, (8 / MT >= 4 ? 4 : 1)>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+    if (tpw == 3) return launch_t<MT, (8 / MT >= 3 ? 3 : 1)>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+    if (tpw == 2) return launch_t<MT, (8 / MT >= 2 ? 2 : 1)>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+    return launch_t<MT, 1>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
 }
 
 }  // namespace
@@ -144,6 +154,6 @@ int launch_token_gemm(const void* x, const void* w, const void* bias, void* y32,
 }  // namespace kvpr
 
 extern "C" int kvpr_debug_set_token_gemm_cfg(int v) {
-    kvpr::g_token_cfg = v;
+    kvpr::g_token_tpw = v;
     return KVPR_OK;
 }
