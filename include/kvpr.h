@@ -191,6 +191,26 @@ int kvpr_timing_read(kvpr_ctx* ctx, int slot, kvpr_layer_timing* timing);
 int kvpr_decode_step(kvpr_ctx* ctx, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
                      void* x_out_dev, const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_layer);
 
+/* ---- column-by-column schedule with offloaded weights (Sec. 3.2 "Column-by-column schedule",
+ * Sec. 3.3, Algorithm 1): the throughput-oriented mode.  The weights live in pinned host memory too;
+ * a layer's weights are loaded once and used for n_gpu_batches batches before the next layer.
+ *
+ * kvpr_create_offload: as kvpr_create (ffn_dim > 0 required) plus a pinned weight store for n_layers
+ * layers, two device weight buffers (the next layer's weights load while this layer's batches run)
+ * and a weight stream.  The X / KV store has n_layers * n_gpu_batches slots; the store functions and
+ * the splits arrays address slot = layer * n_gpu_batches + batch_index in place of `layer`.
+ * kvpr_weights_write: copies one layer's parameters from ordinary host memory (pointers in `host`,
+ * same shapes as the device struct; null biases mean 0) into the pinned weight store.
+ * kvpr_decode_step_columns: one decode token for all batches.  x_in_dev / x_out_dev are
+ * [n_gpu_batches, batch, hidden] float16 hidden states.  Per layer the part of the weights the
+ * recomputation needs ([Wk;Wv], bias) is loaded first and the recomputation runs before the
+ * projections that need Wq ("fine-grained MHA pipeline").  kvpr_decode_step is not available on
+ * such a context. */
+int kvpr_create_offload(const kvpr_model_desc* desc, int n_gpu_batches, void* compute_stream, kvpr_ctx** out);
+int kvpr_weights_write(kvpr_ctx* ctx, int layer, const kvpr_layer_weights* host);
+int kvpr_decode_step_columns(kvpr_ctx* ctx, int seq, const void* x_in_dev, void* x_out_dev,
+                             const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_slot);
+
 /* Greedy sampling step of the row-by-row schedule: logits = hidden . W_lm^T in float32
  * (logits_dev: scratch [batch, vocab] float32), tokens_dev[n] = argmax over the vocabulary (lowest
  * index on ties), and, if emb_dev is non-null, x_next_dev[n] = emb_dev[tokens_dev[n]] (float16

@@ -78,6 +78,9 @@ _SIGS = {
     "kvpr_layer_decode_timed": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, _i]),
     "kvpr_timing_read": (_i, [_vp, _i, C.POINTER(kvpr_layer_timing)]),
     "kvpr_decode_step": (_i, [_vp, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(kvpr_layer_timing)]),
+    "kvpr_create_offload": (_i, [C.POINTER(kvpr_model_desc), _i, _vp, C.POINTER(_vp)]),
+    "kvpr_weights_write": (_i, [_vp, _i, C.POINTER(kvpr_layer_weights)]),
+    "kvpr_decode_step_columns": (_i, [_vp, _i, _vp, _vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(kvpr_layer_timing)]),
     "kvpr_greedy_next": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "kvpr_recompute_gemm": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp]),
     "kvpr_decode_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
@@ -221,6 +224,25 @@ def kvpr_decode_step(ctx, seq, layer_weights, x_in_dev, x_out_dev, splits=None, 
     sout = (C.c_int32 * n)()
     tim = (kvpr_layer_timing * n)() if timing else None
     _check(lib.kvpr_decode_step(ctx, seq, arr, _ptr(x_in_dev), _ptr(x_out_dev), sin, sout, tim))
+    return list(sout), (list(tim) if timing else None)
+
+
+def kvpr_create_offload(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, n_gpu_batches, stream=None, dtype=KVPR_F16):
+    d = kvpr_model_desc(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, dtype)
+    out = _vp()
+    _check(lib.kvpr_create_offload(C.byref(d), n_gpu_batches, _stream(stream), C.byref(out)))
+    return out
+
+
+def kvpr_weights_write(ctx, layer, host_weights):
+    _check(lib.kvpr_weights_write(ctx, layer, C.byref(host_weights)))
+
+
+def kvpr_decode_step_columns(ctx, seq, n_slots, x_in_dev, x_out_dev, splits=None, timing=False):
+    sin = (C.c_int32 * n_slots)(*splits) if splits is not None else None
+    sout = (C.c_int32 * n_slots)()
+    tim = (kvpr_layer_timing * n_slots)() if timing else None
+    _check(lib.kvpr_decode_step_columns(ctx, seq, _ptr(x_in_dev), _ptr(x_out_dev), sin, sout, tim))
     return list(sout), (list(tim) if timing else None)
 
 

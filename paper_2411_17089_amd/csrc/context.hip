@@ -57,6 +57,16 @@ struct kvpr_ctx {
     static constexpr int kMaxChunks = 32;
     hipEvent_t ev_chunk[2][kMaxChunks]{};   // per device buffer: "activation chunk j has landed"
     int chunks = 1;                          // 1 = the paper's schedule: all of X[0:l], then one GEMM
+    // column-by-column schedule with offloaded weights (n_gpu_batches > 0)
+    int nb = 0;                              // GPU batches per layer; the store then has n_layers * nb slots
+    hipStream_t wstream = nullptr;           // weight loads
+    std::vector<half*> hw;                   // pinned weight blob per layer
+    half* dw[2] = {nullptr, nullptr};        // device weight blobs (ping-pong across layers)
+    half* hid_all = nullptr;                 // [nb, batch, hidden] hidden states of all GPU batches
+    hipEvent_t ev_wkv[2]{}, ev_wall[2]{}, ev_wfree[2]{};
+    bool wfree_recorded[2] = {false, false};
+    std::vector<bool> w_written;
+    int slots() const { return nb > 0 ? d.n_layers * nb : d.n_layers; }
     bool free_recorded[2] = {false, false};
     std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
     kvpr_profile_t prof{};
@@ -110,8 +120,14 @@ int resolve_split(kvpr_ctx* c, int seq, int split, int32_t* out) {
 }
 
 // Enqueue one attention layer's decode on the three streams.  ev may be null (no timing).
+// wf (nullable): fences for weights that are themselves in flight from the host
+struct WeightFence {
+    hipEvent_t kv_ready;    // Wk|Wv and their bias have landed
+    hipEvent_t all_ready;   // the whole layer has landed
+};
+
 int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weights* w, const half* x_new, half* out,
-                  int buf, LayerEvents* ev, bool fence_copy_to_start) {
+                  int buf, LayerEvents* ev, bool fence_copy_to_start, const WeightFence* wf = nullptr) {
     const int b = c->d.batch, h = c->d.hidden;
     const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
     half* dkv = c->dkv[buf];
@@ -154,42 +170,56 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     if (ev) KVPR_HIP(hipEventRecord(ev->c_kv, c->copy));
     if (int rc = debug_sync(c)) return rc;
 
-    // ---- compute stream: new token's q (float32) and k|v row `seq` of the device cache (Eq. 1, Eq. 5) ----
-    if (ev) KVPR_HIP(hipEventRecord(ev->p0, c->compute));
-    if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->q32, dkv + (size_t)seq * kr, b, 3 * h, h, h,
-                                               2 * (int64_t)h, 0, c->compute))
-        return rc;
-    KVPR_HIP(hipEventRecord(c->ev_proj, c->compute));
-    if (ev) KVPR_HIP(hipEventRecord(ev->p1, c->compute));
-
-    // ---- store stream: write the new rows back to the host store ----
-    KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_proj, 0));
-    if (ev) KVPR_HIP(hipEventRecord(ev->s0, c->store));
-    KVPR_HIP(hipMemcpyAsync(c->hkv[layer] + (size_t)seq * kr, dkv + (size_t)seq * kr, kr * sizeof(half),
-                            hipMemcpyDeviceToHost, c->store));
-    KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xr, x_new, xr * sizeof(half), hipMemcpyDeviceToHost,
-                            c->store));
-    KVPR_HIP(hipEventRecord(c->ev_store, c->store));
-    if (ev) KVPR_HIP(hipEventRecord(ev->s1, c->store));
-    if (int rc = debug_sync(c)) return rc;
-
+    // ---- new token's q (float32) and k|v row `seq` of the device cache (Eq. 1, Eq. 5), then the store-back ----
+    auto project_and_store = [&]() -> int {
+        if (wf) KVPR_HIP(hipStreamWaitEvent(c->compute, wf->all_ready, 0));
+        if (ev) KVPR_HIP(hipEventRecord(ev->p0, c->compute));
+        if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->q32, dkv + (size_t)seq * kr, b, 3 * h, h, h,
+                                                   2 * (int64_t)h, 0, c->compute))
+            return rc;
+        KVPR_HIP(hipEventRecord(c->ev_proj, c->compute));
+        if (ev) KVPR_HIP(hipEventRecord(ev->p1, c->compute));
+        // store stream: write the new rows back to the host store
+        KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_proj, 0));
+        if (ev) KVPR_HIP(hipEventRecord(ev->s0, c->store));
+        KVPR_HIP(hipMemcpyAsync(c->hkv[layer] + (size_t)seq * kr, dkv + (size_t)seq * kr, kr * sizeof(half),
+                                hipMemcpyDeviceToHost, c->store));
+        KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xr, x_new, xr * sizeof(half), hipMemcpyDeviceToHost,
+                                c->store));
+        KVPR_HIP(hipEventRecord(c->ev_store, c->store));
+        if (ev) KVPR_HIP(hipEventRecord(ev->s1, c->store));
+        return debug_sync(c);
+    };
     // ---- recompute rows [0, l) as soon as their activations have landed (Eq. 7) ----
-    if (nchunk <= 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_x[buf], 0));
-    if (ev) KVPR_HIP(hipEventRecord(ev->r0, c->compute));
-    if (l > 0) {
-        const half* wkv = (const half*)w->wqkv + (size_t)h * h;
-        const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
-        for (int j = 0; j < nchunk; ++j) {
-            // with several chunks the GEMM of chunk j runs while chunks j+1.. and the cache are still on the link
-            if (nchunk > 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_chunk[buf][j], 0));
-            const int64_t rows = (int64_t)(bound[j + 1] - bound[j]) * b;
-            if (int rc = kvpr::launch_gemm(dx + (size_t)bound[j] * xr, wkv, bkv, dkv + (size_t)bound[j] * kr, rows, 2 * h, h,
-                                           2 * (int64_t)h, c->compute))
-                return rc;
+    auto recompute = [&]() -> int {
+        if (wf) KVPR_HIP(hipStreamWaitEvent(c->compute, wf->kv_ready, 0));
+        if (nchunk <= 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_x[buf], 0));
+        if (ev) KVPR_HIP(hipEventRecord(ev->r0, c->compute));
+        if (l > 0) {
+            const half* wkv = (const half*)w->wqkv + (size_t)h * h;
+            const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
+            for (int j = 0; j < nchunk; ++j) {
+                // with several chunks the GEMM of chunk j runs while chunks j+1.. and the cache are still on the link
+                if (nchunk > 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_chunk[buf][j], 0));
+                const int64_t rows = (int64_t)(bound[j + 1] - bound[j]) * b;
+                if (int rc = kvpr::launch_gemm(dx + (size_t)bound[j] * xr, wkv, bkv, dkv + (size_t)bound[j] * kr, rows, 2 * h,
+                                               h, 2 * (int64_t)h, c->compute))
+                    return rc;
+            }
         }
+        if (ev) KVPR_HIP(hipEventRecord(ev->r1, c->compute));
+        return debug_sync(c);
+    };
+    if (wf) {
+        // offloaded weights: Wk|Wv arrive first, so the recomputation goes first and the projections that need
+        // Wq follow (fine-grained MHA pipeline, Sec. 3.3 "Hiding KV cache partial recomputation")
+        if (int rc = recompute()) return rc;
+        if (int rc = project_and_store()) return rc;
+    } else {
+        // resident weights: the token projection runs while the activations are still on the link
+        if (int rc = project_and_store()) return rc;
+        if (int rc = recompute()) return rc;
     }
-    if (ev) KVPR_HIP(hipEventRecord(ev->r1, c->compute));
-    if (int rc = debug_sync(c)) return rc;
 
     // ---- merge = wait for the transferred rows; then attention over all seq+1 rows (Eq. 2) ----
     KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_kv[buf], 0));
@@ -245,7 +275,7 @@ int read_timing(kvpr_ctx* c, LayerEvents* ev, int seq, int l, kvpr_layer_timing*
 
 int check_decode_args(kvpr_ctx* c, int layer, int seq) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
-    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (layer < 0 || layer >= c->slots()) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->slots());
     if (seq < 0 || seq + 1 > c->d.max_seq)
         return fail(KVPR_E_RANGE, "seq %d: need 0 <= seq and seq + 1 <= max_seq = %d", seq, c->d.max_seq);
     return KVPR_OK;
@@ -276,7 +306,14 @@ void destroy_impl(kvpr_ctx* c) {
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
         for (hipEvent_t e : c->ev_chunk[i]) if (e) (void)hipEventDestroy(e);
     }
-    void* dev[] = {c->q32, c->z16, c->attn_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2};
+    if (c->wstream) (void)hipStreamSynchronize(c->wstream);
+    for (auto p : c->hw) if (p) (void)hipHostFree(p);
+    for (int i = 0; i < 2; ++i) {
+        hipEvent_t we[] = {c->ev_wkv[i], c->ev_wall[i], c->ev_wfree[i]};
+        for (hipEvent_t e : we) if (e) (void)hipEventDestroy(e);
+    }
+    if (c->wstream) (void)hipStreamDestroy(c->wstream);
+    void* dev[] = {c->q32, c->z16, c->attn_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2, c->dw[0], c->dw[1], c->hid_all};
     for (void* p : dev) if (p) (void)hipFree(p);
     hipEvent_t evs[] = {c->ev_proj, c->ev_store, c->ev_begin};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
@@ -291,7 +328,53 @@ void destroy_impl(kvpr_ctx* c) {
 
 extern "C" const char* kvpr_last_error(void) { return kvpr::g_err; }
 
+namespace {
+
+// element offsets (in halfs) of one layer's parameters inside a weight blob; the host (pinned) and
+// device blobs share the layout so that a range of the blob is one contiguous copy.  [Wk;Wv] and
+// the q|k|v bias come right after Wq: the range [wkv, wo) is what the recomputation needs.
+struct BlobLayout {
+    size_t wq, wkv, bqkv, wo, bo, ln1_g, ln1_b, ln2_g, ln2_b, w1, b1, w2, b2, total;
+    BlobLayout(size_t h, size_t f) {
+        size_t o = 0;
+        auto take = [&](size_t n) { size_t at = o; o += (n + 63) / 64 * 64; return at; };   // 128-byte aligned pieces
+        wq = take(h * h);          // rows [0, h) of wqkv
+        wkv = take(2 * h * h);     // rows [h, 3h): contiguous with wq because h*h is a multiple of 64
+        bqkv = take(3 * h);
+        wo = take(h * h);
+        bo = take(h);
+        ln1_g = take(h); ln1_b = take(h); ln2_g = take(h); ln2_b = take(h);
+        w1 = take(f * h); b1 = take(f);
+        w2 = take(h * f); b2 = take(h);
+        total = o;
+    }
+};
+
+kvpr_layer_weights blob_weights(half* blob, const BlobLayout& L) {
+    kvpr_layer_weights w{};
+    w.wqkv = blob + L.wq; w.bqkv = blob + L.bqkv; w.wo = blob + L.wo; w.bo = blob + L.bo;
+    w.ln1_g = blob + L.ln1_g; w.ln1_b = blob + L.ln1_b; w.ln2_g = blob + L.ln2_g; w.ln2_b = blob + L.ln2_b;
+    w.w1 = blob + L.w1; w.b1 = blob + L.b1; w.w2 = blob + L.w2; w.b2 = blob + L.b2;
+    return w;
+}
+
+int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_stream, kvpr_ctx** out);
+
+}  // namespace
+
 extern "C" int kvpr_create(const kvpr_model_desc* d, void* compute_stream, kvpr_ctx** out) {
+    return create_impl(d, 0, compute_stream, out);
+}
+
+extern "C" int kvpr_create_offload(const kvpr_model_desc* d, int n_gpu_batches, void* compute_stream, kvpr_ctx** out) {
+    if (n_gpu_batches < 1 || n_gpu_batches > 64) return fail(KVPR_E_RANGE, "n_gpu_batches %d outside [1, 64]", n_gpu_batches);
+    if (d && d->ffn_dim <= 0) return fail(KVPR_E_INVAL, "the column-by-column schedule needs a full decoder layer (ffn_dim > 0)");
+    return create_impl(d, n_gpu_batches, compute_stream, out);
+}
+
+namespace {
+
+int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_stream, kvpr_ctx** out) {
     if (!d || !out) return fail(KVPR_E_INVAL, "desc / out is null");
     if (d->dtype != KVPR_F16) return fail(KVPR_E_INVAL, "only KVPR_F16 is supported");
     if (d->n_layers < 1 || d->batch < 1 || d->max_seq < 1) return fail(KVPR_E_RANGE, "n_layers, batch, max_seq must be >= 1");
@@ -305,8 +388,10 @@ extern "C" int kvpr_create(const kvpr_model_desc* d, void* compute_stream, kvpr_
     kvpr_ctx* c = new (std::nothrow) kvpr_ctx;
     if (!c) return fail(KVPR_E_NOMEM, "out of host memory");
     c->d = *d;
+    c->nb = n_gpu_batches;
     c->compute = (hipStream_t)compute_stream;
-    c->nbuf = d->n_layers > 1 ? 2 : 1;
+    const int slots = c->slots();
+    c->nbuf = slots > 1 ? 2 : 1;
     const size_t x_bytes = (size_t)d->max_seq * c->x_row_halfs() * sizeof(half);
     const size_t kv_bytes = 2 * x_bytes;
     auto bail = [&](int code, const char* what, hipError_t e) {
@@ -320,11 +405,11 @@ extern "C" int kvpr_create(const kvpr_model_desc* d, void* compute_stream, kvpr_
     hipError_t e;
     if ((e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking)) != hipSuccess) return bail(KVPR_E_HIP, "copy stream", e);
     if ((e = hipStreamCreateWithFlags(&c->store, hipStreamNonBlocking)) != hipSuccess) return bail(KVPR_E_HIP, "store stream", e);
-    c->hx.assign(d->n_layers, nullptr);
-    c->hkv.assign(d->n_layers, nullptr);
-    c->x_rows.assign(d->n_layers, 0);
-    c->kv_rows.assign(d->n_layers, 0);
-    for (int i = 0; i < d->n_layers; ++i) {
+    c->hx.assign(slots, nullptr);
+    c->hkv.assign(slots, nullptr);
+    c->x_rows.assign(slots, 0);
+    c->kv_rows.assign(slots, 0);
+    for (int i = 0; i < slots; ++i) {
         if ((e = hipHostMalloc((void**)&c->hx[i], x_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned X store", e);
         if ((e = hipHostMalloc((void**)&c->hkv[i], kv_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned KV store", e);
     }
@@ -354,9 +439,27 @@ extern "C" int kvpr_create(const kvpr_model_desc* d, void* compute_stream, kvpr_
         if ((e = hipMalloc((void**)&c->ffn1, (size_t)d->batch * d->ffn_dim * sizeof(half))) != hipSuccess)
             return bail(KVPR_E_NOMEM, "FFN buffer", e);
     }
+    if (c->nb > 0) {
+        const BlobLayout L(d->hidden, d->ffn_dim);
+        if ((e = hipStreamCreateWithFlags(&c->wstream, hipStreamNonBlocking)) != hipSuccess) return bail(KVPR_E_HIP, "weight stream", e);
+        c->hw.assign(d->n_layers, nullptr);
+        c->w_written.assign(d->n_layers, false);
+        for (int i = 0; i < d->n_layers; ++i)
+            if ((e = hipHostMalloc((void**)&c->hw[i], L.total * sizeof(half), hipHostMallocDefault)) != hipSuccess)
+                return bail(KVPR_E_NOMEM, "pinned weight store", e);
+        for (int i = 0; i < 2; ++i) {
+            if ((e = hipMalloc((void**)&c->dw[i], L.total * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "device weight buffer", e);
+            if ((e = hipEventCreateWithFlags(&c->ev_wkv[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+            if ((e = hipEventCreateWithFlags(&c->ev_wall[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+            if ((e = hipEventCreateWithFlags(&c->ev_wfree[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+        }
+        if ((e = hipMalloc((void**)&c->hid_all, (size_t)c->nb * bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "hidden states", e);
+    }
     *out = c;
     return KVPR_OK;
 }
+
+}  // namespace
 
 extern "C" int kvpr_destroy(kvpr_ctx* c) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
@@ -392,7 +495,7 @@ extern "C" int kvpr_set_profile(kvpr_ctx* c, const kvpr_profile_t* p, int cost_m
 
 extern "C" int kvpr_store_write(kvpr_ctx* c, int layer, int t0, int t1, const void* x_host, const void* kv_host) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
-    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (layer < 0 || layer >= c->slots()) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->slots());
     if (t0 < 0 || t1 < t0 || t1 > c->d.max_seq) return fail(KVPR_E_RANGE, "rows [%d, %d) outside [0, %d]", t0, t1, c->d.max_seq);
     // the copy/store streams may still be touching the store
     KVPR_HIP(hipStreamSynchronize(c->copy));
@@ -411,7 +514,7 @@ extern "C" int kvpr_store_write(kvpr_ctx* c, int layer, int t0, int t1, const vo
 
 extern "C" int kvpr_store_ptrs(kvpr_ctx* c, int layer, void** x_host, void** kv_host) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
-    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (layer < 0 || layer >= c->slots()) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->slots());
     if (x_host) *x_host = c->hx[layer];
     if (kv_host) *kv_host = c->hkv[layer];
     // the caller may now write any row directly: treat all rows as holding data
@@ -422,7 +525,7 @@ extern "C" int kvpr_store_ptrs(kvpr_ctx* c, int layer, void** x_host, void** kv_
 
 extern "C" int kvpr_store_prefill_kv(kvpr_ctx* c, int layer, int seq, const kvpr_layer_weights* w) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
-    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (layer < 0 || layer >= c->slots()) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->slots());
     if (seq < 0 || seq > c->d.max_seq) return fail(KVPR_E_RANGE, "seq %d outside [0, %d]", seq, c->d.max_seq);
     if (int rc = check_weights(c, w, false)) return rc;
     if (c->x_rows[layer] < seq) return fail(KVPR_E_STATE, "layer %d: only %d activation rows written", layer, c->x_rows[layer]);
@@ -494,6 +597,7 @@ extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* 
                                 kvpr_layer_timing* per_layer) {
     if (int rc = check_decode_args(c, 0, seq)) return rc;
     if (c->d.ffn_dim <= 0) return fail(KVPR_E_STATE, "kvpr_decode_step needs ffn_dim > 0");
+    if (c->nb > 0) return fail(KVPR_E_STATE, "context was created for offloaded weights: use kvpr_decode_step_columns");
     if (!layers || !x_in_dev || !x_out_dev) return fail(KVPR_E_INVAL, "layers / x_in_dev / x_out_dev is null");
     const int L = c->d.n_layers, b = c->d.batch, h = c->d.hidden, f = c->d.ffn_dim;
     std::vector<int32_t> ls(L);
@@ -542,6 +646,102 @@ extern "C" int kvpr_greedy_next(const void* hidden_dev, const void* w_lm_dev, co
     if (int rc = kvpr::launch_token_gemm_flags(hidden_dev, w_lm_dev, nullptr, logits_dev, nullptr, batch, vocab, hidden, vocab, 0, 0, st)) return rc;
     if (int rc = kvpr::launch_argmax_rows((const float*)logits_dev, batch, vocab, tokens_dev, st)) return rc;
     if (emb_dev) return kvpr::launch_gather_rows(emb_dev, tokens_dev, x_next_dev, batch, hidden, st);
+    return KVPR_OK;
+}
+
+// ---- column-by-column schedule with offloaded weights (Sec. 3.2, Sec. 3.3, Algorithm 1) ----
+extern "C" int kvpr_weights_write(kvpr_ctx* c, int layer, const kvpr_layer_weights* host) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (c->nb <= 0) return fail(KVPR_E_STATE, "context was not created with kvpr_create_offload");
+    if (layer < 0 || layer >= c->d.n_layers) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->d.n_layers);
+    if (int rc = check_weights(c, host, true)) return rc;
+    KVPR_HIP(hipStreamSynchronize(c->wstream));
+    const size_t h = c->d.hidden, f = c->d.ffn_dim;
+    const BlobLayout L(h, f);
+    half* blob = c->hw[layer];
+    auto put = [&](size_t at, const void* src, size_t n) {
+        if (src) memcpy(blob + at, src, n * sizeof(half));
+        else memset(blob + at, 0, n * sizeof(half));            // absent bias = 0
+    };
+    put(L.wq, host->wqkv, 3 * h * h);                           // wq and wkv are adjacent: one fused [3h, h] block
+    put(L.bqkv, host->bqkv, 3 * h);
+    put(L.wo, host->wo, h * h);
+    put(L.bo, host->bo, h);
+    put(L.ln1_g, host->ln1_g, h); put(L.ln1_b, host->ln1_b, h);
+    put(L.ln2_g, host->ln2_g, h); put(L.ln2_b, host->ln2_b, h);
+    put(L.w1, host->w1, f * h); put(L.b1, host->b1, f);
+    put(L.w2, host->w2, h * f); put(L.b2, host->b2, h);
+    c->w_written[layer] = true;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_dev, void* x_out_dev,
+                                        const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_slot) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (c->nb <= 0) return fail(KVPR_E_STATE, "context was not created with kvpr_create_offload");
+    if (seq < 0 || seq + 1 > c->d.max_seq)
+        return fail(KVPR_E_RANGE, "seq %d: need 0 <= seq and seq + 1 <= max_seq = %d", seq, c->d.max_seq);
+    if (!x_in_dev || !x_out_dev) return fail(KVPR_E_INVAL, "x_in_dev / x_out_dev is null");
+    const int L = c->d.n_layers, nb = c->nb, b = c->d.batch, h = c->d.hidden, f = c->d.ffn_dim;
+    const int S = L * nb;
+    std::vector<int32_t> ls(S);
+    for (int j = 0; j < L; ++j)
+        if (!c->w_written[j]) return fail(KVPR_E_STATE, "layer %d: weights were never written to the host store", j);
+    for (int i = 0; i < S; ++i) {
+        if (int rc = resolve_split(c, seq, splits_in ? splits_in[i] : -1, &ls[i])) return rc;
+        if (int rc = check_rows(c, i, seq, ls[i])) return rc;
+    }
+    if (per_slot)
+        if (int rc = ensure_timing_events(c, S)) return rc;
+    const BlobLayout BL(h, f);
+    const size_t bh = (size_t)b * h;
+    const size_t kv_part = (BL.wo - BL.wkv) * sizeof(half);       // [Wk;Wv] rows and the q|k|v bias
+    // weights of layer j into device blob j % 2: the part the recomputation needs first (fine-grained MHA
+    // pipeline, Sec. 3.3), then Wq and everything else
+    auto load_weights = [&](int j) -> int {
+        const int wb = j & 1;
+        if (c->wfree_recorded[wb]) KVPR_HIP(hipStreamWaitEvent(c->wstream, c->ev_wfree[wb], 0));
+        KVPR_HIP(hipMemcpyAsync(c->dw[wb] + BL.wkv, c->hw[j] + BL.wkv, kv_part, hipMemcpyHostToDevice, c->wstream));
+        KVPR_HIP(hipEventRecord(c->ev_wkv[wb], c->wstream));
+        KVPR_HIP(hipMemcpyAsync(c->dw[wb] + BL.wq, c->hw[j] + BL.wq, (BL.wkv - BL.wq) * sizeof(half), hipMemcpyHostToDevice, c->wstream));
+        KVPR_HIP(hipMemcpyAsync(c->dw[wb] + BL.wo, c->hw[j] + BL.wo, (BL.total - BL.wo) * sizeof(half), hipMemcpyHostToDevice, c->wstream));
+        KVPR_HIP(hipEventRecord(c->ev_wall[wb], c->wstream));
+        return KVPR_OK;
+    };
+    if (int rc = load_weights(0)) return rc;
+    for (int j = 0; j < L; ++j) {
+        const int wb = j & 1;
+        if (j + 1 < L)
+            if (int rc = load_weights(j + 1)) return rc;          // next layer's weights travel while this layer's batches run
+        const kvpr_layer_weights w = blob_weights(c->dw[wb], BL);
+        const WeightFence wf{c->ev_wkv[wb], c->ev_wall[wb]};
+        for (int k = 0; k < nb; ++k) {
+            const int slot = j * nb + k;
+            const half* hid_in = (j == 0) ? (const half*)x_in_dev + (size_t)k * bh : c->hid_all + (size_t)k * bh;
+            half* hid_out = (j == L - 1) ? (half*)x_out_dev + (size_t)k * bh : c->hid_all + (size_t)k * bh;
+            // LayerNorm parameters arrive with the second part of the blob
+            KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_wall[wb], 0));
+            if (int rc = kvpr::launch_layernorm(hid_in, w.ln1_g, w.ln1_b, c->xn, b, h, c->compute)) return rc;
+            if (int rc = enqueue_layer(c, slot, seq, ls[slot], &w, c->xn, c->attn_out, slot % c->nbuf,
+                                       per_slot ? &c->tev[slot] : nullptr, false, &wf))
+                return rc;
+            if (int rc = kvpr::launch_add(hid_in, c->attn_out, c->ffn2, bh, c->compute)) return rc;
+            if (int rc = kvpr::launch_layernorm(c->ffn2, w.ln2_g, w.ln2_b, c->xn, b, h, c->compute)) return rc;
+            if (int rc = kvpr::launch_token_gemm_flags(c->xn, w.w1, w.b1, nullptr, c->ffn1, b, f, h, 0, f, 1, c->compute)) return rc;
+            if (int rc = kvpr::launch_token_gemm_flags(c->ffn1, w.w2, w.b2, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
+            if (int rc = kvpr::launch_add(c->ffn2, c->attn_out, hid_out, bh, c->compute)) return rc;
+        }
+        KVPR_HIP(hipEventRecord(c->ev_wfree[wb], c->compute));
+        c->wfree_recorded[wb] = true;
+    }
+    if (splits_out) std::copy(ls.begin(), ls.end(), splits_out);
+    if (per_slot) {
+        KVPR_HIP(hipStreamSynchronize(c->compute));
+        KVPR_HIP(hipStreamSynchronize(c->copy));
+        KVPR_HIP(hipStreamSynchronize(c->store));
+        for (int i = 0; i < S; ++i)
+            if (int rc = read_timing(c, &c->tev[i], seq, ls[i], &per_slot[i])) return rc;
+    }
     return KVPR_OK;
 }
 

@@ -1,0 +1,145 @@
+"""GPU parity of the column-by-column schedule with offloaded weights (kvpr_decode_step_columns):
+every GPU batch is an independent set of sequences, so the oracle's decoder stack is run per batch."""
+import numpy as np
+import pytest
+import torch
+
+import kvpr_inputs
+from oracle import kvpr_oracle as ko
+from kvpr_testlib import dev, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def k():
+    import paper_2411_17089_amd as k
+    return k
+
+
+def _host_weights(k, L):
+    """Host arrays in the library's layouts (W stored [out, in]); returns (struct, keep-alive list)."""
+    arrs = {
+        "wqkv": np.ascontiguousarray(np.concatenate([L["Wq"].T, L["Wk"].T, L["Wv"].T], 0)),
+        "bqkv": np.concatenate([L["bq"], L["bk"], L["bv"]]),
+        "wo": np.ascontiguousarray(L["Wo"].T), "bo": L["bo"],
+        "w1": np.ascontiguousarray(L["W1"].T), "b1": L["b1"], "w2": np.ascontiguousarray(L["W2"].T), "b2": L["b2"],
+        "ln1_g": L["ln1_g"], "ln1_b": L["ln1_b"], "ln2_g": L["ln2_g"], "ln2_b": L["ln2_b"],
+    }
+    arrs = {n: np.ascontiguousarray(a, dtype=np.float16) for n, a in arrs.items()}
+    return k.make_weights(**arrs), arrs
+
+
+class Columns:
+    def __init__(self, k, n_layers, nb, b, s, h, H, ffn, seed0=300):
+        self.k, self.L, self.nb, self.b, self.s, self.h = k, n_layers, nb, b, s, h
+        self.params = []
+        for j in range(n_layers):
+            P = kvpr_inputs.make_layer(seed0 + j, b, 1, h, H)          # weights of layer j (X unused)
+            P.update(kvpr_inputs.make_ffn(seed0 + j, h, ffn))
+            self.params.append(P)
+        # per (layer, batch) activations of the cached positions
+        self.layers = [[dict(self.params[j], X=kvpr_inputs._draw(np.random.default_rng([seed0, j, q]), (s, b, h), 1.0))
+                        for q in range(nb)] for j in range(n_layers)]
+        self.stored = [[ko.stored_kv(self.layers[j][q], "fp16") for q in range(nb)] for j in range(n_layers)]
+        self.ctx = k.kvpr_create_offload(n_layers, h, H, h // H, ffn, b, s + 3, nb)
+        self.keep = []
+        for j in range(n_layers):
+            w, arrs = _host_weights(k, self.params[j])
+            self.keep.append(arrs)
+            k.kvpr_weights_write(self.ctx, j, w)
+            for q in range(nb):
+                k.kvpr_store_write(self.ctx, j * nb + q, 0, s, np.ascontiguousarray(self.layers[j][q]["X"]),
+                                   self.stored[j][q].astype(np.float16))
+        self.x_in = kvpr_inputs._draw(np.random.default_rng(seed0 - 1), (nb, b, h), 1.0)
+        self.x_out = torch.empty((nb, b, h), dtype=torch.float16, device="cuda")
+
+    def oracle(self, splits):
+        outs = []
+        for q in range(self.nb):
+            ref, _ = ko.decoder_stack_decode([self.layers[j][q] for j in range(self.L)], self.x_in[q],
+                                             [splits[j * self.nb + q] for j in range(self.L)],
+                                             [self.stored[j][q] for j in range(self.L)])
+            outs.append(ref)
+        return np.stack(outs)
+
+    def close(self):
+        self.k.kvpr_destroy(self.ctx)
+
+
+@pytest.mark.parametrize("n_layers,nb,b,s,h,H,ffn", [(3, 3, 4, 40, 256, 2, 1024), (2, 2, 32, 24, 512, 4, 2048), (4, 1, 2, 33, 768, 12, 3072)])
+def test_columns_match_oracle(k, n_layers, nb, b, s, h, H, ffn):
+    st = Columns(k, n_layers, nb, b, s, h, H, ffn)
+    try:
+        S = n_layers * nb
+        rng = np.random.default_rng(9)
+        for trial in range(3):
+            splits = [int(v) for v in rng.integers(0, s + 1, S)]
+            if trial == 0:
+                splits = [0] * S
+            if trial == 1:
+                splits = [s] * S
+            print(f"columns layers={n_layers} nb={nb} b={b} s={s} h={h} splits={splits}", flush=True)
+            got_splits, _ = k.kvpr_decode_step_columns(st.ctx, s, S, dev(st.x_in), st.x_out, splits)
+            torch.cuda.synchronize()
+            assert got_splits == splits
+            ref = st.oracle(splits)
+            got = st.x_out.cpu().numpy()
+            assert np.isfinite(got).all()
+            assert rel_err(got, ref) <= 5e-3
+    finally:
+        st.close()
+
+
+def test_columns_debug_modes_timing_and_errors(k):
+    st = Columns(k, 3, 2, 4, 48, 256, 2, 1024)
+    try:
+        S = 6
+        splits = [7, 48, 0, 20, 33, 48]
+        _, tim = k.kvpr_decode_step_columns(st.ctx, 48, S, dev(st.x_in), st.x_out, splits, timing=True)
+        torch.cuda.synchronize()
+        base = st.x_out.cpu().numpy().copy()
+        assert [t.split for t in tim] == splits and all(t.ms_total > 0 for t in tim)
+        assert rel_err(base, st.oracle(splits)) <= 5e-3
+        for flags in (k.KVPR_DEBUG_SYNC, k.KVPR_DEBUG_POISON, k.KVPR_DEBUG_POISON | k.KVPR_DEBUG_SYNC):
+            k.kvpr_set_debug(st.ctx, flags)
+            k.kvpr_decode_step_columns(st.ctx, 48, S, dev(st.x_in), st.x_out, splits)
+            torch.cuda.synchronize()
+            assert np.array_equal(st.x_out.cpu().numpy(), base), flags
+        k.kvpr_set_debug(st.ctx, 0)
+        # planned splits
+        prof = k.make_profile(40e9, 2e14)
+        k.kvpr_set_profile(st.ctx, prof, k.KVPR_COST_EQ10, 1)
+        want = k.kvpr_plan_split(prof, k.KVPR_COST_EQ10, 4, 48, 256, 2, 1)[0]
+        got_splits, _ = k.kvpr_decode_step_columns(st.ctx, 48, S, dev(st.x_in), st.x_out, None)
+        torch.cuda.synchronize()
+        assert got_splits == [want] * S
+        assert rel_err(st.x_out.cpu().numpy(), st.oracle(got_splits)) <= 5e-3
+        # the row-by-row entry point is refused on this context, and vice versa
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_decode_step(st.ctx, 48, [k.kvpr_layer_weights()] * 3, dev(st.x_in), st.x_out, None)
+        assert e.value.code == k.KVPR_E_STATE
+    finally:
+        st.close()
+    ctx = k.kvpr_create(2, 256, 2, 128, 1024, 2, 8)
+    try:
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_decode_step_columns(ctx, 4, 2, 1, 1, None)
+        assert e.value.code == k.KVPR_E_STATE
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_weights_write(ctx, 0, k.kvpr_layer_weights())
+        assert e.value.code == k.KVPR_E_STATE
+    finally:
+        k.kvpr_destroy(ctx)
+    with pytest.raises(k.KvprError):
+        k.kvpr_create_offload(2, 256, 2, 128, 0, 2, 8, 2)          # needs an FFN
+    with pytest.raises(k.KvprError):
+        k.kvpr_create_offload(2, 256, 2, 128, 1024, 2, 8, 0)
+    ctx = k.kvpr_create_offload(2, 256, 2, 128, 1024, 2, 8, 2)
+    try:
+        with pytest.raises(k.KvprError) as e:                        # weights never written
+            k.kvpr_decode_step_columns(ctx, 0, 4, torch.zeros(2, 2, 256, dtype=torch.float16, device="cuda"),
+                                       torch.zeros(2, 2, 256, dtype=torch.float16, device="cuda"), [0] * 4)
+        assert e.value.code == k.KVPR_E_STATE
+    finally:
+        k.kvpr_destroy(ctx)
