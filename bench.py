@@ -129,6 +129,76 @@ def run_stack(args):
     print(json.dumps(result))
 
 
+def run_columns(args):
+    """Throughput-oriented mode (column-by-column schedule, weights offloaded too): every layer's weights
+    are loaded once per token and used for --gpu-batches batches.  Reports tokens/s with the scheduler's
+    split and, for reference, with l = 0 (no recomputation: transfer the whole cache)."""
+    import torch
+    import kvpr_inputs
+    import paper_2411_17089_amd as k
+    h, H, d = kvpr_inputs.SHAPES[args.model]
+    b, s, L, nb, ffn, gen = args.batch, args.seq, args.layers, args.gpu_batches, 4 * h, args.gen
+    S = L * nb
+    cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
+    rng = np.random.default_rng(0)
+    torch.manual_seed(0)
+    ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + 2 * (gen + args.warmup) + 2, nb)
+    rh = lambda shape, sc: (rng.standard_normal(shape, dtype=np.float32) * np.float32(sc)).astype(np.float16)
+    t0 = time.perf_counter()
+    base = dict(wqkv=rh((3 * h, h), 0.02), bqkv=rh((3 * h,), 0.01), wo=rh((h, h), 0.02), bo=rh((h,), 0.01),
+                ln1_g=(1 + rh((h,), 0.05)).astype(np.float16), ln1_b=rh((h,), 0.02), w1=rh((ffn, h), 0.02), b1=rh((ffn,), 0.01),
+                w2=rh((h, ffn), 0.02), b2=rh((h,), 0.01), ln2_g=(1 + rh((h,), 0.05)).astype(np.float16), ln2_b=rh((h,), 0.02))
+    dev_w = {n: torch.from_numpy(a).cuda() for n, a in base.items()}
+    wdev = k.make_weights(**dev_w)
+    for j in range(L):
+        # one random parameter set, rolled by j rows per layer: distinct bytes per layer without 40 host-side draws
+        lay = {n: (np.roll(a, j, axis=0) if a.ndim == 2 else a) for n, a in base.items()}
+        lay = {n: np.ascontiguousarray(a) for n, a in lay.items()}
+        k.kvpr_weights_write(ctx, j, k.make_weights(**lay))
+        dw = k.make_weights(**{n: torch.from_numpy(a).cuda() for n, a in lay.items()}) if j else wdev
+        for q in range(nb):
+            X = torch.randn((s, b, h), device="cuda", dtype=torch.float16)
+            k.kvpr_store_write(ctx, j * nb + q, 0, s, X.cpu().numpy(), None)
+            k.kvpr_store_prefill_kv(ctx, j * nb + q, s, dw)
+    setup_s = time.perf_counter() - t0
+    prof = k.kvpr_profile(ctx, b, s)
+    k.kvpr_set_profile(ctx, prof, cm, args.granularity)
+    x = (torch.randn((nb, b, h), device="cuda") * 1.0).half()
+    x_out = torch.empty_like(x)
+    seq = s
+    results = {}
+    for name, splits in (("kvpr", None), ("no_recompute", [0] * S)):
+        for _ in range(args.warmup):
+            k.kvpr_decode_step_columns(ctx, seq, S, x, x_out, splits)
+            seq += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(gen):
+            used, _ = k.kvpr_decode_step_columns(ctx, seq, S, x, x_out, splits)
+            seq += 1
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        results[name] = {"tokens_per_s": nb * b * gen / wall, "ms_per_token_step": wall * 1e3 / gen,
+                         "ms_per_layer_batch": wall * 1e3 / gen / S, "split": used[0]}
+    blob_bytes = 12 * h * h * 2
+    r = results["kvpr"]
+    out = {
+        "metric": "decode_tokens_per_s_column_schedule_weights_offloaded", "value": r["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": gen, "warmup": args.warmup, "ms_per_step": r["ms_per_token_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic (seeded random weights and N(0,1) activations; cache = GPU prefill)",
+        "config": {"workload": f"{args.model}-shaped stack, {L} layers, {nb} GPU batches x batch {b} (effective batch {nb * b}), "
+                               f"context {s}, {gen} tokens, weights ({blob_bytes / 2**20:.0f} MiB/layer), X and KV in pinned host memory",
+                   "cost_model": args.cost_model, "granularity": args.granularity},
+        "kvpr": r, "no_recompute": results["no_recompute"],
+        "speedup_over_no_recompute": results["no_recompute"]["ms_per_token_step"] / r["ms_per_token_step"],
+        "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12},
+        "pinned_GiB": (S * (s + 2 * (gen + args.warmup) + 2) * b * 3 * h * 2 + L * blob_bytes) / 2 ** 30, "setup_s": setup_s,
+    }
+    k.kvpr_destroy(ctx)
+    print(json.dumps(out))
+
+
 def run_kernels(args):
     """Standalone launches of the path's kernels at the bench shape, for rocprofv3 counter runs:
     a plain device copy of known size (reference for scaling FETCH_SIZE / WRITE_SIZE), the recompute
@@ -187,6 +257,9 @@ def main():
     ap.add_argument("--split", type=int, default=-1, help="-1 = scheduler's l*")
     ap.add_argument("--cost-model", default="eq10", choices=["eq10", "ns", "row", "pipe"])
     ap.add_argument("--stack", action="store_true", help="layer-pipelined decode of a whole stack instead of one layer")
+    ap.add_argument("--columns", action="store_true",
+                    help="throughput mode: column-by-column schedule with the weights offloaded too (use with --layers, --gpu-batches)")
+    ap.add_argument("--gpu-batches", type=int, default=4)
     ap.add_argument("--kernels", action="store_true", help="launch each kernel of the path standalone (for rocprofv3 --pmc runs)")
     ap.add_argument("--layers", type=int, default=40)
     ap.add_argument("--gen", type=int, default=32)
@@ -215,6 +288,8 @@ def main():
         return run_stack(args)
     if args.kernels:
         return run_kernels(args)
+    if args.columns:
+        return run_columns(args)
     h, H, d = kvpr_inputs.SHAPES[args.model]
     b, s = args.batch, args.seq
     cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
