@@ -131,3 +131,58 @@ def plan_split_chunked(chunks: int, b: int, s: int, h: int, p: int, v_com: float
         if t < best_t:
             best_l, best_t = l, t
     return best_l, best_t
+
+
+# --------------------------------------------------------------------------
+# The same cost forms for any per-position sizes: Eq. 6 and Eq. 8 are linear in
+# the number of positions, M_X = x_bpp * l, M_KV = kv_bpp * (s' - l),
+# N_KV = flops_pp * l.  With x_bpp = b*h*p, kv_bpp = 2*b*h*p, flops_pp = 4*b*h^2
+# this is the paper's model; a compressed store (Sec. 4.4) only changes the two
+# byte rates.  chunks > 1 selects the chunked-copy extension above (Eq. 10 only).
+# --------------------------------------------------------------------------
+def cost_linear(model: int, chunks: int, l: int, s: int, x_bpp: int, kv_bpp: int, flops_pp: int,
+                v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0) -> float:
+    m_x = x_bpp * l
+    m_kv = kv_bpp * (s - l)
+    n_kv = flops_pp * l
+    send_x = float(m_x) / v_com
+    send_kv = float(m_kv) / v_com
+    gemm = float(n_kv) / v_gpu
+    if chunks > 1:
+        if model != COST_EQ10:
+            raise ValueError("the chunked schedule is modelled for Eq. 10 only")
+        if l < s:
+            send_kv = send_kv + lat_com
+        finished = 0.0
+        if l > 0:
+            for j in range(1, chunks + 1):
+                arrived = send_x * float(j) / float(chunks) + lat_com
+                begin = max(arrived, finished)
+                finished = begin + (gemm / float(chunks) + lat_gpu)
+        link = ((send_x + lat_com) if l > 0 else 0.0) + send_kv
+        return max(finished, link)
+    if l > 0:
+        send_x = send_x + lat_com
+        gemm = gemm + lat_gpu
+    if l < s:
+        send_kv = send_kv + lat_com
+    if model == COST_EQ10:
+        return send_x + max(gemm, send_kv)
+    if model == COST_ROW:
+        return max(gemm, send_kv)
+    if model == COST_NS:
+        return max(gemm + send_x, send_kv)
+    if model == COST_PIPE:
+        return max(send_x + send_kv, gemm)
+    raise ValueError(f"unknown cost model {model}")
+
+
+def plan_split_linear(model: int, chunks: int, s: int, x_bpp: int, kv_bpp: int, flops_pp: int,
+                      v_com: float, v_gpu: float, granularity: int = 1,
+                      lat_com: float = 0.0, lat_gpu: float = 0.0):
+    best_l, best_t = -1, float("inf")
+    for l in candidates(s, granularity):
+        t = cost_linear(model, chunks, l, s, x_bpp, kv_bpp, flops_pp, v_com, v_gpu, lat_com, lat_gpu)
+        if t < best_t:
+            best_l, best_t = l, t
+    return best_l, best_t

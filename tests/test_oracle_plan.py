@@ -146,3 +146,47 @@ def test_chunked_cost_reduces_to_eq10_and_hand_values():
     assert all(a >= b for a, b in zip(ts, ts[1:]))
     assert ts[0] == po.plan_split(po.COST_EQ10, **real)[1]
     assert ts[-1] >= po.bytes_x(32, 1024, 4096, 2) / 57e9
+
+
+def test_linear_model_reduces_to_the_papers_sizes():
+    # with Eq. 6 / Eq. 8 per-position sizes the linear form is Eq. 10 (and its variants) itself
+    b, s, h, p = 3, 37, 128, 2
+    for model in (po.COST_EQ10, po.COST_NS, po.COST_ROW, po.COST_PIPE):
+        for l in range(0, s + 1):
+            a = po.cost(model, l, b, s, h, p, 7e9, 3e13, 2e-5, 1e-5)
+            c = po.cost_linear(model, 1, l, s, b * h * p, 2 * b * h * p, 4 * b * h * h, 7e9, 3e13, 2e-5, 1e-5)
+            assert a == c
+        assert po.plan_split(model, b, s, h, p, 7e9, 3e13, 4) == \
+            po.plan_split_linear(model, 1, s, b * h * p, 2 * b * h * p, 4 * b * h * h, 7e9, 3e13, 4)
+    for chunks in (2, 3, 5):
+        for l in (0, 8, 24, 37):
+            assert po.cost_chunked(chunks, l, b, s, h, p, 7e9, 3e13, 2e-5, 1e-5) == \
+                po.cost_linear(po.COST_EQ10, chunks, l, s, b * h * p, 2 * b * h * p, 4 * b * h * h, 7e9, 3e13, 2e-5, 1e-5)
+
+
+def test_linear_model_hand_values_with_compressed_sizes():
+    # x: 9 B/pos, cache: 18 B/pos, 60 flop/pos, link 3 B/s, GPU 10 flop/s, s = 8
+    # l = 2: send_x = 6, gemm = 12, send_kv = 36  -> Eq. 10: 6 + 36 = 42
+    # l = 6: send_x = 18, gemm = 36, send_kv = 12 -> Eq. 10: 18 + 36 = 54;  pipe: max(30, 36) = 36
+    assert po.cost_linear(po.COST_EQ10, 1, 2, 8, 9, 18, 60, 3.0, 10.0) == 42.0
+    assert po.cost_linear(po.COST_EQ10, 1, 6, 8, 9, 18, 60, 3.0, 10.0) == 54.0
+    assert po.cost_linear(po.COST_PIPE, 1, 6, 8, 9, 18, 60, 3.0, 10.0) == 36.0
+    # crossing of gemm (6 l) and send_kv (6 (8 - l)) is l = 4: t = 12 + 24 = 36, the minimum
+    assert po.plan_split_linear(po.COST_EQ10, 1, 8, 9, 18, 60, 3.0, 10.0) == (4, 36.0)
+
+
+def test_compressing_only_the_cache_disables_recomputation():
+    # Sec. 4.4 with the activations left in float16: a position's activations (2h bytes) cost more on the
+    # link than its 4-bit cache (9h/8 bytes), so Eq. 10 is increasing in l and l* = 0; with both compressed
+    # (9h/16 against 9h/8 bytes) the 1 : 2 ratio of Eq. 6 is back and l* is where it was in float16
+    b, s, h = 32, 1024, 4096
+    v_com, v_gpu = 57e9, 1.0e15
+    fp = 4 * b * h * h
+    l_kv_only, _ = po.plan_split_linear(po.COST_EQ10, 1, s, b * 2 * h, b * 9 * h // 8, fp, v_com, v_gpu, 64)
+    assert l_kv_only == 0
+    l_both, t_both = po.plan_split_linear(po.COST_EQ10, 1, s, b * 9 * h // 16, b * 9 * h // 8, fp, v_com, v_gpu, 1)
+    r, k = fp / v_gpu, (b * 9 * h // 8) / v_com
+    l_closed = k * s / (r + k)
+    assert abs(l_both - l_closed) <= 1
+    l_fp16, t_fp16 = po.plan_split(po.COST_EQ10, b, s, h, 2, v_com, v_gpu, 1)
+    assert l_both < l_fp16 and t_both < t_fp16       # less to send: the GPU takes a smaller share, the step is shorter
