@@ -270,6 +270,8 @@ def main():
                     help="extension: copy X[0:l] in this many parts and start each part's GEMM as it lands (1 = paper's schedule)")
     ap.add_argument("--extension-chunks", type=int, default=3,
                     help="after the timed region, also measure the chunked-copy extension with this many parts (0 = skip)")
+    ap.add_argument("--store-int4", default="none", choices=["none", "kv", "both"],
+                    help="keep the host store group-wise 4-bit compressed (Sec. 4.4): the cache only, or the cache and the activations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
     args = ap.parse_args()
@@ -302,22 +304,23 @@ def main():
     w = k.make_weights(wqkv=wqkv, bqkv=bqkv, wo=wo, bo=bo)
     out = torch.empty((b, h), dtype=torch.float16, device="cuda")
 
-    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2)
+    qflags = {"none": 0, "kv": k.KVPR_KV_INT4, "both": k.KVPR_STORE_INT4}[args.store_int4]
+    # bytes per cached position (whole batch) as they cross the link, flops per recomputed position (Eq. 6, Eq. 8)
+    x_bpp = b * (k.kvpr_int4_row_bytes(h) if qflags & k.KVPR_X_INT4 else 2 * h)
+    kv_bpp = b * (k.kvpr_int4_row_bytes(2 * h) if qflags & k.KVPR_KV_INT4 else 4 * h)
+    f_pp = 4 * b * h * h
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, dtype=k.KVPR_F16 | qflags)
     k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
     k.kvpr_store_prefill_kv(ctx, 0, s, w)          # stand-in for prefill: cache = X.[Wk|Wv]+b, computed on the GPU
 
     prof = k.kvpr_profile(ctx, b, s)
     k.kvpr_set_profile(ctx, prof, cm, args.granularity)
     k.kvpr_set_chunks(ctx, args.chunks)
-    if args.chunks > 1 and cm == k.KVPR_COST_EQ10:
-        l_star, t_bound = k.kvpr_plan_split_chunked(prof, args.chunks, b, s, h, 2, args.granularity)
-        split = l_star if args.split < 0 else args.split
-        t_bound_split = k.kvpr_cost_chunked(prof, args.chunks, split, b, s, h, 2)
-    else:
-        l_star, t_bound = k.kvpr_plan_split(prof, cm, b, s, h, 2, args.granularity)
-        split = l_star if args.split < 0 else args.split
-        t_bound_split = k.kvpr_cost(prof, cm, split, b, s, h, 2)
-    l_eq10, t_eq10 = k.kvpr_plan_split(prof, k.KVPR_COST_EQ10, b, s, h, 2, args.granularity)
+    pchunks = args.chunks if cm == k.KVPR_COST_EQ10 else 1
+    l_star, t_bound = k.kvpr_plan_split_linear(prof, cm, pchunks, s, x_bpp, kv_bpp, f_pp, args.granularity)
+    split = l_star if args.split < 0 else args.split
+    t_bound_split = k.kvpr_cost_linear(prof, cm, pchunks, split, s, x_bpp, kv_bpp, f_pp)
+    l_eq10, t_eq10 = k.kvpr_plan_split_linear(prof, k.KVPR_COST_EQ10, 1, s, x_bpp, kv_bpp, f_pp, args.granularity)
 
     for _ in range(args.warmup):
         k.kvpr_layer_decode(ctx, 0, s, split, w, x_new, out)
@@ -335,7 +338,7 @@ def main():
     ms_act, ms_kv = mean("ms_act_copy"), mean("ms_kv_copy")
     gemm_flops = 4.0 * b * split * h * h
     attn_bytes = 2.0 * b * (s + 1) * h * 2
-    h2d_bytes = b * h * 2.0 * (split + 2 * (s - split))
+    h2d_bytes = float(x_bpp * split + kv_bpp * (s - split))
     gemm_tflops = gemm_flops / (ms_gemm * 1e-3) / 1e12 if split > 0 else 0.0
     attn_gbps = attn_bytes / (ms_attn * 1e-3) / 1e9
     h2d_gbps = h2d_bytes / ((ms_act + ms_kv) * 1e-3) / 1e9
@@ -360,7 +363,8 @@ def main():
         "data": "synthetic (seeded N(0,1) activations, N(0,0.02) weights; cache = GPU prefill of the same X)",
         "config": {"workload": f"{args.model}-shaped attention layer, hidden {h}, {H} heads x {d}, batch {b}, context {s}, "
                                f"decode 1 token at split l={split}",
-                   "cost_model": args.cost_model, "granularity": args.granularity, "l_star": l_star, "chunks": args.chunks},
+                   "cost_model": args.cost_model, "granularity": args.granularity, "l_star": l_star, "chunks": args.chunks,
+                   "store_int4": args.store_int4},
         "ms_per_layer": ms_step,
         "ms_assemble": mean("ms_assemble"), "ms_total_events": mean("ms_total"),
         "cost_model_bound_ms": t_bound_split * 1e3,
@@ -369,7 +373,7 @@ def main():
         "latency_over_bound": mean("ms_assemble") / (t_bound_split * 1e3),
         "step_over_bound": ms_step / (t_bound_split * 1e3),
         "breakdown_ms": {"act_copy": ms_act, "kv_copy": ms_kv, "recompute": ms_gemm, "proj": mean("ms_proj"),
-                         "attn": ms_attn, "out": mean("ms_out"), "store": mean("ms_store")},
+                         "attn": ms_attn, "out": mean("ms_out"), "store": mean("ms_store"), "kv_dequant": mean("ms_dequant")},
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12,
                     "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9, "d2h_GBps": prof.d2h_bytes_per_s / 1e9,
                     "attn_GBps": prof.attn_bytes_per_s / 1e9},
@@ -387,7 +391,7 @@ def main():
         # same layer, same number of steps, X[0:l] copied in parts with each part's GEMM started as it lands
         c = args.extension_chunks
         k.kvpr_set_chunks(ctx, c)
-        l_c, t_c = k.kvpr_plan_split_chunked(prof, c, b, s, h, 2, args.granularity)
+        l_c, t_c = k.kvpr_plan_split_linear(prof, k.KVPR_COST_EQ10, c, s, x_bpp, kv_bpp, f_pp, args.granularity)
         for _ in range(args.warmup):
             k.kvpr_layer_decode(ctx, 0, s, l_c, w, x_new, out)
         torch.cuda.synchronize()
@@ -412,7 +416,8 @@ def main():
             "value": n_seq / dt, "unit": "tokens/s per layer", "cores": cores, "kind": "oracle",
             "sample": f"first {n_seq} of the {b} sequences of the same layer, one decode step: numpy float64 recompute of "
                       f"all {s} K/V rows (Eq. 1) + attention + output projection; {dt:.2f} s",
-            "max_rel_err_gpu_vs_oracle_on_sample": float(np.max(np.abs(got - o_ref)) / np.max(np.abs(o_ref))),
+            ("max_rel_err_gpu_vs_oracle_on_sample" if not qflags else "max_rel_err_gpu_over_4bit_store_vs_exact_oracle_on_sample"):
+                float(np.max(np.abs(got - o_ref)) / np.max(np.abs(o_ref))),
         }
     k.kvpr_destroy(ctx)
     print(json.dumps(result))

@@ -49,6 +49,16 @@ extern "C" {
 #define KVPR_E_STATE  -5   /* call not valid in the current state (e.g. rows unwritten) */
 
 #define KVPR_F16 1
+/* Flags or-ed into kvpr_model_desc.dtype: keep the host store group-wise 4-bit compressed
+ * (Sec. 4.4 "KV Cache Compression").  KV_INT4 compresses the cache rows, X_INT4 the stored
+ * activations; KVPR_STORE_INT4 sets both.  All arithmetic stays float16 / float32: rows are
+ * dequantised on the GPU after the copy, new rows are quantised on the GPU before the store-back.
+ * Compressing the cache alone makes a position's activations (2h bytes) larger than its cache
+ * (9h/8 bytes), and Eq. 10 then never chooses to recompute; with both, the 1 : 2 ratio of Eq. 6
+ * is kept (9h/16 against 9h/8 bytes per position and sequence). */
+#define KVPR_KV_INT4    0x100
+#define KVPR_X_INT4     0x200
+#define KVPR_STORE_INT4 (KVPR_KV_INT4 | KVPR_X_INT4)
 
 /* Cost forms for the scheduler.  EQ10 is the paper's Eq. 10 (activations and cache
  * share one link, activations first).  ROW is Eq. 10 without its first term (the
@@ -76,7 +86,7 @@ typedef struct {
     int32_t ffn_dim;    /* 0 = attention block only (kvpr_decode_step then unavailable)  */
     int32_t batch;      /* b >= 1                                                        */
     int32_t max_seq;    /* rows per layer in the host store and device buffers; a decode at seq cached positions needs seq + 1 <= max_seq */
-    int32_t dtype;      /* KVPR_F16                                                      */
+    int32_t dtype;      /* KVPR_F16, optionally | KVPR_KV_INT4 | KVPR_X_INT4             */
 } kvpr_model_desc;
 
 /* Profiler output (Sec. 3.1 "profiler module"): the two constants of Eq. 9 / Eq. 10
@@ -115,7 +125,8 @@ typedef struct {
     float ms_total;      /* first enqueue -> output projection and store-back done     */
     double t_bound_s;    /* cost-model prediction for the split used (0 if no profile) */
     int32_t split;       /* the split l actually used                                   */
-    int32_t reserved;
+    float ms_dequant;    /* dequantisation of the transferred cache rows (0 without KVPR_KV_INT4); the
+                            activations' dequantisation is part of ms_recompute        */
 } kvpr_layer_timing;
 
 const char* kvpr_last_error(void);
@@ -130,10 +141,13 @@ int kvpr_set_debug(kvpr_ctx* ctx, int flags);
 int kvpr_set_profile(kvpr_ctx* ctx, const kvpr_profile_t* prof, int cost_model, int granularity);
 
 /* Host store (Sec. 3.3 "pinned memory").  Copies rows [t0, t1) of `layer` from
- * ordinary host memory; x_host is [t1-t0, batch, hidden], kv_host [t1-t0, batch, 2*hidden];
- * either may be null to leave that array untouched. */
+ * ordinary host memory; x_host is [t1-t0, batch, hidden], kv_host [t1-t0, batch, 2*hidden],
+ * both float16; either may be null to leave that array untouched.  An array that the context
+ * keeps compressed is quantised on the GPU on the way (the call then synchronises the device). */
 int kvpr_store_write(kvpr_ctx* ctx, int layer, int t0, int t1, const void* x_host, const void* kv_host);
-/* Borrowed pointers to a layer's pinned arrays X[max_seq,batch,hidden] and KV[max_seq,batch,2*hidden]. */
+/* Borrowed pointers to a layer's pinned arrays X[max_seq,batch,hidden] and KV[max_seq,batch,2*hidden]
+ * (float16), or, for an array kept compressed, its packed form [max_seq, batch, kvpr_int4_row_bytes(cols)]
+ * with cols = hidden for X and 2*hidden for KV. */
 int kvpr_store_ptrs(kvpr_ctx* ctx, int layer, void** x_host, void** kv_host);
 /* Stand-in for prefill: computes KV[0:seq] of `layer` from the stored X[0:seq] on the
  * GPU (Eq. 1 for K and V) and writes it into the host store.  Synchronises. */
@@ -166,6 +180,16 @@ int kvpr_cost_chunked(const kvpr_profile_t* prof, int chunks, int split, int bat
                       int elem_bytes, double* t_pred);
 int kvpr_plan_split_chunked(const kvpr_profile_t* prof, int chunks, int batch, int seq, int hidden,
                             int elem_bytes, int granularity, int32_t* l_star, double* t_pred);
+
+/* The same scheduler on per-position sizes (Eq. 6 and Eq. 8 are linear in the number of positions):
+ * M_X = x_bytes_per_pos * l, M_KV = kv_bytes_per_pos * (seq - l), N_KV = flops_per_pos * l.  With
+ * b*h*p, 2*b*h*p and 4*b*h*h these are kvpr_cost / kvpr_plan_split; a compressed store (Sec. 4.4)
+ * passes its own byte rates.  chunks > 1 selects the chunked schedule above (KVPR_COST_EQ10 only). */
+int kvpr_cost_linear(const kvpr_profile_t* prof, int cost_model, int chunks, int split, int seq,
+                     int64_t x_bytes_per_pos, int64_t kv_bytes_per_pos, int64_t flops_per_pos, double* t_pred);
+int kvpr_plan_split_linear(const kvpr_profile_t* prof, int cost_model, int chunks, int seq,
+                           int64_t x_bytes_per_pos, int64_t kv_bytes_per_pos, int64_t flops_per_pos,
+                           int granularity, int32_t* l_star, double* t_pred);
 
 /* One decode step of one attention layer (Sec. 3.2 row-by-row pipeline with partial
  * recomputation; Eq. 1, 2, 3, 5, 7).  `seq` = cached positions s already in the host
@@ -238,6 +262,16 @@ size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S)
  * (used for q), the remaining N - out_f32_cols columns as float16 to y16_dev with row stride ld16. */
 int kvpr_token_gemm(const void* x_dev, const void* w_dev, const void* bias_dev, void* y32_dev, void* y16_dev,
                     int M, int N, int K, int out_f32_cols, int64_t ld16, void* stream);
+
+/* Group-wise 4-bit codec of the compressed store (Sec. 4.4; the paper fixes no format, this is the
+ * library's): rows of `cols` float16 columns (cols % 64 == 0) in groups of 64 columns; per group
+ * mn = min, scale = float16((max - mn) / 15), code = clamp(rint((x - mn) / scale), 0, 15) in float32
+ * (all codes 0 when scale == 0), value = float16(code * scale + mn).  A packed row is cols/2 code bytes
+ * (element 2k in the low nibble of byte k) followed by cols/64 float16 pairs (scale, mn):
+ * kvpr_int4_row_bytes(cols) = 9*cols/16 bytes.  src_dev / dst_dev hold `rows` contiguous rows. */
+size_t kvpr_int4_row_bytes(int cols);
+int kvpr_quant_int4(const void* src_dev, void* dst_dev, int64_t rows, int cols, void* stream);
+int kvpr_dequant_int4(const void* src_dev, void* dst_dev, int64_t rows, int cols, void* stream);
 
 #ifdef __cplusplus
 }

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkvpr.so")
 
 KVPR_OK, KVPR_E_INVAL, KVPR_E_RANGE, KVPR_E_NOMEM, KVPR_E_HIP, KVPR_E_STATE = 0, -1, -2, -3, -4, -5
 KVPR_F16 = 1
+KVPR_KV_INT4, KVPR_X_INT4, KVPR_STORE_INT4 = 0x100, 0x200, 0x300
 KVPR_COST_EQ10, KVPR_COST_NS, KVPR_COST_ROW, KVPR_COST_PIPE = 0, 1, 2, 3
 KVPR_DEBUG_SYNC, KVPR_DEBUG_POISON = 1, 2
 
@@ -41,10 +42,10 @@ class kvpr_layer_weights(C.Structure):
 class kvpr_layer_timing(C.Structure):
     _fields_ = [(n, C.c_float) for n in
                 ("ms_act_copy", "ms_kv_copy", "ms_recompute", "ms_proj", "ms_attn", "ms_out", "ms_store",
-                 "ms_assemble", "ms_total")] + [("t_bound_s", C.c_double), ("split", C.c_int32), ("reserved", C.c_int32)]
+                 "ms_assemble", "ms_total")] + [("t_bound_s", C.c_double), ("split", C.c_int32), ("ms_dequant", C.c_float)]
 
     def as_dict(self):
-        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+        return {n: getattr(self, n) for n, _ in self._fields_}
 
 
 class KvprError(RuntimeError):
@@ -74,6 +75,8 @@ _SIGS = {
     "kvpr_set_chunks": (_i, [_vp, _i]),
     "kvpr_cost_chunked": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_double)]),
     "kvpr_plan_split_chunked": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
+    "kvpr_cost_linear": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i64, _i64, _i64, C.POINTER(C.c_double)]),
+    "kvpr_plan_split_linear": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i64, _i64, _i64, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "kvpr_layer_decode": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(kvpr_layer_timing)]),
     "kvpr_layer_decode_timed": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, _i]),
     "kvpr_timing_read": (_i, [_vp, _i, C.POINTER(kvpr_layer_timing)]),
@@ -86,6 +89,9 @@ _SIGS = {
     "kvpr_decode_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "kvpr_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "kvpr_token_gemm": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
+    "kvpr_int4_row_bytes": (_sz, [_i]),
+    "kvpr_quant_int4": (_i, [_vp, _vp, _i64, _i, _vp]),
+    "kvpr_dequant_int4": (_i, [_vp, _vp, _i64, _i, _vp]),
 }
 EXPORTS = tuple(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -192,6 +198,20 @@ def kvpr_plan_split_chunked(prof, chunks, batch, seq, hidden, elem_bytes=2, gran
     return l.value, t.value
 
 
+def kvpr_cost_linear(prof, cost_model, chunks, split, seq, x_bytes_per_pos, kv_bytes_per_pos, flops_per_pos):
+    t = C.c_double()
+    _check(lib.kvpr_cost_linear(C.byref(prof), cost_model, chunks, split, seq, x_bytes_per_pos, kv_bytes_per_pos,
+                                flops_per_pos, C.byref(t)))
+    return t.value
+
+
+def kvpr_plan_split_linear(prof, cost_model, chunks, seq, x_bytes_per_pos, kv_bytes_per_pos, flops_per_pos, granularity=1):
+    l, t = C.c_int32(), C.c_double()
+    _check(lib.kvpr_plan_split_linear(C.byref(prof), cost_model, chunks, seq, x_bytes_per_pos, kv_bytes_per_pos,
+                                      flops_per_pos, granularity, C.byref(l), C.byref(t)))
+    return l.value, t.value
+
+
 def make_weights(**tensors) -> kvpr_layer_weights:
     """kvpr_layer_weights from device tensors given by field name; keeps no reference (caller keeps them alive)."""
     w = kvpr_layer_weights()
@@ -266,3 +286,15 @@ def kvpr_decode_attention(q_dev, kv_dev, z_dev, ws_dev, S, batch, hidden, n_head
 def kvpr_token_gemm(x_dev, w_dev, bias_dev, y32_dev, y16_dev, M, N, K, out_f32_cols, ld16, stream=None):
     _check(lib.kvpr_token_gemm(_ptr(x_dev), _ptr(w_dev), _ptr(bias_dev), _ptr(y32_dev), _ptr(y16_dev), M, N, K,
                                out_f32_cols, ld16, _stream(stream)))
+
+
+def kvpr_int4_row_bytes(cols) -> int:
+    return lib.kvpr_int4_row_bytes(cols)
+
+
+def kvpr_quant_int4(src_dev, dst_dev, rows, cols, stream=None):
+    _check(lib.kvpr_quant_int4(_ptr(src_dev), _ptr(dst_dev), rows, cols, _stream(stream)))
+
+
+def kvpr_dequant_int4(src_dev, dst_dev, rows, cols, stream=None):
+    _check(lib.kvpr_dequant_int4(_ptr(src_dev), _ptr(dst_dev), rows, cols, _stream(stream)))

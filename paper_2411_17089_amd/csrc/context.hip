@@ -31,10 +31,10 @@ typedef _Float16 half;
 
 // events bracketing each category of one layer (timing enabled)
 struct LayerEvents {
-    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, a0, a1, o1, s0, s1, end;
+    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, d0, a0, a1, o1, s0, s1, end;
     int seq = -1, split = -1;            // what the slot last recorded
     hipEvent_t* all() { return &start; }
-    static constexpr int count = 14;
+    static constexpr int count = 15;
 };
 
 }  // namespace
@@ -42,7 +42,10 @@ struct LayerEvents {
 struct kvpr_ctx {
     kvpr_model_desc d{};
     hipStream_t compute = nullptr, copy = nullptr, store = nullptr;
-    std::vector<half*> hx, hkv;          // pinned, per layer
+    std::vector<char*> hx, hkv;          // pinned, per layer: float16 rows, or packed 4-bit rows (Sec. 4.4)
+    bool qx = false, qkv = false;        // which of the two arrays the store keeps 4-bit compressed
+    char* dxq[2] = {nullptr, nullptr};   // device staging for packed rows (only when compressed)
+    char* dkvq[2] = {nullptr, nullptr};
     std::vector<int> x_rows, kv_rows;    // contiguous prefix of rows known to hold data
     int nbuf = 0;
     half* dx[2] = {nullptr, nullptr};
@@ -76,6 +79,11 @@ struct kvpr_ctx {
 
     size_t x_row_halfs() const { return (size_t)d.batch * d.hidden; }
     size_t kv_row_halfs() const { return (size_t)d.batch * 2 * d.hidden; }
+    // bytes of one position (all sequences of the batch) as the host store holds it and as it crosses the link
+    size_t x_store_bytes() const { return qx ? d.batch * kvpr::int4_row_bytes(d.hidden) : x_row_halfs() * sizeof(half); }
+    size_t kv_store_bytes() const { return qkv ? d.batch * kvpr::int4_row_bytes(2 * d.hidden) : kv_row_halfs() * sizeof(half); }
+    int64_t flops_per_pos() const { return 4 * (int64_t)d.batch * d.hidden * d.hidden; }   // Eq. 8
+    int plan_chunks() const { return (chunks > 1 && cost_model == KVPR_COST_EQ10) ? chunks : 1; }
 };
 
 namespace {
@@ -110,9 +118,8 @@ int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn)
 int resolve_split(kvpr_ctx* c, int seq, int split, int32_t* out) {
     if (split == -1) {
         if (!c->have_prof) return fail(KVPR_E_STATE, "split = -1 needs kvpr_set_profile first");
-        if (c->chunks > 1 && c->cost_model == KVPR_COST_EQ10)
-            return kvpr_plan_split_chunked(&c->prof, c->chunks, c->d.batch, seq, c->d.hidden, 2, c->granularity, out, nullptr);
-        return kvpr_plan_split(&c->prof, c->cost_model, c->d.batch, seq, c->d.hidden, 2, c->granularity, out, nullptr);
+        return kvpr_plan_split_linear(&c->prof, c->cost_model, c->plan_chunks(), seq, (int64_t)c->x_store_bytes(),
+                                      (int64_t)c->kv_store_bytes(), c->flops_per_pos(), c->granularity, out, nullptr);
     }
     if (split < 0 || split > seq) return fail(KVPR_E_RANGE, "split %d outside [0, %d]", split, seq);
     *out = split;
@@ -130,8 +137,12 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
                   int buf, LayerEvents* ev, bool fence_copy_to_start, const WeightFence* wf = nullptr) {
     const int b = c->d.batch, h = c->d.hidden;
     const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
+    const size_t xsb = c->x_store_bytes(), ksb = c->kv_store_bytes();
     half* dkv = c->dkv[buf];
     half* dx = c->dx[buf];
+    // where copies from / to the store land on the device: the float16 buffers, or the packed staging buffers
+    char* x_stage = c->qx ? c->dxq[buf] : (char*)dx;
+    char* kv_stage = c->qkv ? c->dkvq[buf] : (char*)dkv;
 
     if (ev) {
         ev->seq = seq;
@@ -141,6 +152,9 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     if (c->debug & KVPR_DEBUG_POISON) {
         if (int rc = kvpr::launch_fill_u16(dkv, (size_t)(seq + 1) * kr, 0x7E00, c->compute)) return rc;
         if (int rc = kvpr::launch_fill_u16(dx, (size_t)seq * xr, 0x7E00, c->compute)) return rc;
+        // packed staging: all-ones words decode to NaN scale and minimum
+        if (c->qx) if (int rc = kvpr::launch_fill_u16(x_stage, (size_t)seq * xsb / 2, 0xFFFF, c->compute)) return rc;
+        if (c->qkv) if (int rc = kvpr::launch_fill_u16(kv_stage, (size_t)seq * ksb / 2, 0xFFFF, c->compute)) return rc;
     }
     if (fence_copy_to_start || (c->debug & KVPR_DEBUG_POISON)) {
         KVPR_HIP(hipEventRecord(c->ev_begin, c->compute));
@@ -157,15 +171,15 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     for (int j = 0; j <= nchunk; ++j) bound[j] = (j == nchunk) ? l : (int)((int64_t)l * j / nchunk) / 8 * 8;
     for (int j = 0; j < nchunk; ++j) {
         if (bound[j + 1] > bound[j])
-            KVPR_HIP(hipMemcpyAsync(dx + (size_t)bound[j] * xr, c->hx[layer] + (size_t)bound[j] * xr,
-                                    (size_t)(bound[j + 1] - bound[j]) * xr * sizeof(half), hipMemcpyHostToDevice, c->copy));
+            KVPR_HIP(hipMemcpyAsync(x_stage + (size_t)bound[j] * xsb, c->hx[layer] + (size_t)bound[j] * xsb,
+                                    (size_t)(bound[j + 1] - bound[j]) * xsb, hipMemcpyHostToDevice, c->copy));
         if (nchunk > 1) KVPR_HIP(hipEventRecord(c->ev_chunk[buf][j], c->copy));
     }
     KVPR_HIP(hipEventRecord(c->ev_x[buf], c->copy));
     if (ev) KVPR_HIP(hipEventRecord(ev->c_x, c->copy));
     if (l < seq)
-        KVPR_HIP(hipMemcpyAsync(dkv + (size_t)l * kr, c->hkv[layer] + (size_t)l * kr,
-                                (size_t)(seq - l) * kr * sizeof(half), hipMemcpyHostToDevice, c->copy));
+        KVPR_HIP(hipMemcpyAsync(kv_stage + (size_t)l * ksb, c->hkv[layer] + (size_t)l * ksb, (size_t)(seq - l) * ksb,
+                                hipMemcpyHostToDevice, c->copy));
     KVPR_HIP(hipEventRecord(c->ev_kv[buf], c->copy));
     if (ev) KVPR_HIP(hipEventRecord(ev->c_kv, c->copy));
     if (int rc = debug_sync(c)) return rc;
@@ -177,15 +191,20 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
         if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->q32, dkv + (size_t)seq * kr, b, 3 * h, h, h,
                                                    2 * (int64_t)h, 0, c->compute))
             return rc;
+        // a compressed store receives the new rows packed (Sec. 4.4); attention below still reads the exact row
+        if (c->qkv)
+            if (int rc = kvpr::launch_quant_int4(dkv + (size_t)seq * kr, kv_stage + (size_t)seq * ksb, b, 2 * h, c->compute)) return rc;
+        if (c->qx)
+            if (int rc = kvpr::launch_quant_int4(x_new, x_stage + (size_t)seq * xsb, b, h, c->compute)) return rc;
         KVPR_HIP(hipEventRecord(c->ev_proj, c->compute));
         if (ev) KVPR_HIP(hipEventRecord(ev->p1, c->compute));
         // store stream: write the new rows back to the host store
         KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_proj, 0));
         if (ev) KVPR_HIP(hipEventRecord(ev->s0, c->store));
-        KVPR_HIP(hipMemcpyAsync(c->hkv[layer] + (size_t)seq * kr, dkv + (size_t)seq * kr, kr * sizeof(half),
-                                hipMemcpyDeviceToHost, c->store));
-        KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xr, x_new, xr * sizeof(half), hipMemcpyDeviceToHost,
+        KVPR_HIP(hipMemcpyAsync(c->hkv[layer] + (size_t)seq * ksb, kv_stage + (size_t)seq * ksb, ksb, hipMemcpyDeviceToHost,
                                 c->store));
+        KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xsb, c->qx ? (const void*)(x_stage + (size_t)seq * xsb) : (const void*)x_new,
+                                xsb, hipMemcpyDeviceToHost, c->store));
         KVPR_HIP(hipEventRecord(c->ev_store, c->store));
         if (ev) KVPR_HIP(hipEventRecord(ev->s1, c->store));
         return debug_sync(c);
@@ -202,6 +221,9 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
                 // with several chunks the GEMM of chunk j runs while chunks j+1.. and the cache are still on the link
                 if (nchunk > 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_chunk[buf][j], 0));
                 const int64_t rows = (int64_t)(bound[j + 1] - bound[j]) * b;
+                if (c->qx)
+                    if (int rc = kvpr::launch_dequant_int4(x_stage + (size_t)bound[j] * xsb, dx + (size_t)bound[j] * xr, rows, h, c->compute))
+                        return rc;
                 if (int rc = kvpr::launch_gemm(dx + (size_t)bound[j] * xr, wkv, bkv, dkv + (size_t)bound[j] * kr, rows, 2 * h,
                                                h, 2 * (int64_t)h, c->compute))
                     return rc;
@@ -223,6 +245,10 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
 
     // ---- merge = wait for the transferred rows; then attention over all seq+1 rows (Eq. 2) ----
     KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_kv[buf], 0));
+    if (ev) KVPR_HIP(hipEventRecord(ev->d0, c->compute));
+    if (c->qkv && l < seq)
+        if (int rc = kvpr::launch_dequant_int4(kv_stage + (size_t)l * ksb, dkv + (size_t)l * kr, (int64_t)(seq - l) * b, 2 * h, c->compute))
+            return rc;
     if (ev) KVPR_HIP(hipEventRecord(ev->a0, c->compute));
     if (int rc = kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, seq + 1, b, h, c->d.n_heads, c->compute))
         return rc;
@@ -249,7 +275,7 @@ int read_timing(kvpr_ctx* c, LayerEvents* ev, int seq, int l, kvpr_layer_timing*
         return KVPR_OK;
     };
     kvpr_layer_timing r{};
-    float to_gemm = 0.f, to_kv = 0.f;
+    float to_gemm = 0.f, to_kv = 0.f, to_deq = 0.f;
     if (int rc = ms(ev->c0, ev->c_x, &r.ms_act_copy)) return rc;
     if (int rc = ms(ev->c_x, ev->c_kv, &r.ms_kv_copy)) return rc;
     if (int rc = ms(ev->r0, ev->r1, &r.ms_recompute)) return rc;
@@ -260,15 +286,15 @@ int read_timing(kvpr_ctx* c, LayerEvents* ev, int seq, int l, kvpr_layer_timing*
     if (int rc = ms(ev->start, ev->r1, &to_gemm)) return rc;
     if (int rc = ms(ev->start, ev->c_kv, &to_kv)) return rc;
     if (int rc = ms(ev->start, ev->end, &r.ms_total)) return rc;
-    r.ms_assemble = std::max(to_gemm, to_kv);
+    if (int rc = ms(ev->d0, ev->a0, &r.ms_dequant)) return rc;
+    if (int rc = ms(ev->start, ev->a0, &to_deq)) return rc;
+    // both halves resident as float16: with a compressed cache that is the end of its dequantisation
+    r.ms_assemble = (c->qkv && l < seq) ? to_deq : std::max(to_gemm, to_kv);
     r.split = l;
-    if (c->have_prof) {
-        if (c->chunks > 1 && c->cost_model == KVPR_COST_EQ10) {
-            if (int rc = kvpr_cost_chunked(&c->prof, c->chunks, l, c->d.batch, seq, c->d.hidden, 2, &r.t_bound_s)) return rc;
-        } else if (int rc = kvpr_cost(&c->prof, c->cost_model, l, c->d.batch, seq, c->d.hidden, 2, &r.t_bound_s)) {
+    if (c->have_prof)
+        if (int rc = kvpr_cost_linear(&c->prof, c->cost_model, c->plan_chunks(), l, seq, (int64_t)c->x_store_bytes(),
+                                      (int64_t)c->kv_store_bytes(), c->flops_per_pos(), &r.t_bound_s))
             return rc;
-        }
-    }
     *t = r;
     return KVPR_OK;
 }
@@ -301,6 +327,8 @@ void destroy_impl(kvpr_ctx* c) {
     for (int i = 0; i < 2; ++i) {
         if (c->dx[i]) (void)hipFree(c->dx[i]);
         if (c->dkv[i]) (void)hipFree(c->dkv[i]);
+        if (c->dxq[i]) (void)hipFree(c->dxq[i]);
+        if (c->dkvq[i]) (void)hipFree(c->dkvq[i]);
         if (c->ev_x[i]) (void)hipEventDestroy(c->ev_x[i]);
         if (c->ev_kv[i]) (void)hipEventDestroy(c->ev_kv[i]);
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
@@ -376,7 +404,8 @@ namespace {
 
 int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_stream, kvpr_ctx** out) {
     if (!d || !out) return fail(KVPR_E_INVAL, "desc / out is null");
-    if (d->dtype != KVPR_F16) return fail(KVPR_E_INVAL, "only KVPR_F16 is supported");
+    if ((d->dtype & ~KVPR_STORE_INT4) != KVPR_F16)
+        return fail(KVPR_E_INVAL, "dtype must be KVPR_F16, optionally with KVPR_KV_INT4 / KVPR_X_INT4");
     if (d->n_layers < 1 || d->batch < 1 || d->max_seq < 1) return fail(KVPR_E_RANGE, "n_layers, batch, max_seq must be >= 1");
     if (d->batch > 64) return fail(KVPR_E_RANGE, "batch %d > 64 is not supported by the token GEMM", d->batch);
     if (d->head_dim != 64 && d->head_dim != 128) return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
@@ -389,11 +418,14 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     if (!c) return fail(KVPR_E_NOMEM, "out of host memory");
     c->d = *d;
     c->nb = n_gpu_batches;
+    c->qx = (d->dtype & KVPR_X_INT4) != 0;
+    c->qkv = (d->dtype & KVPR_KV_INT4) != 0;
     c->compute = (hipStream_t)compute_stream;
     const int slots = c->slots();
     c->nbuf = slots > 1 ? 2 : 1;
     const size_t x_bytes = (size_t)d->max_seq * c->x_row_halfs() * sizeof(half);
     const size_t kv_bytes = 2 * x_bytes;
+    const size_t xs_bytes = (size_t)d->max_seq * c->x_store_bytes(), kvs_bytes = (size_t)d->max_seq * c->kv_store_bytes();
     auto bail = [&](int code, const char* what, hipError_t e) {
         int rc = fail(code, "%s: %s", what, hipGetErrorString(e));
         char keep[sizeof kvpr::g_err];
@@ -410,12 +442,14 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     c->x_rows.assign(slots, 0);
     c->kv_rows.assign(slots, 0);
     for (int i = 0; i < slots; ++i) {
-        if ((e = hipHostMalloc((void**)&c->hx[i], x_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned X store", e);
-        if ((e = hipHostMalloc((void**)&c->hkv[i], kv_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned KV store", e);
+        if ((e = hipHostMalloc((void**)&c->hx[i], xs_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned X store", e);
+        if ((e = hipHostMalloc((void**)&c->hkv[i], kvs_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned KV store", e);
     }
     for (int i = 0; i < c->nbuf; ++i) {
         if ((e = hipMalloc((void**)&c->dx[i], x_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "device X buffer", e);
         if ((e = hipMalloc((void**)&c->dkv[i], kv_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "device KV buffer", e);
+        if (c->qx && (e = hipMalloc((void**)&c->dxq[i], xs_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "device packed X buffer", e);
+        if (c->qkv && (e = hipMalloc((void**)&c->dkvq[i], kvs_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "device packed KV buffer", e);
     }
     for (int i = 0; i < 2; ++i) {
         if ((e = hipEventCreateWithFlags(&c->ev_x[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
@@ -486,6 +520,8 @@ extern "C" int kvpr_set_profile(kvpr_ctx* c, const kvpr_profile_t* p, int cost_m
     int32_t l;
     // validates the profile, the model and the granularity
     if (int rc = kvpr_plan_split(p, cost_model, c->d.batch, 1, c->d.hidden, 2, granularity, &l, nullptr)) return rc;
+    if (c->chunks > 1 && cost_model == KVPR_COST_EQ10)
+        if (int rc = kvpr_plan_split_chunked(p, c->chunks, c->d.batch, 1, c->d.hidden, 2, granularity, &l, nullptr)) return rc;
     c->prof = *p;
     c->cost_model = cost_model;
     c->granularity = granularity;
@@ -501,14 +537,34 @@ extern "C" int kvpr_store_write(kvpr_ctx* c, int layer, int t0, int t1, const vo
     KVPR_HIP(hipStreamSynchronize(c->copy));
     KVPR_HIP(hipStreamSynchronize(c->store));
     const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
-    if (x_host) {
-        memcpy(c->hx[layer] + (size_t)t0 * xr, x_host, (size_t)(t1 - t0) * xr * sizeof(half));
-        if (t0 <= c->x_rows[layer]) c->x_rows[layer] = std::max(c->x_rows[layer], t1);
+    const size_t xsb = c->x_store_bytes(), ksb = c->kv_store_bytes();
+    const size_t n = (size_t)(t1 - t0);
+    // an array kept compressed is packed on the GPU (one codec implementation): float16 rows up, packed rows down
+    auto write_packed = [&](const void* src, half* dev, char* stage, char* dst, size_t row_halfs, size_t row_store_bytes,
+                            int cols) -> int {
+        KVPR_HIP(hipDeviceSynchronize());
+        KVPR_HIP(hipMemcpy(dev, src, n * row_halfs * sizeof(half), hipMemcpyHostToDevice));
+        if (int rc = kvpr::launch_quant_int4(dev, stage, (int64_t)n * c->d.batch, cols, c->compute)) return rc;
+        KVPR_HIP(hipMemcpyAsync(dst, stage, n * row_store_bytes, hipMemcpyDeviceToHost, c->compute));
+        KVPR_HIP(hipStreamSynchronize(c->compute));
+        return KVPR_OK;
+    };
+    if (x_host && n > 0) {
+        if (c->qx) {
+            if (int rc = write_packed(x_host, c->dx[0], c->dxq[0], c->hx[layer] + (size_t)t0 * xsb, xr, xsb, c->d.hidden)) return rc;
+        } else {
+            memcpy(c->hx[layer] + (size_t)t0 * xsb, x_host, n * xsb);
+        }
     }
-    if (kv_host) {
-        memcpy(c->hkv[layer] + (size_t)t0 * kr, kv_host, (size_t)(t1 - t0) * kr * sizeof(half));
-        if (t0 <= c->kv_rows[layer]) c->kv_rows[layer] = std::max(c->kv_rows[layer], t1);
+    if (x_host && t0 <= c->x_rows[layer]) c->x_rows[layer] = std::max(c->x_rows[layer], t1);
+    if (kv_host && n > 0) {
+        if (c->qkv) {
+            if (int rc = write_packed(kv_host, c->dkv[0], c->dkvq[0], c->hkv[layer] + (size_t)t0 * ksb, kr, ksb, 2 * c->d.hidden)) return rc;
+        } else {
+            memcpy(c->hkv[layer] + (size_t)t0 * ksb, kv_host, n * ksb);
+        }
     }
+    if (kv_host && t0 <= c->kv_rows[layer]) c->kv_rows[layer] = std::max(c->kv_rows[layer], t1);
     return KVPR_OK;
 }
 
@@ -531,14 +587,20 @@ extern "C" int kvpr_store_prefill_kv(kvpr_ctx* c, int layer, int seq, const kvpr
     if (c->x_rows[layer] < seq) return fail(KVPR_E_STATE, "layer %d: only %d activation rows written", layer, c->x_rows[layer]);
     if (seq == 0) return KVPR_OK;
     const int h = c->d.hidden;
-    const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
+    const size_t xsb = c->x_store_bytes(), ksb = c->kv_store_bytes();
     KVPR_HIP(hipDeviceSynchronize());
-    KVPR_HIP(hipMemcpyAsync(c->dx[0], c->hx[layer], (size_t)seq * xr * sizeof(half), hipMemcpyHostToDevice, c->compute));
+    // the activations as the store returns them (dequantised if it keeps them packed)
+    KVPR_HIP(hipMemcpyAsync(c->qx ? (void*)c->dxq[0] : (void*)c->dx[0], c->hx[layer], (size_t)seq * xsb, hipMemcpyHostToDevice, c->compute));
+    if (c->qx)
+        if (int rc = kvpr::launch_dequant_int4(c->dxq[0], c->dx[0], (int64_t)seq * c->d.batch, h, c->compute)) return rc;
     const half* wkv = (const half*)w->wqkv + (size_t)h * h;
     const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
     if (int rc = kvpr::launch_gemm(c->dx[0], wkv, bkv, c->dkv[0], (int64_t)seq * c->d.batch, 2 * h, h, 2 * (int64_t)h, c->compute))
         return rc;
-    KVPR_HIP(hipMemcpyAsync(c->hkv[layer], c->dkv[0], (size_t)seq * kr * sizeof(half), hipMemcpyDeviceToHost, c->compute));
+    if (c->qkv)
+        if (int rc = kvpr::launch_quant_int4(c->dkv[0], c->dkvq[0], (int64_t)seq * c->d.batch, 2 * h, c->compute)) return rc;
+    KVPR_HIP(hipMemcpyAsync(c->hkv[layer], c->qkv ? (const void*)c->dkvq[0] : (const void*)c->dkv[0], (size_t)seq * ksb,
+                            hipMemcpyDeviceToHost, c->compute));
     KVPR_HIP(hipStreamSynchronize(c->compute));
     c->kv_rows[layer] = std::max(c->kv_rows[layer], seq);
     return KVPR_OK;
@@ -779,6 +841,28 @@ extern "C" int kvpr_token_gemm(const void* x, const void* w, const void* bias, v
     return kvpr::launch_token_gemm_flags(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, 0, (hipStream_t)stream);
 }
 
+extern "C" size_t kvpr_int4_row_bytes(int cols) {
+    if (cols < 64 || cols % 64) return 0;
+    return kvpr::int4_row_bytes(cols);
+}
+
+static int check_codec_args(const void* src, const void* dst, int64_t rows, int cols) {
+    if (rows < 0 || cols < 64 || cols % 64) return fail(KVPR_E_RANGE, "rows=%lld cols=%d: need rows >= 0 and cols a positive multiple of 64", (long long)rows, cols);
+    if (rows * (int64_t)(cols / 8) > ((int64_t)1 << 38)) return fail(KVPR_E_RANGE, "rows * cols too large");
+    if (rows > 0 && (!src || !dst)) return fail(KVPR_E_INVAL, "src / dst is null");
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_quant_int4(const void* src, void* dst, int64_t rows, int cols, void* stream) {
+    if (int rc = check_codec_args(src, dst, rows, cols)) return rc;
+    return kvpr::launch_quant_int4(src, dst, rows, cols, (hipStream_t)stream);
+}
+
+extern "C" int kvpr_dequant_int4(const void* src, void* dst, int64_t rows, int cols, void* stream) {
+    if (int rc = check_codec_args(src, dst, rows, cols)) return rc;
+    return kvpr::launch_dequant_int4(src, dst, rows, cols, (hipStream_t)stream);
+}
+
 // ---- profiler (Sec. 3.1) ----
 namespace {
 
@@ -815,29 +899,31 @@ extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out
     if (rows > (int64_t)c->d.batch * (c->d.max_seq - 1))
         return fail(KVPR_E_RANGE, "batch*seq = %lld exceeds the context's batch*(max_seq-1)", (long long)rows);
     const int h = c->d.hidden;
-    const size_t kv_bytes = (size_t)rows * 2 * h * sizeof(half);
-    const size_t cap_bytes = (size_t)c->d.max_seq * c->kv_row_halfs() * sizeof(half);
+    // the link is measured on what a full cache copy of [seq, batch] moves: packed rows if the store keeps them packed
+    const size_t kv_bytes = c->qkv ? (size_t)rows * kvpr::int4_row_bytes(2 * h) : (size_t)rows * 2 * h * sizeof(half);
+    const size_t cap_bytes = (size_t)c->d.max_seq * c->kv_store_bytes();
     KVPR_HIP(hipDeviceSynchronize());
     kvpr_profile_t p{};
     double t = 0;
-    half* hkv = c->hkv[0];
+    char* hkv = c->hkv[0];
     half* dkv = c->dkv[0];
+    char* kv_stage = c->qkv ? c->dkvq[0] : (char*)dkv;
 
     // v_com: one pinned copy of the size of the whole cache of [seq, batch]
     if (int rc = time_median(c->copy, 5, [&]() -> int {
-            KVPR_HIP(hipMemcpyAsync(dkv, hkv, kv_bytes, hipMemcpyHostToDevice, c->copy));
+            KVPR_HIP(hipMemcpyAsync(kv_stage, hkv, kv_bytes, hipMemcpyHostToDevice, c->copy));
             return KVPR_OK; }, &t)) return rc;
     p.h2d_bytes_per_s = (double)kv_bytes / t;
     // d2h: the same bytes back to where they came from (the store keeps its contents)
     if (int rc = time_median(c->store, 3, [&]() -> int {
-            KVPR_HIP(hipMemcpyAsync(hkv, dkv, kv_bytes, hipMemcpyDeviceToHost, c->store));
+            KVPR_HIP(hipMemcpyAsync(hkv, kv_stage, kv_bytes, hipMemcpyDeviceToHost, c->store));
             return KVPR_OK; }, &t)) return rc;
     p.d2h_bytes_per_s = (double)kv_bytes / t;
     // best H2D rate over a size sweep
     p.h2d_peak_bytes_per_s = p.h2d_bytes_per_s;
     for (size_t sz = (size_t)64 << 10; sz <= std::min(cap_bytes, (size_t)1 << 30); sz *= 4) {
         if (int rc = time_median(c->copy, 5, [&]() -> int {
-                KVPR_HIP(hipMemcpyAsync(dkv, hkv, sz, hipMemcpyHostToDevice, c->copy));
+                KVPR_HIP(hipMemcpyAsync(kv_stage, hkv, sz, hipMemcpyHostToDevice, c->copy));
                 return KVPR_OK; }, &t)) return rc;
         p.h2d_peak_bytes_per_s = std::max(p.h2d_peak_bytes_per_s, (double)sz / t);
     }

@@ -33,6 +33,9 @@ int launch_fill_random(void* p, size_t n_halfs, float scale, uint32_t seed, hipS
 int launch_layernorm(const void* x, const void* g, const void* b, void* y, int rows, int h, hipStream_t st);
 int launch_argmax_rows(const float* logits, int M, int N, int32_t* out, hipStream_t st);
 int launch_gather_rows(const void* table, const int32_t* idx, void* out, int M, int h, hipStream_t st);
+size_t int4_row_bytes(int cols);
+int launch_quant_int4(const void* src, void* dst, int64_t rows, int cols, hipStream_t st);
+int launch_dequant_int4(const void* src, void* dst, int64_t rows, int cols, hipStream_t st);
 int launch_add(const void* a, const void* b, void* y, size_t n, hipStream_t st);
 
 }  // namespace kvpr

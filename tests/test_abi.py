@@ -78,6 +78,38 @@ def test_chunked_planner_bit_exact_against_oracle(k):
     assert e.value.code == k.KVPR_E_RANGE
 
 
+def test_linear_planner_bit_exact_against_oracle(k):
+    """Per-position sizes (Eq. 6 / Eq. 8 as rates): the paper's, and those of a 4-bit store (Sec. 4.4)."""
+    from oracle import kvpr_int4_oracle as qo
+    for b, s, h, v_com, v_gpu in [(32, 1024, 4096, 57.3e9, 1.05e15), (1, 128, 768, 20e9, 3e13), (16, 4096, 7168, 55e9, 9e14),
+                                  (4, 37, 256, 1e9, 5e11)]:
+        sizes = [(b * h * 2, 2 * b * h * 2), (b * qo.packed_bytes(h), b * qo.packed_bytes(2 * h)),
+                 (b * h * 2, b * qo.packed_bytes(2 * h)), (0, 17)]
+        assert k.kvpr_int4_row_bytes(h) == qo.packed_bytes(h) and k.kvpr_int4_row_bytes(2 * h) == qo.packed_bytes(2 * h)
+        fp = 4 * b * h * h
+        for lat in ((0.0, 0.0), (2e-5, 1e-5)):
+            prof = k.make_profile(v_com, v_gpu, *lat)
+            for xb, kb in sizes:
+                for model, _ in MODELS:
+                    for chunks in ((1, 3) if model == po.COST_EQ10 else (1,)):
+                        for g in (1, 8):
+                            want = po.plan_split_linear(model, chunks, s, xb, kb, fp, v_com, v_gpu, g, *lat)
+                            assert k.kvpr_plan_split_linear(prof, model, chunks, s, xb, kb, fp, g) == want
+                        for l in {0, 1, s // 2, s}:
+                            assert k.kvpr_cost_linear(prof, model, chunks, l, s, xb, kb, fp) == \
+                                po.cost_linear(model, chunks, l, s, xb, kb, fp, v_com, v_gpu, *lat)
+            # the paper's sizes through the linear entry point are kvpr_plan_split itself
+            assert k.kvpr_plan_split_linear(prof, 0, 1, s, b * h * 2, 2 * b * h * 2, fp, 1) == k.kvpr_plan_split(prof, 0, b, s, h, 2, 1)
+    good = k.make_profile(1e9, 1e12)
+    for args, code in (((0, 1, 8, -1, 4, 4, 1), k.KVPR_E_RANGE), ((0, 0, 8, 2, 4, 4, 1), k.KVPR_E_RANGE),
+                       ((1, 2, 8, 2, 4, 4, 1), k.KVPR_E_INVAL), ((0, 1, 8, 2, 4, 4, 0), k.KVPR_E_RANGE),
+                       ((0, 1, 8, 2 ** 60, 4, 4, 1), k.KVPR_E_RANGE)):
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_plan_split_linear(good, *args)
+        assert e.value.code == code, args
+    assert k.kvpr_int4_row_bytes(100) == 0 and k.kvpr_int4_row_bytes(0) == 0
+
+
 def test_planner_rejects_bad_arguments(k):
     good = k.make_profile(1e9, 1e12)
     for prof in (k.make_profile(0.0, 1e12), k.make_profile(1e9, -1.0), k.make_profile(float("nan"), 1e12),
@@ -116,11 +148,18 @@ def test_kernel_entry_points_validate_before_touching_the_gpu(k):
         k.kvpr_token_gemm(1, 1, None, 1, 1, 65, 64, 128, 0, 64, stream=0)     # M > 64
     assert e.value.code == k.KVPR_E_RANGE
     assert k.kvpr_attention_workspace_bytes(32, 4096, 32, 1025) > 0
+    for fn in (k.kvpr_quant_int4, k.kvpr_dequant_int4):
+        with pytest.raises(k.KvprError) as e:
+            fn(1, 1, 4, 100, stream=0)                                         # cols % 64
+        assert e.value.code == k.KVPR_E_RANGE
+        with pytest.raises(k.KvprError) as e:
+            fn(None, 1, 4, 128, stream=0)
+        assert e.value.code == k.KVPR_E_INVAL
 
 
 def test_create_rejects_bad_descriptions(k):
     bad = [dict(hidden=768, n_heads=12, head_dim=32), dict(hidden=768, n_heads=11, head_dim=64),
-           dict(hidden=96 * 2, n_heads=2, head_dim=96), dict(dtype=7), dict(ffn_dim=100)]
+           dict(hidden=96 * 2, n_heads=2, head_dim=96), dict(dtype=7), dict(dtype=0x100), dict(dtype=0x401), dict(ffn_dim=100)]
     base = dict(n_layers=1, hidden=768, n_heads=12, head_dim=64, ffn_dim=0, batch=1, max_seq=16, dtype=k.KVPR_F16)
     for upd in bad:
         kw = dict(base, **upd)

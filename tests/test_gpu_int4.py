@@ -1,0 +1,254 @@
+"""GPU parity of the group-wise 4-bit host store (Sec. 4.4): the codec kernels bit for bit against the
+oracle's codec, then the layer decode, the decoder stack and the column schedule over a compressed store."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import kvpr_inputs
+from oracle import kvpr_int4_oracle as qo
+from oracle import kvpr_oracle as ko
+from oracle import kvpr_plan_oracle as po
+from kvpr_testlib import dev, rel_err, upload_layer
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def k():
+    import paper_2411_17089_amd as k
+    return k
+
+
+def _codec_inputs(seed, rows, cols):
+    rng = np.random.default_rng(seed)
+    a = (rng.standard_normal((rows, cols)) * rng.choice([1e-3, 0.05, 1.0, 30.0], (rows, 1))).astype(np.float16)
+    if rows >= 4:
+        a[0, :64] = np.float16(0.37)                      # constant group: scale 0
+        a[1, :64] = np.tile(np.arange(16), 4)             # integers 0..15: exact
+        a[2, :64] = np.linspace(-60000, 60000, 64)        # widest span float16 allows
+        a[3, :64] = np.float16(1.0) + np.arange(64) * np.float16(2 ** -10)   # span of a few ulps
+    return a
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 64), (7, 256), (33, 768), (96, 1536), (1027, 8192), (0, 128)])
+def test_codec_kernels_bit_exact(k, rows, cols):
+    print(f"codec rows={rows} cols={cols}", flush=True)
+    pb = k.kvpr_int4_row_bytes(cols)
+    assert pb == qo.packed_bytes(cols)
+    a = _codec_inputs(rows * 131 + cols, rows, cols)
+    src = dev(a) if rows else torch.empty((0, cols), dtype=torch.float16, device="cuda")
+    packed = torch.full((max(rows, 1), pb), 0xAB, dtype=torch.uint8, device="cuda")
+    k.kvpr_quant_int4(src, packed, rows, cols)
+    torch.cuda.synchronize()
+    if rows == 0:
+        assert (packed.cpu().numpy() == 0xAB).all()
+        return
+    codes, scale, mn = qo.quantize_rows(a)
+    want = qo.pack_rows(codes, scale, mn)
+    got = packed.cpu().numpy()
+    assert np.array_equal(got, want), np.argwhere(got != want)[:5]
+    back = torch.empty((rows, cols), dtype=torch.float16, device="cuda")
+    k.kvpr_dequant_int4(packed, back, rows, cols)
+    torch.cuda.synchronize()
+    want_back = qo.dequantize_rows(codes, scale, mn)
+    assert np.array_equal(back.cpu().numpy().view(np.uint16), want_back.view(np.uint16))
+
+
+class QRig:
+    """One attention layer over a compressed store plus the oracle-side data."""
+
+    def __init__(self, k, seed, b, s, h, H, flags, max_seq=None):
+        self.k, self.b, self.s, self.h, self.H, self.flags = k, b, s, h, H, flags
+        self.qx, self.qkv = bool(flags & k.KVPR_X_INT4), bool(flags & k.KVPR_KV_INT4)
+        self.layer = kvpr_inputs.make_layer(seed, b, s, h, H)
+        self.stored = ko.stored_kv(self.layer, "fp16").astype(np.float16)
+        self.d = upload_layer(self.layer)
+        self.w = k.make_weights(wqkv=self.d["wqkv"], bqkv=self.d["bqkv"], wo=self.d["wo"], bo=self.d["bo"])
+        self.max_seq = max_seq or s + 2
+        self.ctx = k.kvpr_create(1, h, H, h // H, 0, b, self.max_seq, dtype=k.KVPR_F16 | flags)
+        k.kvpr_store_write(self.ctx, 0, 0, s, np.ascontiguousarray(self.layer["X"]), np.ascontiguousarray(self.stored))
+        self.out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+
+    def oracle(self, l):
+        kv = qo.roundtrip(self.stored).astype(np.float64) if self.qkv else self.stored.astype(np.float64)
+        lay = dict(self.layer)
+        if self.qx:
+            lay["X"] = qo.roundtrip(self.layer["X"]).astype(np.float64)
+        return ko.layer_decode(lay, l, kv)
+
+    def decode(self, l, timing=False):
+        t = self.k.kvpr_layer_decode(self.ctx, 0, self.s, l, self.w, self.d["x_new"], self.out, timing)
+        torch.cuda.synchronize()
+        return self.out.cpu().numpy().copy(), t
+
+    def host_bytes(self):
+        """The store's two arrays as raw bytes [max_seq, b, bytes per sequence row]."""
+        xp, kvp = self.k.kvpr_store_ptrs(self.ctx, 0)
+        xb = self.k.kvpr_int4_row_bytes(self.h) if self.qx else 2 * self.h
+        kb = self.k.kvpr_int4_row_bytes(2 * self.h) if self.qkv else 4 * self.h
+        x = np.ctypeslib.as_array(ctypes.cast(xp, ctypes.POINTER(ctypes.c_uint8)), (self.max_seq * self.b * xb,))
+        kv = np.ctypeslib.as_array(ctypes.cast(kvp, ctypes.POINTER(ctypes.c_uint8)), (self.max_seq * self.b * kb,))
+        return x.reshape(self.max_seq, self.b, xb), kv.reshape(self.max_seq, self.b, kb)
+
+    def close(self):
+        self.k.kvpr_destroy(self.ctx)
+
+
+@pytest.mark.parametrize("flagname", ["KVPR_STORE_INT4", "KVPR_KV_INT4", "KVPR_X_INT4"])
+@pytest.mark.parametrize("seed,b,s,h,H", [(11, 3, 77, 256, 2), (12, 32, 40, 512, 4), (13, 2, 130, 768, 12)])
+def test_layer_decode_over_compressed_store(k, flagname, seed, b, s, h, H):
+    flags = getattr(k, flagname)
+    rig = QRig(k, seed, b, s, h, H, flags)
+    try:
+        # what store_write left on the host is the oracle's packed form of the float16 rows, bit for bit
+        xb, kvb = rig.host_bytes()
+        if rig.qx:
+            assert np.array_equal(xb[:s], qo.pack_rows(*qo.quantize_rows(rig.layer["X"])))
+        else:
+            assert np.array_equal(xb[:s].view(np.float16), rig.layer["X"])
+        if rig.qkv:
+            assert np.array_equal(kvb[:s], qo.pack_rows(*qo.quantize_rows(rig.stored)))
+        else:
+            assert np.array_equal(kvb[:s].view(np.float16), rig.stored)
+        exact = ko.layer_decode(rig.layer, 0)["o"]
+        for l in sorted({0, 1, 8, s // 2, s - 1, s}):
+            print(f"int4 {flagname} b={b} s={s} h={h} split {l}", flush=True)
+            ref = rig.oracle(l)
+            o, _ = rig.decode(l)
+            assert np.isfinite(o).all()
+            assert rel_err(o, ref["o"]) <= TOL, l
+            assert rel_err(o, exact) <= 0.1, l                    # and still close to the uncompressed result
+        # store-back: the new activation row is packed from exact inputs -> bit-exact; the new cache row is packed
+        # from the GPU's own float16 row, which may differ from the oracle's by an ulp -> compare values
+        xb, kvb = rig.host_bytes()
+        ref = rig.oracle(0)
+        if rig.qx:
+            assert np.array_equal(xb[s], qo.pack_rows(*qo.quantize_rows(rig.layer["x_new"])))
+        else:
+            assert np.array_equal(xb[s].view(np.float16), rig.layer["x_new"])
+        if rig.qkv:
+            got_row = qo.dequantize_rows(*qo.unpack_rows(kvb[s], 2 * h)).astype(np.float64)
+            _, sc, _ = qo.quantize_rows(ref["kv"][s].astype(np.float16))
+            step = np.repeat(sc.astype(np.float64), 64, axis=-1)
+            assert np.all(np.abs(got_row - ref["kv"][s]) <= 0.51 * step + 4e-3 * np.abs(ref["kv"][s]) + 1e-3)
+        else:
+            assert rel_err(kvb[s].view(np.float16), ref["kv"][s]) <= 2e-3
+    finally:
+        rig.close()
+
+
+def test_two_steps_debug_modes_planned_split_and_timing(k):
+    b, s, h, H = 4, 64, 256, 2
+    rig = QRig(k, 21, b, s, h, H, k.KVPR_STORE_INT4, max_seq=s + 3)
+    try:
+        base, tim = rig.decode(24, timing=True)
+        assert tim.split == 24 and tim.ms_dequant > 0 and tim.ms_total >= tim.ms_attn
+        for flags in (k.KVPR_DEBUG_SYNC, k.KVPR_DEBUG_POISON, k.KVPR_DEBUG_POISON | k.KVPR_DEBUG_SYNC):
+            k.kvpr_set_debug(rig.ctx, flags)
+            o, _ = rig.decode(24)
+            assert np.array_equal(o, base), flags
+        k.kvpr_set_debug(rig.ctx, 0)
+        # the planner sees the compressed byte rates: bytes per position of the whole batch
+        v_com, v_gpu = 2.0e9, 4.0e12
+        k.kvpr_set_profile(rig.ctx, k.make_profile(v_com, v_gpu), k.KVPR_COST_EQ10, 8)
+        want, t_want = po.plan_split_linear(po.COST_EQ10, 1, s, b * qo.packed_bytes(h), b * qo.packed_bytes(2 * h),
+                                            4 * b * h * h, v_com, v_gpu, 8)
+        _, tim = rig.decode(-1, timing=True)
+        assert tim.split == want and tim.t_bound_s == t_want and 0 < want < s
+        # second token: the store now holds s + 1 packed rows, the last one written by the first step
+        x2 = kvpr_inputs._draw(np.random.default_rng(77), (b, h), 1.0)
+        first = rig.oracle(0)
+        kv_all = np.concatenate([rig.stored.astype(np.float64), ko.round_fp16(first["kv"][s:s + 1])], 0)
+        lay2 = dict(rig.layer, X=qo.roundtrip(np.concatenate([rig.layer["X"], rig.layer["x_new"][None]], 0)).astype(np.float64),
+                    x_new=x2)
+        for l in (0, 30, s + 1):
+            ref = ko.layer_decode(lay2, l, qo.roundtrip(kv_all.astype(np.float16)).astype(np.float64))["o"]
+            k.kvpr_layer_decode(rig.ctx, 0, s + 1, l, rig.w, dev(x2), rig.out, False)
+            torch.cuda.synchronize()
+            assert rel_err(rig.out.cpu().numpy(), ref) <= TOL, l
+    finally:
+        rig.close()
+
+
+def test_prefill_helper_and_profile_on_compressed_store(k):
+    b, s, h, H = 8, 48, 256, 4
+    rig = QRig(k, 31, b, s, h, H, k.KVPR_STORE_INT4, max_seq=s + 2)
+    try:
+        # prefill stand-in: K/V from the activations the store returns, packed on the way back
+        k.kvpr_store_prefill_kv(rig.ctx, 0, s, rig.w)
+        lay = dict(rig.layer, X=qo.roundtrip(rig.layer["X"]).astype(np.float64))
+        want = ko.stored_kv(lay, "fp16")
+        _, kvb = rig.host_bytes()
+        got = qo.dequantize_rows(*qo.unpack_rows(kvb[:s], 2 * h)).astype(np.float64)
+        _, sc, _ = qo.quantize_rows(want.astype(np.float16))
+        step = np.repeat(sc.astype(np.float64), 64, axis=-1)
+        assert np.all(np.abs(got - want) <= 0.51 * step + 4e-3 * np.abs(want) + 1e-3)
+        p = k.kvpr_profile(rig.ctx, b, s)
+        assert p.h2d_bytes_per_s > 1e8 and p.gemm_flops_per_s > 1e10 and p.d2h_bytes_per_s > 1e8
+    finally:
+        rig.close()
+
+
+def test_decoder_stack_and_columns_over_compressed_store(k):
+    n_layers, nb, b, s, h, H, ffn = 3, 2, 4, 40, 256, 2, 1024
+    params, layers, stored = [], [], []
+    for j in range(n_layers):
+        P = kvpr_inputs.make_layer(500 + j, b, 1, h, H)
+        P.update(kvpr_inputs.make_ffn(500 + j, h, ffn))
+        params.append(P)
+        layers.append([dict(P, X=kvpr_inputs._draw(np.random.default_rng([500, j, q]), (s, b, h), 1.0)) for q in range(nb)])
+        stored.append([ko.stored_kv(layers[j][q], "fp16").astype(np.float16) for q in range(nb)])
+    x_in = kvpr_inputs._draw(np.random.default_rng(499), (nb, b, h), 1.0)
+
+    def oracle(q, splits):
+        ls = [dict(layers[j][q], X=qo.roundtrip(layers[j][q]["X"]).astype(np.float64)) for j in range(n_layers)]
+        st = [qo.roundtrip(stored[j][q]).astype(np.float64) for j in range(n_layers)]
+        return ko.decoder_stack_decode(ls, x_in[q], splits, st)[0]
+
+    # row-by-row stack (resident weights), batch q = 0
+    ctx = k.kvpr_create(n_layers, h, H, h // H, ffn, b, s + 2, dtype=k.KVPR_F16 | k.KVPR_STORE_INT4)
+    try:
+        keep, ws = [], []
+        for j in range(n_layers):
+            d = upload_layer(params[j])
+            keep.append(d)
+            ws.append(k.make_weights(**{n: d[n] for n in ("wqkv", "bqkv", "wo", "bo", "ln1_g", "ln1_b", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")}))
+            k.kvpr_store_write(ctx, j, 0, s, np.ascontiguousarray(layers[j][0]["X"]), stored[j][0])
+        out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+        for splits in ([0, 0, 0], [s, s, s], [7, 25, 40]):
+            print(f"int4 stack splits={splits}", flush=True)
+            k.kvpr_decode_step(ctx, s, ws, dev(x_in[0]), out, splits)
+            torch.cuda.synchronize()
+            assert rel_err(out.cpu().numpy(), oracle(0, splits)) <= TOL
+    finally:
+        k.kvpr_destroy(ctx)
+
+    # column-by-column schedule with offloaded weights
+    ctx = k.kvpr_create_offload(n_layers, h, H, h // H, ffn, b, s + 2, nb, dtype=k.KVPR_F16 | k.KVPR_STORE_INT4)
+    try:
+        keep = []
+        for j in range(n_layers):
+            L = params[j]
+            arrs = {
+                "wqkv": np.concatenate([L["Wq"].T, L["Wk"].T, L["Wv"].T], 0), "bqkv": np.concatenate([L["bq"], L["bk"], L["bv"]]),
+                "wo": L["Wo"].T, "bo": L["bo"], "w1": L["W1"].T, "b1": L["b1"], "w2": L["W2"].T, "b2": L["b2"],
+                "ln1_g": L["ln1_g"], "ln1_b": L["ln1_b"], "ln2_g": L["ln2_g"], "ln2_b": L["ln2_b"],
+            }
+            arrs = {n: np.ascontiguousarray(a, dtype=np.float16) for n, a in arrs.items()}
+            keep.append(arrs)
+            k.kvpr_weights_write(ctx, j, k.make_weights(**arrs))
+            for q in range(nb):
+                k.kvpr_store_write(ctx, j * nb + q, 0, s, np.ascontiguousarray(layers[j][q]["X"]), stored[j][q])
+        x_out = torch.empty((nb, b, h), dtype=torch.float16, device="cuda")
+        splits = [5, 40, 0, 16, 33, 24]
+        print(f"int4 columns splits={splits}", flush=True)
+        k.kvpr_decode_step_columns(ctx, s, n_layers * nb, dev(x_in), x_out, splits)
+        torch.cuda.synchronize()
+        got = x_out.cpu().numpy()
+        for q in range(nb):
+            assert rel_err(got[q], oracle(q, [splits[j * nb + q] for j in range(n_layers)])) <= TOL, q
+    finally:
+        k.kvpr_destroy(ctx)
