@@ -53,6 +53,14 @@ def cpu_baseline(layer, n_seq: int):
     return r["o"], dt, min(threads, len(os.sched_getaffinity(0)))
 
 
+def store_sizes(k, mode, b, h):
+    """(dtype flags, bytes of X per cached position, bytes of KV per cached position) for --store-int4."""
+    q = {"none": 0, "kv": k.KVPR_KV_INT4, "both": k.KVPR_STORE_INT4}[mode]
+    x_bpp = b * (k.kvpr_int4_row_bytes(h) if q & k.KVPR_X_INT4 else 2 * h)
+    kv_bpp = b * (k.kvpr_int4_row_bytes(2 * h) if q & k.KVPR_KV_INT4 else 4 * h)
+    return q, x_bpp, kv_bpp
+
+
 def run_stack(args):
     """Layer-pipelined decode of a whole OPT-shaped stack (default OPT-13B: 40 layers, batch 32,
     prompt 1024, 32 greedy tokens).  Weights are random-init on the GPU, every layer's X and KV
@@ -66,7 +74,8 @@ def run_stack(args):
     torch.manual_seed(0)
     rnd = lambda shape, sc: (torch.randn(shape, device="cuda", dtype=torch.float32) * sc).half()
     t0 = time.perf_counter()
-    ctx = k.kvpr_create(L, h, H, d, ffn, b, s + gen + args.warmup + 2)
+    qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
+    ctx = k.kvpr_create(L, h, H, d, ffn, b, s + gen + args.warmup + 2, dtype=k.KVPR_F16 | qflags)
     keep, ws = [], []
     for i in range(L):
         t = dict(wqkv=rnd((3 * h, h), 0.02), bqkv=rnd((3 * h,), 0.01), wo=rnd((h, h), 0.02), bo=rnd((h,), 0.01),
@@ -109,7 +118,7 @@ def run_stack(args):
     _, tim = k.kvpr_decode_step(ctx, seq, ws, x, x_out, None, timing=True)
     tmean = lambda name: float(np.mean([getattr(t, name) for t in tim[2:]]))
     breakdown = {n: tmean("ms_" + n) for n in ("act_copy", "kv_copy", "recompute", "proj", "attn", "out", "store", "total")}
-    link_bytes = sum(b * h * 2.0 * (l + 2 * (s + args.warmup + i - l)) for i, l in enumerate(all_splits)) * L
+    link_bytes = float(sum(x_bpp * l + kv_bpp * (s + args.warmup + i - l) for i, l in enumerate(all_splits)) * L)
     result = {
         "metric": "decode_tokens_per_s_layer_pipelined_stack", "value": b * gen / wall, "unit": "tokens/s",
         "n_gpus": 1, "steps": gen, "warmup": args.warmup, "ms_per_step": wall * 1e3 / gen, "higher_is_better": True,
@@ -117,13 +126,14 @@ def run_stack(args):
         "data": "synthetic (random-init weights and N(0,1) activations generated on the GPU, seed 0)",
         "config": {"workload": f"{args.model}-shaped stack, {L} layers, hidden {h}, batch {b}, prompt {s}, {gen} greedy tokens, "
                                f"vocab {vocab}, X and KV of every layer in pinned host memory", "cost_model": args.cost_model,
-                   "granularity": args.granularity, "splits_first_last": [all_splits[0], all_splits[-1]]},
+                   "granularity": args.granularity, "splits_first_last": [all_splits[0], all_splits[-1]],
+                   "store_int4": args.store_int4},
         "ms_per_layer": wall * 1e3 / gen / L,
         "h2d_GBps_sustained": link_bytes / wall / 1e9, "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
         "h2d_frac_of_peak": link_bytes / wall / prof.h2d_peak_bytes_per_s,
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12},
         "breakdown_ms_per_layer": breakdown, "host_enqueue_ms_per_token": host_s * 1e3 / gen,
-        "pinned_store_GiB": L * (s + gen + args.warmup + 1) * b * 3 * h * 2 / 2 ** 30, "setup_s": setup_s,
+        "pinned_store_GiB": L * (s + gen + args.warmup + 2) * (x_bpp + kv_bpp) / 2 ** 30, "setup_s": setup_s,
     }
     k.kvpr_destroy(ctx)
     print(json.dumps(result))
@@ -142,7 +152,8 @@ def run_columns(args):
     cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
     rng = np.random.default_rng(0)
     torch.manual_seed(0)
-    ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + 2 * (gen + args.warmup) + 2, nb)
+    qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
+    ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + 2 * (gen + args.warmup) + 2, nb, dtype=k.KVPR_F16 | qflags)
     rh = lambda shape, sc: (rng.standard_normal(shape, dtype=np.float32) * np.float32(sc)).astype(np.float16)
     t0 = time.perf_counter()
     base = dict(wqkv=rh((3 * h, h), 0.02), bqkv=rh((3 * h,), 0.01), wo=rh((h, h), 0.02), bo=rh((h,), 0.01),
@@ -189,11 +200,11 @@ def run_columns(args):
         "data": "synthetic (seeded random weights and N(0,1) activations; cache = GPU prefill)",
         "config": {"workload": f"{args.model}-shaped stack, {L} layers, {nb} GPU batches x batch {b} (effective batch {nb * b}), "
                                f"context {s}, {gen} tokens, weights ({blob_bytes / 2**20:.0f} MiB/layer), X and KV in pinned host memory",
-                   "cost_model": args.cost_model, "granularity": args.granularity},
+                   "cost_model": args.cost_model, "granularity": args.granularity, "store_int4": args.store_int4},
         "kvpr": r, "no_recompute": results["no_recompute"],
         "speedup_over_no_recompute": results["no_recompute"]["ms_per_token_step"] / r["ms_per_token_step"],
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12},
-        "pinned_GiB": (S * (s + 2 * (gen + args.warmup) + 2) * b * 3 * h * 2 + L * blob_bytes) / 2 ** 30, "setup_s": setup_s,
+        "pinned_GiB": (S * (s + 2 * (gen + args.warmup) + 2) * (x_bpp + kv_bpp) + L * blob_bytes) / 2 ** 30, "setup_s": setup_s,
     }
     k.kvpr_destroy(ctx)
     print(json.dumps(out))
@@ -304,10 +315,8 @@ def main():
     w = k.make_weights(wqkv=wqkv, bqkv=bqkv, wo=wo, bo=bo)
     out = torch.empty((b, h), dtype=torch.float16, device="cuda")
 
-    qflags = {"none": 0, "kv": k.KVPR_KV_INT4, "both": k.KVPR_STORE_INT4}[args.store_int4]
     # bytes per cached position (whole batch) as they cross the link, flops per recomputed position (Eq. 6, Eq. 8)
-    x_bpp = b * (k.kvpr_int4_row_bytes(h) if qflags & k.KVPR_X_INT4 else 2 * h)
-    kv_bpp = b * (k.kvpr_int4_row_bytes(2 * h) if qflags & k.KVPR_KV_INT4 else 4 * h)
+    qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
     f_pp = 4 * b * h * h
     ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, dtype=k.KVPR_F16 | qflags)
     k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)

@@ -120,7 +120,7 @@ def test_layer_decode_over_compressed_store(k, flagname, seed, b, s, h, H):
             o, _ = rig.decode(l)
             assert np.isfinite(o).all()
             assert rel_err(o, ref["o"]) <= TOL, l
-            assert rel_err(o, exact) <= 0.1, l                    # and still close to the uncompressed result
+            assert rel_err(o, exact) <= 0.25, l                   # and still near the uncompressed result (4-bit noise)
         # store-back: the new activation row is packed from exact inputs -> bit-exact; the new cache row is packed
         # from the GPU's own float16 row, which may differ from the oracle's by an ulp -> compare values
         xb, kvb = rig.host_bytes()
