@@ -25,7 +25,11 @@ SHAPES = {
     "opt-6.7b": (4096, 32, 128),
     "opt-13b": (5120, 40, 128),
     "opt-30b": (7168, 56, 128),
+    "llama2-7b": (4096, 32, 128),
+    "llama2-13b": (5120, 40, 128),
 }
+# gated-FFN width of the LLaMA-2 shapes
+LLAMA_FFN = {"llama2-7b": 11008, "llama2-13b": 13824}
 
 
 def _draw(rng: np.random.Generator, shape, scale: float) -> np.ndarray:
@@ -64,4 +68,17 @@ def make_ffn(seed: int, h: int, ffn: int, w_scale: float = 0.02, b_scale: float 
         out[name] = (np.float32(1.0) + rng.standard_normal((h,), dtype=np.float32) * np.float32(0.05)).astype(np.float16)
     for name in ("ln1_b", "ln2_b"):
         out[name] = _draw(rng, (h,), 0.02)
+    return out
+
+
+def make_gated_ffn(seed: int, h: int, ffn: int, w_scale: float = 0.02) -> dict:
+    """Extra parameters of a LLaMA-style decoder layer: two RMSNorm gains and the gate / up / down
+    matrices of the gated FFN, in y = x . W orientation."""
+    rng = np.random.default_rng([seed, 0x11A3A])
+    out = {"ffn": ffn}
+    out["Wg"] = _draw(rng, (h, ffn), w_scale)
+    out["Wu"] = _draw(rng, (h, ffn), w_scale)
+    out["Wd"] = _draw(rng, (ffn, h), w_scale)
+    for name in ("ln1_g", "ln2_g"):
+        out[name] = (np.float32(1.0) + rng.standard_normal((h,), dtype=np.float32) * np.float32(0.05)).astype(np.float16)
     return out
