@@ -60,6 +60,15 @@ extern "C" {
 #define KVPR_X_INT4     0x200
 #define KVPR_STORE_INT4 (KVPR_KV_INT4 | KVPR_X_INT4)
 
+/* Layer family (kvpr_model_desc.arch).  OPT: biases, LayerNorm, two-matrix ReLU FFN (Eq. 4).
+ * LLAMA (the paper's LLaMA-2 experiments): no biases needed, RMSNorm, gated FFN
+ * down(silu(gate) * up), and rotary position embedding on q and k.  The cache holds K after the
+ * rotation, so the partial recomputation (Eq. 7) rotates every recomputed K row with its own
+ * position (row index / batch) and the decode token's q, k with position seq.  Pairing: element i
+ * of a head with element i + head_dim/2, angle p * rope_base^(-2i/head_dim). */
+#define KVPR_ARCH_OPT   0
+#define KVPR_ARCH_LLAMA 1
+
 /* Cost forms for the scheduler.  EQ10 is the paper's Eq. 10 (activations and cache
  * share one link, activations first).  ROW is Eq. 10 without its first term (the
  * paper's row-by-row case).  NS charges the activation copy to the compute arm only:
@@ -87,6 +96,8 @@ typedef struct {
     int32_t batch;      /* b >= 1                                                        */
     int32_t max_seq;    /* rows per layer in the host store and device buffers; a decode at seq cached positions needs seq + 1 <= max_seq */
     int32_t dtype;      /* KVPR_F16, optionally | KVPR_KV_INT4 | KVPR_X_INT4             */
+    int32_t arch;       /* KVPR_ARCH_OPT or KVPR_ARCH_LLAMA                              */
+    float rope_base;    /* KVPR_ARCH_LLAMA: base of the rotary angles; 0 = 10000         */
 } kvpr_model_desc;
 
 /* Profiler output (Sec. 3.1 "profiler module"): the two constants of Eq. 9 / Eq. 10
@@ -101,7 +112,9 @@ typedef struct {
     double h2d_peak_bytes_per_s; /* reported only: best rate over a 64 KiB .. 1 GiB sweep    */
 } kvpr_profile_t;
 
-/* Device pointers to one layer's parameters.  FFN / LayerNorm members may be null when ffn_dim == 0. */
+/* Device pointers to one layer's parameters.  FFN / LayerNorm members may be null when ffn_dim == 0.
+ * KVPR_ARCH_LLAMA: biases and ln*_b are ignored and may be null; ln*_g are the RMSNorm gains;
+ * w1 is [2*ffn, h] = the gate matrix's rows followed by the up matrix's rows; w2 [h, ffn] is the down matrix. */
 typedef struct {
     const void *wqkv, *bqkv;   /* [3h, h], [3h]                       (Eq. 1)  */
     const void *wo, *bo;       /* [h, h], [h]                         (Eq. 3)  */
@@ -262,6 +275,21 @@ size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S)
  * (used for q), the remaining N - out_f32_cols columns as float16 to y16_dev with row stride ld16. */
 int kvpr_token_gemm(const void* x_dev, const void* w_dev, const void* bias_dev, void* y32_dev, void* y16_dev,
                     int M, int N, int K, int out_f32_cols, int64_t ld16, void* stream);
+
+/* ---- rotary models (KVPR_ARCH_LLAMA), exposed for parity tests ----
+ * kvpr_rope_table: host arithmetic only.  out_host [n_pos, head_dim/2, 2] float32 = (cos, sin) of
+ * p * base^(-2i/head_dim), evaluated in double.  head_dim 64 or 128.
+ * kvpr_recompute_gemm_rope: kvpr_recompute_gemm with columns [0, rope_cols) (the K half, a multiple of
+ * 128) rotated in float32 before the float16 conversion; row r has position pos0 + r / batch, which
+ * must stay below n_pos (the table's rows).  table_dev is the device copy of kvpr_rope_table's output.
+ * kvpr_rope_token: qk32_dev float32 [batch, 2*hidden] = [q | k] of the decode token before rotation;
+ * writes the rotated q as float32 [batch, hidden] and the rotated k as float16 with row stride ldk. */
+int kvpr_rope_table(float* out_host, int n_pos, int head_dim, double base);
+int kvpr_recompute_gemm_rope(const void* a_dev, const void* w_dev, const void* bias_dev, void* c_dev, int64_t M, int N, int K,
+                             int64_t ldc, const void* table_dev, int n_pos, int rope_cols, int head_dim, int batch,
+                             int pos0, void* stream);
+int kvpr_rope_token(const void* qk32_dev, const void* table_dev, int n_pos, int pos, int batch, int hidden, int head_dim,
+                    void* q32_dev, void* k16_dev, int64_t ldk, void* stream);
 
 /* Group-wise 4-bit codec of the compressed store (Sec. 4.4; the paper fixes no format, this is the
  * library's): rows of `cols` float16 columns (cols % 64 == 0) in groups of 64 columns; per group

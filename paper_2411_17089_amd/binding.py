@@ -21,11 +21,12 @@ KVPR_F16 = 1
 KVPR_KV_INT4, KVPR_X_INT4, KVPR_STORE_INT4 = 0x100, 0x200, 0x300
 KVPR_COST_EQ10, KVPR_COST_NS, KVPR_COST_ROW, KVPR_COST_PIPE = 0, 1, 2, 3
 KVPR_DEBUG_SYNC, KVPR_DEBUG_POISON = 1, 2
+KVPR_ARCH_OPT, KVPR_ARCH_LLAMA = 0, 1
 
 
 class kvpr_model_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("n_layers", "hidden", "n_heads", "head_dim", "ffn_dim", "batch", "max_seq", "dtype")]
+                ("n_layers", "hidden", "n_heads", "head_dim", "ffn_dim", "batch", "max_seq", "dtype", "arch")] + [("rope_base", C.c_float)]
 
 
 class kvpr_profile_t(C.Structure):
@@ -55,7 +56,7 @@ class KvprError(RuntimeError):
 
 
 if not os.path.exists(LIB_PATH):
-    raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2411_17089_amd.build` "
+    raise ImportError(f"{LIB_PATH} not found: build it with `python paper_2411_17089_amd/build.py` "
                       "(there is no CPU fallback)")
 lib = C.CDLL(LIB_PATH)
 
@@ -89,6 +90,9 @@ _SIGS = {
     "kvpr_decode_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "kvpr_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "kvpr_token_gemm": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
+    "kvpr_rope_table": (_i, [_vp, _i, _i, C.c_double]),
+    "kvpr_recompute_gemm_rope": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp, _i, _i, _i, _i, _i, _vp]),
+    "kvpr_rope_token": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _i64, _vp]),
     "kvpr_int4_row_bytes": (_sz, [_i]),
     "kvpr_quant_int4": (_i, [_vp, _vp, _i64, _i, _vp]),
     "kvpr_dequant_int4": (_i, [_vp, _vp, _i64, _i, _vp]),
@@ -127,8 +131,9 @@ def kvpr_last_error() -> str:
     return lib.kvpr_last_error().decode()
 
 
-def kvpr_create(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, stream=None, dtype=KVPR_F16):
-    d = kvpr_model_desc(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, dtype)
+def kvpr_create(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, stream=None, dtype=KVPR_F16,
+                arch=KVPR_ARCH_OPT, rope_base=0.0):
+    d = kvpr_model_desc(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, dtype, arch, rope_base)
     out = _vp()
     _check(lib.kvpr_create(C.byref(d), _stream(stream), C.byref(out)))
     return out
@@ -247,8 +252,9 @@ def kvpr_decode_step(ctx, seq, layer_weights, x_in_dev, x_out_dev, splits=None, 
     return list(sout), (list(tim) if timing else None)
 
 
-def kvpr_create_offload(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, n_gpu_batches, stream=None, dtype=KVPR_F16):
-    d = kvpr_model_desc(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, dtype)
+def kvpr_create_offload(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, n_gpu_batches, stream=None, dtype=KVPR_F16,
+                        arch=KVPR_ARCH_OPT, rope_base=0.0):
+    d = kvpr_model_desc(n_layers, hidden, n_heads, head_dim, ffn_dim, batch, max_seq, dtype, arch, rope_base)
     out = _vp()
     _check(lib.kvpr_create_offload(C.byref(d), n_gpu_batches, _stream(stream), C.byref(out)))
     return out
@@ -298,3 +304,22 @@ def kvpr_quant_int4(src_dev, dst_dev, rows, cols, stream=None):
 
 def kvpr_dequant_int4(src_dev, dst_dev, rows, cols, stream=None):
     _check(lib.kvpr_dequant_int4(_ptr(src_dev), _ptr(dst_dev), rows, cols, _stream(stream)))
+
+
+def kvpr_rope_table(n_pos, head_dim, base=10000.0):
+    """numpy float32 [n_pos, head_dim/2, 2] = (cos, sin)."""
+    import numpy as np
+    out = np.empty((n_pos, head_dim // 2, 2), dtype=np.float32)
+    _check(lib.kvpr_rope_table(out.ctypes.data, n_pos, head_dim, base))
+    return out
+
+
+def kvpr_recompute_gemm_rope(a_dev, w_dev, bias_dev, c_dev, M, N, K, ldc, table_dev, n_pos, rope_cols, head_dim, batch, pos0,
+                             stream=None):
+    _check(lib.kvpr_recompute_gemm_rope(_ptr(a_dev), _ptr(w_dev), _ptr(bias_dev), _ptr(c_dev), M, N, K, ldc, _ptr(table_dev),
+                                        n_pos, rope_cols, head_dim, batch, pos0, _stream(stream)))
+
+
+def kvpr_rope_token(qk32_dev, table_dev, n_pos, pos, batch, hidden, head_dim, q32_dev, k16_dev, ldk, stream=None):
+    _check(lib.kvpr_rope_token(_ptr(qk32_dev), _ptr(table_dev), n_pos, pos, batch, hidden, head_dim, _ptr(q32_dev),
+                               _ptr(k16_dev), ldk, _stream(stream)))

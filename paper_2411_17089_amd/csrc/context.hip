@@ -3,6 +3,7 @@
 #include "kvpr_internal.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -52,6 +53,10 @@ struct kvpr_ctx {
     half* dkv[2] = {nullptr, nullptr};
     float* q32 = nullptr;
     half* z16 = nullptr;
+    // rotary models (KVPR_ARCH_LLAMA): q|k of the decode token before rotation, and the (cos, sin) table
+    bool llama = false;
+    float* qk32 = nullptr;
+    float2* rope_tab = nullptr;          // [max_seq][head_dim / 2]
     void* attn_ws = nullptr;
     // hidden-state scratch of the full decoder layer
     half *hid = nullptr, *xn = nullptr, *attn_out = nullptr, *ffn1 = nullptr, *ffn2 = nullptr;
@@ -109,9 +114,10 @@ int ensure_timing_events(kvpr_ctx* c, int slots) {
 int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn) {
     if (!w) return fail(KVPR_E_INVAL, "weights are null");
     if (!w->wqkv || !w->wo) return fail(KVPR_E_INVAL, "wqkv / wo must not be null");
-    if (need_ffn && (!w->w1 || !w->w2 || !w->ln1_g || !w->ln1_b || !w->ln2_g || !w->ln2_b))
-        return fail(KVPR_E_INVAL, "FFN / LayerNorm weights must not be null for a full decoder layer");
-    (void)c;
+    if (need_ffn && (!w->w1 || !w->w2 || !w->ln1_g || !w->ln2_g))
+        return fail(KVPR_E_INVAL, "FFN / norm weights must not be null for a full decoder layer");
+    if (need_ffn && !c->llama && (!w->ln1_b || !w->ln2_b))
+        return fail(KVPR_E_INVAL, "LayerNorm offsets must not be null for a full decoder layer");
     return KVPR_OK;
 }
 
@@ -188,9 +194,18 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     auto project_and_store = [&]() -> int {
         if (wf) KVPR_HIP(hipStreamWaitEvent(c->compute, wf->all_ready, 0));
         if (ev) KVPR_HIP(hipEventRecord(ev->p0, c->compute));
-        if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->q32, dkv + (size_t)seq * kr, b, 3 * h, h, h,
-                                                   2 * (int64_t)h, 0, c->compute))
+        if (c->llama) {
+            // q and k stay float32 until they are rotated with position seq; v goes straight into the cache row
+            if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->qk32, dkv + (size_t)seq * kr + h, b, 3 * h, h,
+                                                       2 * h, 2 * (int64_t)h, 0, c->compute))
+                return rc;
+            if (int rc = kvpr::launch_rope_token(c->qk32, c->rope_tab, seq, b, h, c->d.head_dim, c->q32, dkv + (size_t)seq * kr,
+                                                 2 * (int64_t)h, c->compute))
+                return rc;
+        } else if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->q32, dkv + (size_t)seq * kr, b, 3 * h, h, h,
+                                                          2 * (int64_t)h, 0, c->compute)) {
             return rc;
+        }
         // a compressed store receives the new rows packed (Sec. 4.4); attention below still reads the exact row
         if (c->qkv)
             if (int rc = kvpr::launch_quant_int4(dkv + (size_t)seq * kr, kv_stage + (size_t)seq * ksb, b, 2 * h, c->compute)) return rc;
@@ -224,8 +239,12 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
                 if (c->qx)
                     if (int rc = kvpr::launch_dequant_int4(x_stage + (size_t)bound[j] * xsb, dx + (size_t)bound[j] * xr, rows, h, c->compute))
                         return rc;
-                if (int rc = kvpr::launch_gemm(dx + (size_t)bound[j] * xr, wkv, bkv, dkv + (size_t)bound[j] * kr, rows, 2 * h,
-                                               h, 2 * (int64_t)h, c->compute))
+                // rotary models: the K half is rotated with the positions of its rows, bound[j] .. bound[j+1]-1
+                if (int rc = c->llama
+                                 ? kvpr::launch_gemm_rope(dx + (size_t)bound[j] * xr, wkv, bkv, dkv + (size_t)bound[j] * kr, rows, 2 * h, h,
+                                                          2 * (int64_t)h, c->rope_tab, h, c->d.head_dim, b, bound[j], c->compute)
+                                 : kvpr::launch_gemm(dx + (size_t)bound[j] * xr, wkv, bkv, dkv + (size_t)bound[j] * kr, rows, 2 * h, h,
+                                                     2 * (int64_t)h, c->compute))
                     return rc;
             }
         }
@@ -341,7 +360,7 @@ void destroy_impl(kvpr_ctx* c) {
         for (hipEvent_t e : we) if (e) (void)hipEventDestroy(e);
     }
     if (c->wstream) (void)hipStreamDestroy(c->wstream);
-    void* dev[] = {c->q32, c->z16, c->attn_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2, c->dw[0], c->dw[1], c->hid_all};
+    void* dev[] = {c->qk32, c->rope_tab, c->q32, c->z16, c->attn_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2, c->dw[0], c->dw[1], c->hid_all};
     for (void* p : dev) if (p) (void)hipFree(p);
     hipEvent_t evs[] = {c->ev_proj, c->ev_store, c->ev_begin};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
@@ -363,7 +382,7 @@ namespace {
 // the q|k|v bias come right after Wq: the range [wkv, wo) is what the recomputation needs.
 struct BlobLayout {
     size_t wq, wkv, bqkv, wo, bo, ln1_g, ln1_b, ln2_g, ln2_b, w1, b1, w2, b2, total;
-    BlobLayout(size_t h, size_t f) {
+    BlobLayout(size_t h, size_t f, bool gated) {
         size_t o = 0;
         auto take = [&](size_t n) { size_t at = o; o += (n + 63) / 64 * 64; return at; };   // 128-byte aligned pieces
         wq = take(h * h);          // rows [0, h) of wqkv
@@ -372,7 +391,7 @@ struct BlobLayout {
         wo = take(h * h);
         bo = take(h);
         ln1_g = take(h); ln1_b = take(h); ln2_g = take(h); ln2_b = take(h);
-        w1 = take(f * h); b1 = take(f);
+        w1 = take((gated ? 2 : 1) * f * h); b1 = take(f);   // gated FFN: [gate; up] stacked
         w2 = take(h * f); b2 = take(h);
         total = o;
     }
@@ -413,11 +432,15 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
         return fail(KVPR_E_INVAL, "hidden (%d) != n_heads (%d) * head_dim (%d)", d->hidden, d->n_heads, d->head_dim);
     if (d->hidden % 128) return fail(KVPR_E_INVAL, "hidden must be a multiple of 128");
     if (d->ffn_dim < 0 || d->ffn_dim % 128) return fail(KVPR_E_INVAL, "ffn_dim must be 0 or a multiple of 128");
+    if (d->arch != KVPR_ARCH_OPT && d->arch != KVPR_ARCH_LLAMA) return fail(KVPR_E_INVAL, "unknown arch %d", d->arch);
+    if (d->arch == KVPR_ARCH_LLAMA && !(d->rope_base >= 0.f && std::isfinite(d->rope_base)))
+        return fail(KVPR_E_INVAL, "rope_base must be finite and >= 0 (0 = 10000)");
 
     kvpr_ctx* c = new (std::nothrow) kvpr_ctx;
     if (!c) return fail(KVPR_E_NOMEM, "out of host memory");
     c->d = *d;
     c->nb = n_gpu_batches;
+    c->llama = d->arch == KVPR_ARCH_LLAMA;
     c->qx = (d->dtype & KVPR_X_INT4) != 0;
     c->qkv = (d->dtype & KVPR_KV_INT4) != 0;
     c->compute = (hipStream_t)compute_stream;
@@ -466,15 +489,28 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     if ((e = hipMalloc((void**)&c->z16, bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "z buffer", e);
     if ((e = hipMalloc(&c->attn_ws, kvpr::attention_workspace_bytes(d->batch, d->hidden, d->n_heads, d->max_seq))) != hipSuccess)
         return bail(KVPR_E_NOMEM, "attention workspace", e);
+    if (c->llama) {
+        if ((e = hipMalloc((void**)&c->qk32, 2 * bh * sizeof(float))) != hipSuccess) return bail(KVPR_E_NOMEM, "q|k buffer", e);
+        // (cos, sin)(p * theta_i), theta_i = base^(-2i/d): evaluated in double on the host, stored as float
+        std::vector<float2> tab((size_t)d->max_seq * (d->head_dim / 2));
+        if (kvpr_rope_table((float*)tab.data(), d->max_seq, d->head_dim, d->rope_base > 0.f ? (double)d->rope_base : 10000.0) != KVPR_OK) {
+            destroy_impl(c);
+            return KVPR_E_INVAL;
+        }
+        if ((e = hipMalloc((void**)&c->rope_tab, tab.size() * sizeof(float2))) != hipSuccess) return bail(KVPR_E_NOMEM, "rotary table", e);
+        if ((e = hipMemcpy(c->rope_tab, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice)) != hipSuccess)
+            return bail(KVPR_E_HIP, "rotary table upload", e);
+    }
     if (d->ffn_dim > 0) {
         half** bufs[] = {&c->hid, &c->xn, &c->attn_out, &c->ffn2};
         for (half** p : bufs)
             if ((e = hipMalloc((void**)p, bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "hidden-state buffer", e);
-        if ((e = hipMalloc((void**)&c->ffn1, (size_t)d->batch * d->ffn_dim * sizeof(half))) != hipSuccess)
+        // gated FFN: [gate | up] (2 ffn columns) followed by their gated product (ffn columns)
+        if ((e = hipMalloc((void**)&c->ffn1, (size_t)d->batch * d->ffn_dim * (c->llama ? 3 : 1) * sizeof(half))) != hipSuccess)
             return bail(KVPR_E_NOMEM, "FFN buffer", e);
     }
     if (c->nb > 0) {
-        const BlobLayout L(d->hidden, d->ffn_dim);
+        const BlobLayout L(d->hidden, d->ffn_dim, c->llama);
         if ((e = hipStreamCreateWithFlags(&c->wstream, hipStreamNonBlocking)) != hipSuccess) return bail(KVPR_E_HIP, "weight stream", e);
         c->hw.assign(d->n_layers, nullptr);
         c->w_written.assign(d->n_layers, false);
@@ -595,7 +631,9 @@ extern "C" int kvpr_store_prefill_kv(kvpr_ctx* c, int layer, int seq, const kvpr
         if (int rc = kvpr::launch_dequant_int4(c->dxq[0], c->dx[0], (int64_t)seq * c->d.batch, h, c->compute)) return rc;
     const half* wkv = (const half*)w->wqkv + (size_t)h * h;
     const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
-    if (int rc = kvpr::launch_gemm(c->dx[0], wkv, bkv, c->dkv[0], (int64_t)seq * c->d.batch, 2 * h, h, 2 * (int64_t)h, c->compute))
+    if (int rc = c->llama ? kvpr::launch_gemm_rope(c->dx[0], wkv, bkv, c->dkv[0], (int64_t)seq * c->d.batch, 2 * h, h, 2 * (int64_t)h,
+                                                   c->rope_tab, h, c->d.head_dim, c->d.batch, 0, c->compute)
+                          : kvpr::launch_gemm(c->dx[0], wkv, bkv, c->dkv[0], (int64_t)seq * c->d.batch, 2 * h, h, 2 * (int64_t)h, c->compute))
         return rc;
     if (c->qkv)
         if (int rc = kvpr::launch_quant_int4(c->dkv[0], c->dkvq[0], (int64_t)seq * c->d.batch, 2 * h, c->compute)) return rc;
@@ -654,6 +692,37 @@ extern "C" int kvpr_timing_read(kvpr_ctx* c, int slot, kvpr_layer_timing* timing
     return read_timing(c, ev, ev->seq, ev->split, timing);
 }
 
+namespace {
+
+// the parts of a decoder layer around the attention block (c->xn = normalised input of the attention block)
+int pre_attention_norm(kvpr_ctx* c, const kvpr_layer_weights* w, const half* hid_in) {
+    const int b = c->d.batch, h = c->d.hidden;
+    if (c->llama) return kvpr::launch_rmsnorm(hid_in, w->ln1_g, c->xn, b, h, c->compute);
+    return kvpr::launch_layernorm(hid_in, w->ln1_g, w->ln1_b, c->xn, b, h, c->compute);
+}
+
+// hid_out = r + FFN(norm(r)),  r = hid_in + attn_out.  OPT: LayerNorm, ReLU FFN with biases (Eq. 4);
+// LLaMA: RMSNorm, down(silu(gate) * up) with w1 = [gate; up] stacked
+int residual_and_ffn(kvpr_ctx* c, const kvpr_layer_weights* w, const half* hid_in, half* hid_out) {
+    const int b = c->d.batch, h = c->d.hidden, f = c->d.ffn_dim;
+    const size_t bh = (size_t)b * h;
+    if (int rc = kvpr::launch_add(hid_in, c->attn_out, c->ffn2, bh, c->compute)) return rc;      // ffn2 = residual stream
+    if (c->llama) {
+        half* prod = c->ffn1 + (size_t)b * 2 * f;
+        if (int rc = kvpr::launch_rmsnorm(c->ffn2, w->ln2_g, c->xn, b, h, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, nullptr, nullptr, c->ffn1, b, 2 * f, h, 0, 2 * (int64_t)f, 0, c->compute)) return rc;
+        if (int rc = kvpr::launch_silu_mul(c->ffn1, prod, b, f, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(prod, w->w2, nullptr, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
+    } else {
+        if (int rc = kvpr::launch_layernorm(c->ffn2, w->ln2_g, w->ln2_b, c->xn, b, h, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, w->b1, nullptr, c->ffn1, b, f, h, 0, f, 1, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->ffn1, w->w2, w->b2, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
+    }
+    return kvpr::launch_add(c->ffn2, c->attn_out, hid_out, bh, c->compute);
+}
+
+}  // namespace
+
 extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
                                 void* x_out_dev, const int32_t* splits_in, int32_t* splits_out,
                                 kvpr_layer_timing* per_layer) {
@@ -661,7 +730,7 @@ extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* 
     if (c->d.ffn_dim <= 0) return fail(KVPR_E_STATE, "kvpr_decode_step needs ffn_dim > 0");
     if (c->nb > 0) return fail(KVPR_E_STATE, "context was created for offloaded weights: use kvpr_decode_step_columns");
     if (!layers || !x_in_dev || !x_out_dev) return fail(KVPR_E_INVAL, "layers / x_in_dev / x_out_dev is null");
-    const int L = c->d.n_layers, b = c->d.batch, h = c->d.hidden, f = c->d.ffn_dim;
+    const int L = c->d.n_layers, b = c->d.batch, h = c->d.hidden;
     std::vector<int32_t> ls(L);
     for (int i = 0; i < L; ++i) {
         if (int rc = check_weights(c, &layers[i], true)) return rc;
@@ -675,16 +744,11 @@ extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* 
     for (int i = 0; i < L; ++i) {
         const kvpr_layer_weights* w = &layers[i];
         half* hid_out = (i == L - 1) ? (half*)x_out_dev : c->hid;
-        // pre-LayerNorm -> attention block -> residual
-        if (int rc = kvpr::launch_layernorm(hid_in, w->ln1_g, w->ln1_b, c->xn, b, h, c->compute)) return rc;
+        // pre-norm -> attention block -> residual -> norm -> FFN -> residual
+        if (int rc = pre_attention_norm(c, w, hid_in)) return rc;
         if (int rc = enqueue_layer(c, i, seq, ls[i], w, c->xn, c->attn_out, i % c->nbuf, per_layer ? &c->tev[i] : nullptr, false))
             return rc;
-        if (int rc = kvpr::launch_add(hid_in, c->attn_out, c->ffn2, bh, c->compute)) return rc;      // ffn2 = residual stream
-        // LayerNorm -> FFN (Eq. 4, ReLU) -> residual
-        if (int rc = kvpr::launch_layernorm(c->ffn2, w->ln2_g, w->ln2_b, c->xn, b, h, c->compute)) return rc;
-        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, w->b1, nullptr, c->ffn1, b, f, h, 0, f, 1, c->compute)) return rc;
-        if (int rc = kvpr::launch_token_gemm_flags(c->ffn1, w->w2, w->b2, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
-        if (int rc = kvpr::launch_add(c->ffn2, c->attn_out, hid_out, bh, c->compute)) return rc;
+        if (int rc = residual_and_ffn(c, w, hid_in, hid_out)) return rc;
         hid_in = hid_out;
     }
     if (splits_out) std::copy(ls.begin(), ls.end(), splits_out);
@@ -719,7 +783,7 @@ extern "C" int kvpr_weights_write(kvpr_ctx* c, int layer, const kvpr_layer_weigh
     if (int rc = check_weights(c, host, true)) return rc;
     KVPR_HIP(hipStreamSynchronize(c->wstream));
     const size_t h = c->d.hidden, f = c->d.ffn_dim;
-    const BlobLayout L(h, f);
+    const BlobLayout L(h, f, c->llama);
     half* blob = c->hw[layer];
     auto put = [&](size_t at, const void* src, size_t n) {
         if (src) memcpy(blob + at, src, n * sizeof(half));
@@ -731,7 +795,7 @@ extern "C" int kvpr_weights_write(kvpr_ctx* c, int layer, const kvpr_layer_weigh
     put(L.bo, host->bo, h);
     put(L.ln1_g, host->ln1_g, h); put(L.ln1_b, host->ln1_b, h);
     put(L.ln2_g, host->ln2_g, h); put(L.ln2_b, host->ln2_b, h);
-    put(L.w1, host->w1, f * h); put(L.b1, host->b1, f);
+    put(L.w1, host->w1, (c->llama ? 2 : 1) * f * h); put(L.b1, host->b1, f);
     put(L.w2, host->w2, h * f); put(L.b2, host->b2, h);
     c->w_written[layer] = true;
     return KVPR_OK;
@@ -755,7 +819,7 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
     }
     if (per_slot)
         if (int rc = ensure_timing_events(c, S)) return rc;
-    const BlobLayout BL(h, f);
+    const BlobLayout BL(h, f, c->llama);
     const size_t bh = (size_t)b * h;
     const size_t kv_part = (BL.wo - BL.wkv) * sizeof(half);       // [Wk;Wv] rows and the q|k|v bias
     // weights of layer j into device blob j % 2: the part the recomputation needs first (fine-grained MHA
@@ -783,15 +847,11 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
             half* hid_out = (j == L - 1) ? (half*)x_out_dev + (size_t)k * bh : c->hid_all + (size_t)k * bh;
             // LayerNorm parameters arrive with the second part of the blob
             KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_wall[wb], 0));
-            if (int rc = kvpr::launch_layernorm(hid_in, w.ln1_g, w.ln1_b, c->xn, b, h, c->compute)) return rc;
+            if (int rc = pre_attention_norm(c, &w, hid_in)) return rc;
             if (int rc = enqueue_layer(c, slot, seq, ls[slot], &w, c->xn, c->attn_out, slot % c->nbuf,
                                        per_slot ? &c->tev[slot] : nullptr, false, &wf))
                 return rc;
-            if (int rc = kvpr::launch_add(hid_in, c->attn_out, c->ffn2, bh, c->compute)) return rc;
-            if (int rc = kvpr::launch_layernorm(c->ffn2, w.ln2_g, w.ln2_b, c->xn, b, h, c->compute)) return rc;
-            if (int rc = kvpr::launch_token_gemm_flags(c->xn, w.w1, w.b1, nullptr, c->ffn1, b, f, h, 0, f, 1, c->compute)) return rc;
-            if (int rc = kvpr::launch_token_gemm_flags(c->ffn1, w.w2, w.b2, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
-            if (int rc = kvpr::launch_add(c->ffn2, c->attn_out, hid_out, bh, c->compute)) return rc;
+            if (int rc = residual_and_ffn(c, &w, hid_in, hid_out)) return rc;
         }
         KVPR_HIP(hipEventRecord(c->ev_wfree[wb], c->compute));
         c->wfree_recorded[wb] = true;
@@ -839,6 +899,45 @@ extern "C" int kvpr_token_gemm(const void* x, const void* w, const void* bias, v
     if (!x || !w || (out_f32_cols > 0 && !y32) || (out_f32_cols < N && !y16)) return fail(KVPR_E_INVAL, "null pointer");
     if (out_f32_cols < N && ld16 < N - out_f32_cols) return fail(KVPR_E_INVAL, "ld16 too small");
     return kvpr::launch_token_gemm_flags(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, 0, (hipStream_t)stream);
+}
+
+// ---- rotary models ----
+extern "C" int kvpr_rope_table(float* out_host, int n_pos, int head_dim, double base) {
+    if (!out_host) return fail(KVPR_E_INVAL, "out_host is null");
+    if (n_pos < 1 || (head_dim != 64 && head_dim != 128)) return fail(KVPR_E_RANGE, "n_pos=%d head_dim=%d: need n_pos >= 1, head_dim 64 or 128", n_pos, head_dim);
+    if (!(base > 0.0) || !std::isfinite(base)) return fail(KVPR_E_INVAL, "base must be finite and > 0");
+    const int half_d = head_dim / 2;
+    for (int i = 0; i < half_d; ++i) {
+        const double theta = std::pow(base, -2.0 * i / head_dim);
+        for (int p = 0; p < n_pos; ++p) {
+            out_host[((size_t)p * half_d + i) * 2] = (float)std::cos(p * theta);
+            out_host[((size_t)p * half_d + i) * 2 + 1] = (float)std::sin(p * theta);
+        }
+    }
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_recompute_gemm_rope(const void* a, const void* w, const void* bias, void* cdev, int64_t M, int N, int K,
+                                        int64_t ldc, const void* table_dev, int n_pos, int rope_cols, int head_dim, int batch,
+                                        int pos0, void* stream) {
+    if (M < 0 || M >= ((int64_t)1 << 31) || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%lld N=%d K=%d out of range", (long long)M, N, K);
+    if (K % 64 || N % 8 || ldc < N || ldc % 4) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 4 == 0");
+    if (head_dim != 64 && head_dim != 128) return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
+    if (rope_cols < 0 || rope_cols > N || rope_cols % 128) return fail(KVPR_E_INVAL, "rope_cols must be a multiple of 128 in [0, N]");
+    if (batch < 1 || pos0 < 0 || n_pos < 1) return fail(KVPR_E_RANGE, "batch=%d pos0=%d n_pos=%d out of range", batch, pos0, n_pos);
+    if (M == 0) return KVPR_OK;
+    if (pos0 + (M - 1) / batch >= n_pos) return fail(KVPR_E_RANGE, "rows reach position %lld, the table has %d", (long long)(pos0 + (M - 1) / batch), n_pos);
+    if (!a || !w || !cdev || !table_dev) return fail(KVPR_E_INVAL, "a / w / c / table is null");
+    return kvpr::launch_gemm_rope(a, w, bias, cdev, M, N, K, ldc, table_dev, rope_cols, head_dim, batch, pos0, (hipStream_t)stream);
+}
+
+extern "C" int kvpr_rope_token(const void* qk32, const void* table_dev, int n_pos, int pos, int batch, int hidden, int head_dim,
+                               void* q32, void* k16, int64_t ldk, void* stream) {
+    if (batch < 1 || hidden < 1 || pos < 0 || pos >= n_pos) return fail(KVPR_E_RANGE, "batch=%d hidden=%d pos=%d n_pos=%d out of range", batch, hidden, pos, n_pos);
+    if ((head_dim != 64 && head_dim != 128) || hidden % head_dim) return fail(KVPR_E_INVAL, "head_dim must be 64 or 128 and divide hidden");
+    if (ldk < hidden) return fail(KVPR_E_INVAL, "ldk too small");
+    if (!qk32 || !table_dev || !q32 || !k16) return fail(KVPR_E_INVAL, "null pointer");
+    return kvpr::launch_rope_token(qk32, table_dev, pos, batch, hidden, head_dim, q32, k16, ldk, (hipStream_t)stream);
 }
 
 extern "C" size_t kvpr_int4_row_bytes(int cols) {
@@ -936,7 +1035,10 @@ extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out
     int rc = kvpr::launch_fill_random(wtmp, (size_t)2 * h * h, 0.035f, 1u, c->compute);
     if (!rc) rc = kvpr::launch_fill_random(c->dx[0], (size_t)rows * h, 1.7f, 2u, c->compute);
     if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
-            return kvpr::launch_gemm(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->compute); }, &t);
+            // rotary models: positions as if the context's batch held these rows (the rotation costs the same anywhere)
+            return c->llama ? kvpr::launch_gemm_rope(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->rope_tab, h,
+                                                     c->d.head_dim, c->d.batch, 0, c->compute)
+                            : kvpr::launch_gemm(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->compute); }, &t);
     if (!rc) p.gemm_flops_per_s = 4.0 * (double)rows * h * h / t;
     // attention read rate over the cache just produced (context batch, S = rows / batch positions)
     const int S = (int)(rows / c->d.batch);

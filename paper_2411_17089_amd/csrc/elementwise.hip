@@ -87,7 +87,76 @@ __global__ void gather_rows_kernel(const _Float16* __restrict__ table, const int
     for (int i = threadIdx.x; i < h; i += blockDim.x) out[(int64_t)blockIdx.x * h + i] = src[i];
 }
 
+// RMSNorm: y = x / sqrt(mean(x^2) + eps) * g, one workgroup per row, float32 statistics
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const _Float16* __restrict__ x, const _Float16* __restrict__ g,
+                                                      _Float16* __restrict__ y, int h, float eps) {
+    const _Float16* xr = x + (int64_t)blockIdx.x * h;
+    __shared__ float red[4];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < h; i += 256) {
+        const float v = (float)xr[i];
+        s += v * v;
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    const float r = rsqrtf((red[0] + red[1] + red[2] + red[3]) / h + eps);
+    for (int i = threadIdx.x; i < h; i += 256) y[(int64_t)blockIdx.x * h + i] = (_Float16)((float)xr[i] * r * (float)g[i]);
+}
+
+// gated FFN middle: gu [rows, 2f] = [gate | up]  ->  y [rows, f] = silu(gate) * up
+__global__ void silu_mul_kernel(const _Float16* __restrict__ gu, _Float16* __restrict__ y, int f, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const size_t row = i / f, col = i - row * f;
+    const float gt = (float)gu[row * 2 * f + col], up = (float)gu[row * 2 * f + f + col];
+    y[i] = (_Float16)(gt / (1.0f + __expf(-gt)) * up);
+}
+
+// rotary embedding of the decode token: qk [batch, 2h] float32 = [q | k] before rotation, position `pos` for
+// every sequence; q goes out as float32 [batch, h], k as float16 with row stride ldk (a row of the cache).
+// One thread per (row, pair): element i of a head pairs with element i + HD/2.
+__global__ void rope_token_kernel(const float* __restrict__ qk, const float2* __restrict__ table, int pos, int h, int hd,
+                                  float* __restrict__ q_out, _Float16* __restrict__ k_out, int64_t ldk, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int half_h = h / 2, half_d = hd / 2;
+    const size_t row = i / half_h;
+    const int p = (int)(i - row * half_h);
+    const int head = p / half_d, f = p - head * half_d;
+    const int c1 = head * hd + f, c2 = c1 + half_d;
+    const float2 cs = table[(size_t)pos * half_d + f];
+    const float* qr = qk + row * 2 * h;
+    const float q1 = qr[c1], q2 = qr[c2], k1 = qr[h + c1], k2 = qr[h + c2];
+    q_out[row * h + c1] = q1 * cs.x - q2 * cs.y;
+    q_out[row * h + c2] = q2 * cs.x + q1 * cs.y;
+    k_out[row * ldk + c1] = (_Float16)(k1 * cs.x - k2 * cs.y);
+    k_out[row * ldk + c2] = (_Float16)(k2 * cs.x + k1 * cs.y);
+}
+
 }  // namespace
+
+int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int h, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, st, (const _Float16*)x, (const _Float16*)g, (_Float16*)y, h, 1e-5f);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+int launch_silu_mul(const void* gu, void* y, int rows, int f, hipStream_t st) {
+    const size_t n = (size_t)rows * f;
+    hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const _Float16*)gu, (_Float16*)y, f, n);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+int launch_rope_token(const void* qk32, const void* table, int pos, int batch, int h, int head_dim, void* q32, void* k16,
+                      int64_t ldk, hipStream_t st) {
+    const size_t n = (size_t)batch * (h / 2);
+    hipLaunchKernelGGL(rope_token_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)qk32,
+                       (const float2*)table, pos, h, head_dim, (float*)q32, (_Float16*)k16, ldk, n);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
 
 int launch_argmax_rows(const float* logits, int M, int N, int32_t* out, hipStream_t st) {
     hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(256), 0, st, logits, N, out);

@@ -20,6 +20,11 @@
 //  * Workgroup ids are remapped so that the workgroups an XCD runs concurrently (ids equal mod 8)
 //    form a compact block of tiles sharing A/W panels in that XCD's L2.
 //  * Tail rows in M / N are clamped on load (they re-read the last valid row) and skipped on store.
+//  * Rotary models (HD = head width 64 or 128): the cache holds K after the rotary embedding, so the
+//    recomputed K columns are rotated in the epilogue with the position of their row
+//    (pos0 + row / batch), in float32 and in registers: a wave tile is 128 columns wide, so a
+//    column and its partner at distance HD/2 sit in the same lane, two or one accumulator tiles
+//    apart.  cos/sin come from a float2 table [position][HD/2] (L1/L2 hits: a tile spans few positions).
 #include "kvpr_internal.h"
 #include <type_traits>
 
@@ -35,16 +40,23 @@ typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 constexpr int BK = 32;          // halfs per stage
 constexpr int ROW_BYTES = 64;   // one LDS row of a stage
 
+// rotary epilogue: table[pos * HD/2 + i] = (cos, sin)(pos * theta_i); columns [0, cols) of C are rotated
+struct RopeArgs {
+    const float2* table;
+    int cols, batch, pos0;
+};
+
 template <int VM, int LGKM0>
 __device__ __forceinline__ void wait_counts() {
     // vmcnt(VM) [bits 3:0 and 15:14], expcnt untouched (7), lgkmcnt(0) if LGKM0 else untouched (15)
     __builtin_amdgcn_s_waitcnt((VM & 15) | ((VM >> 4) << 14) | 0x0070 | (LGKM0 ? 0 : 0x0F00));
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M>
+template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M, int HD>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     const _Float16* __restrict__ A, const _Float16* __restrict__ W, const _Float16* __restrict__ bias,
-    _Float16* __restrict__ C, int64_t M, int N, int K, int64_t ldc, int tiles_m, int tiles_n, int tiles_per_xcd) {
+    _Float16* __restrict__ C, int64_t M, int N, int K, int64_t ldc, int tiles_m, int tiles_n, int tiles_per_xcd,
+    RopeArgs rope) {
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -197,18 +209,55 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int nl = wn * WTN + i * 32 + 8 * g + 4 * fhalf;
-            float bv[4] = {0.f, 0.f, 0.f, 0.f};
             if (bias && n0 + nl < N) {
                 const half4 b4 = *reinterpret_cast<const half4*>(bias + n0 + nl);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) bv[e] = (float)b4[e];
+                for (int j = 0; j < TM; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][j][g * 4 + e] += (float)b4[e];
             }
+        }
+    }
+    if constexpr (HD > 0) {
+        constexpr int IH = HD / 64;                // accumulator tiles between a column and its partner HD/2 columns on
+        static_assert(WTN % HD == 0 && TN % (2 * IH) == 0, "a wave tile must hold whole heads");
+        if (n0 + wn * WTN < rope.cols) {           // wave-uniform: this wave's 128 columns are K columns
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                int64_t m = m0 + wm * WTM + j * 32 + frow;
+                if (m > M - 1) m = M - 1;
+                const float2* trow = rope.table + (int64_t)(rope.pos0 + (int)(m / rope.batch)) * (HD / 2);
+#pragma unroll
+                for (int i = 0; i < TN; ++i) {
+                    if ((i / IH) % 2 != 0) continue;   // second half of a head: handled with its partner
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int f = (i % IH) * 32 + 8 * g + 4 * fhalf;
+                        const float4 cs0 = *reinterpret_cast<const float4*>(trow + f);
+                        const float4 cs1 = *reinterpret_cast<const float4*>(trow + f + 2);
+                        const float cv[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, sv[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float x1 = acc[i][j][g * 4 + e], x2 = acc[i + IH][j][g * 4 + e];
+                            acc[i][j][g * 4 + e] = x1 * cv[e] - x2 * sv[e];
+                            acc[i + IH][j][g * 4 + e] = x2 * cv[e] + x1 * sv[e];
+                        }
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nl = wn * WTN + i * 32 + 8 * g + 4 * fhalf;
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
                 const int ml = wm * WTM + j * 32 + frow;
                 half4 o;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (_Float16)(acc[i][j][g * 4 + e] + bv[e]);
+                for (int e = 0; e < 4; ++e) o[e] = (_Float16)acc[i][j][g * 4 + e];
                 *reinterpret_cast<half4*>(lds + ml * CROW + nl * 2) = o;
             }
         }
@@ -227,10 +276,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M>
+template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M, int HD = 0>
 int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
-                hipStream_t st) {
-    auto kern = gemm_bias_f16<BM, BN, WM, WN, NSTAGE, GROUP_M>;
+                hipStream_t st, RopeArgs rope = RopeArgs{nullptr, 0, 1, 0}) {
+    auto kern = gemm_bias_f16<BM, BN, WM, WN, NSTAGE, GROUP_M, HD>;
     constexpr int stage_bytes = NSTAGE * (BM + BN) * ROW_BYTES, c_bytes = BM * (BN * 2 + 16);
     constexpr int lds_bytes = stage_bytes > c_bytes ? stage_bytes : c_bytes;
     static bool configured = false;   // per process and instantiation (one device is used)
@@ -244,7 +293,7 @@ int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t
     const int tiles_per_xcd = (int)((total + 7) / 8);
     const unsigned grid = (unsigned)(tiles_per_xcd * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds_bytes, st, (const _Float16*)a, (const _Float16*)w,
-                       (const _Float16*)bias, (_Float16*)c, M, N, K, ldc, tiles_m, tiles_n, tiles_per_xcd);
+                       (const _Float16*)bias, (_Float16*)c, M, N, K, ldc, tiles_m, tiles_n, tiles_per_xcd, rope);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }
@@ -262,6 +311,16 @@ int launch_gemm(const void* a, const void* w, const void* bias, void* c, int64_t
         case 3: return launch_tile<128, 128, 2, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
         default: return launch_tile<256, 256, 4, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
     }
+}
+
+// Eq. 7 for a rotary model: as launch_gemm, with columns [0, rope_cols) (the K half) rotated by the position
+// pos0 + row / batch of their row.  table: float2 [positions][head_dim/2] on the device.
+int launch_gemm_rope(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
+                     const void* table, int rope_cols, int head_dim, int batch, int pos0, hipStream_t st) {
+    if (M == 0) return KVPR_OK;
+    const RopeArgs r{(const float2*)table, rope_cols, batch, pos0};
+    if (head_dim == 64) return launch_tile<256, 256, 4, 2, 4, 8, 64>(a, w, bias, c, M, N, K, ldc, st, r);
+    return launch_tile<256, 256, 4, 2, 4, 8, 128>(a, w, bias, c, M, N, K, ldc, st, r);
 }
 
 }  // namespace kvpr

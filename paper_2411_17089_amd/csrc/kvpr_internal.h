@@ -33,6 +33,12 @@ int launch_fill_random(void* p, size_t n_halfs, float scale, uint32_t seed, hipS
 int launch_layernorm(const void* x, const void* g, const void* b, void* y, int rows, int h, hipStream_t st);
 int launch_argmax_rows(const float* logits, int M, int N, int32_t* out, hipStream_t st);
 int launch_gather_rows(const void* table, const int32_t* idx, void* out, int M, int h, hipStream_t st);
+int launch_gemm_rope(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
+                     const void* table, int rope_cols, int head_dim, int batch, int pos0, hipStream_t st);
+int launch_rmsnorm(const void* x, const void* g, void* y, int rows, int h, hipStream_t st);
+int launch_silu_mul(const void* gu, void* y, int rows, int f, hipStream_t st);
+int launch_rope_token(const void* qk32, const void* table, int pos, int batch, int h, int head_dim, void* q32, void* k16,
+                      int64_t ldk, hipStream_t st);
 size_t int4_row_bytes(int cols);
 int launch_quant_int4(const void* src, void* dst, int64_t rows, int cols, hipStream_t st);
 int launch_dequant_int4(const void* src, void* dst, int64_t rows, int cols, hipStream_t st);

@@ -110,6 +110,20 @@ def test_linear_planner_bit_exact_against_oracle(k):
     assert k.kvpr_int4_row_bytes(100) == 0 and k.kvpr_int4_row_bytes(0) == 0
 
 
+def test_rotary_table_against_oracle(k):
+    from oracle import kvpr_llama_oracle as lo
+    import numpy as np
+    for d, base in ((64, 10000.0), (128, 10000.0), (128, 500000.0)):
+        t = k.kvpr_rope_table(300, d, base)
+        ang = lo.rope_angles(np.arange(300), d, base)
+        assert t.shape == (300, d // 2, 2)
+        assert np.abs(t[..., 0] - np.cos(ang)).max() <= 1.3e-7 and np.abs(t[..., 1] - np.sin(ang)).max() <= 1.3e-7
+    for args, code in (((10, 96, 10000.0), k.KVPR_E_RANGE), ((0, 64, 10000.0), k.KVPR_E_RANGE), ((4, 64, 0.0), k.KVPR_E_INVAL)):
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_rope_table(*args)
+        assert e.value.code == code
+
+
 def test_planner_rejects_bad_arguments(k):
     good = k.make_profile(1e9, 1e12)
     for prof in (k.make_profile(0.0, 1e12), k.make_profile(1e9, -1.0), k.make_profile(float("nan"), 1e12),
@@ -159,7 +173,8 @@ def test_kernel_entry_points_validate_before_touching_the_gpu(k):
 
 def test_create_rejects_bad_descriptions(k):
     bad = [dict(hidden=768, n_heads=12, head_dim=32), dict(hidden=768, n_heads=11, head_dim=64),
-           dict(hidden=96 * 2, n_heads=2, head_dim=96), dict(dtype=7), dict(dtype=0x100), dict(dtype=0x401), dict(ffn_dim=100)]
+           dict(hidden=96 * 2, n_heads=2, head_dim=96), dict(dtype=7), dict(dtype=0x100), dict(dtype=0x401), dict(ffn_dim=100), dict(arch=2),
+           dict(arch=1, rope_base=-1.0)]
     base = dict(n_layers=1, hidden=768, n_heads=12, head_dim=64, ffn_dim=0, batch=1, max_seq=16, dtype=k.KVPR_F16)
     for upd in bad:
         kw = dict(base, **upd)
