@@ -33,10 +33,13 @@ def median(v):
     return v[len(v) // 2]
 
 
-def cpu_baseline(layer, n_seq: int):
+def cpu_baseline(layer, n_seq: int, llama: bool = False):
     """The oracle as it stands (numpy float64, full recompute of K/V then attention) on the first
     n_seq sequences of the same batch, timed on this machine's host cores."""
-    from oracle import kvpr_oracle as ko
+    if llama:
+        from oracle import kvpr_llama_oracle as ko
+    else:
+        from oracle import kvpr_oracle as ko
     sub = dict(layer)
     sub["X"] = np.ascontiguousarray(layer["X"][:, :n_seq])
     sub["x_new"] = np.ascontiguousarray(layer["x_new"][:n_seq])
@@ -69,18 +72,25 @@ def run_stack(args):
     import kvpr_inputs
     import paper_2411_17089_amd as k
     h, H, d = kvpr_inputs.SHAPES[args.model]
-    b, s, L, ffn, vocab, gen = args.batch, args.seq, args.layers, 4 * h, 50272, args.gen
+    llama = args.model.startswith("llama")
+    b, s, L, gen = args.batch, args.seq, args.layers, args.gen
+    ffn, vocab = (kvpr_inputs.LLAMA_FFN[args.model], 32000) if llama else (4 * h, 50272)
     cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
     torch.manual_seed(0)
     rnd = lambda shape, sc: (torch.randn(shape, device="cuda", dtype=torch.float32) * sc).half()
     t0 = time.perf_counter()
     qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
-    ctx = k.kvpr_create(L, h, H, d, ffn, b, s + gen + args.warmup + 2, dtype=k.KVPR_F16 | qflags)
+    ctx = k.kvpr_create(L, h, H, d, ffn, b, s + gen + args.warmup + 2, dtype=k.KVPR_F16 | qflags,
+                        arch=k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT)
     keep, ws = [], []
     for i in range(L):
-        t = dict(wqkv=rnd((3 * h, h), 0.02), bqkv=rnd((3 * h,), 0.01), wo=rnd((h, h), 0.02), bo=rnd((h,), 0.01),
-                 ln1_g=1 + rnd((h,), 0.05), ln1_b=rnd((h,), 0.02), w1=rnd((ffn, h), 0.02), b1=rnd((ffn,), 0.01),
-                 w2=rnd((h, ffn), 0.02), b2=rnd((h,), 0.01), ln2_g=1 + rnd((h,), 0.05), ln2_b=rnd((h,), 0.02))
+        if llama:   # no biases, RMSNorm gains, w1 = [gate; up]
+            t = dict(wqkv=rnd((3 * h, h), 0.02), wo=rnd((h, h), 0.02), ln1_g=1 + rnd((h,), 0.05), w1=rnd((2 * ffn, h), 0.02),
+                     w2=rnd((h, ffn), 0.02), ln2_g=1 + rnd((h,), 0.05))
+        else:
+            t = dict(wqkv=rnd((3 * h, h), 0.02), bqkv=rnd((3 * h,), 0.01), wo=rnd((h, h), 0.02), bo=rnd((h,), 0.01),
+                     ln1_g=1 + rnd((h,), 0.05), ln1_b=rnd((h,), 0.02), w1=rnd((ffn, h), 0.02), b1=rnd((ffn,), 0.01),
+                     w2=rnd((h, ffn), 0.02), b2=rnd((h,), 0.01), ln2_g=1 + rnd((h,), 0.05), ln2_b=rnd((h,), 0.02))
         keep.append(t)
         ws.append(k.make_weights(**t))
         X = torch.randn((s, b, h), device="cuda", dtype=torch.float16)        # post-LN activations ~ N(0,1)
@@ -147,18 +157,23 @@ def run_columns(args):
     import kvpr_inputs
     import paper_2411_17089_amd as k
     h, H, d = kvpr_inputs.SHAPES[args.model]
-    b, s, L, nb, ffn, gen = args.batch, args.seq, args.layers, args.gpu_batches, 4 * h, args.gen
+    llama = args.model.startswith("llama")
+    b, s, L, nb, gen = args.batch, args.seq, args.layers, args.gpu_batches, args.gen
+    ffn = kvpr_inputs.LLAMA_FFN[args.model] if llama else 4 * h
     S = L * nb
     cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
     rng = np.random.default_rng(0)
     torch.manual_seed(0)
     qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
-    ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + 2 * (gen + args.warmup) + 2, nb, dtype=k.KVPR_F16 | qflags)
+    ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + 2 * (gen + args.warmup) + 2, nb, dtype=k.KVPR_F16 | qflags,
+                                arch=k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT)
     rh = lambda shape, sc: (rng.standard_normal(shape, dtype=np.float32) * np.float32(sc)).astype(np.float16)
     t0 = time.perf_counter()
     base = dict(wqkv=rh((3 * h, h), 0.02), bqkv=rh((3 * h,), 0.01), wo=rh((h, h), 0.02), bo=rh((h,), 0.01),
                 ln1_g=(1 + rh((h,), 0.05)).astype(np.float16), ln1_b=rh((h,), 0.02), w1=rh((ffn, h), 0.02), b1=rh((ffn,), 0.01),
                 w2=rh((h, ffn), 0.02), b2=rh((h,), 0.01), ln2_g=(1 + rh((h,), 0.05)).astype(np.float16), ln2_b=rh((h,), 0.02))
+    if llama:   # no biases, RMSNorm gains only, w1 = [gate; up]
+        base = dict(wqkv=base["wqkv"], wo=base["wo"], ln1_g=base["ln1_g"], ln2_g=base["ln2_g"], w1=rh((2 * ffn, h), 0.02), w2=base["w2"])
     dev_w = {n: torch.from_numpy(a).cuda() for n, a in base.items()}
     wdev = k.make_weights(**dev_w)
     for j in range(L):
@@ -191,7 +206,7 @@ def run_columns(args):
         wall = time.perf_counter() - t0
         results[name] = {"tokens_per_s": nb * b * gen / wall, "ms_per_token_step": wall * 1e3 / gen,
                          "ms_per_layer_batch": wall * 1e3 / gen / S, "split": used[0]}
-    blob_bytes = 12 * h * h * 2
+    blob_bytes = (4 * h * h + (3 if llama else 2) * ffn * h) * 2
     r = results["kvpr"]
     out = {
         "metric": "decode_tokens_per_s_column_schedule_weights_offloaded", "value": r["tokens_per_s"], "unit": "tokens/s",
@@ -262,7 +277,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--model", default="opt-6.7b", help="opt-6.7b | opt-13b | opt-30b | tiny")
+    ap.add_argument("--model", default="opt-6.7b", help="opt-6.7b | opt-13b | opt-30b | llama2-7b | llama2-13b | tiny")
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--seq", type=int, default=1024)
     ap.add_argument("--split", type=int, default=-1, help="-1 = scheduler's l*")
@@ -309,16 +324,18 @@ def main():
 
     layer = kvpr_inputs.make_layer(0, b, s, h, H)
     f16 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    llama = args.model.startswith("llama")
+    arch = k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT
     wqkv = f16(np.concatenate([layer["Wq"].T, layer["Wk"].T, layer["Wv"].T], 0))
     bqkv = f16(np.concatenate([layer["bq"], layer["bk"], layer["bv"]]))
     wo, bo, x_new = f16(layer["Wo"].T), f16(layer["bo"]), f16(layer["x_new"])
-    w = k.make_weights(wqkv=wqkv, bqkv=bqkv, wo=wo, bo=bo)
+    w = k.make_weights(wqkv=wqkv, wo=wo) if llama else k.make_weights(wqkv=wqkv, bqkv=bqkv, wo=wo, bo=bo)
     out = torch.empty((b, h), dtype=torch.float16, device="cuda")
 
     # bytes per cached position (whole batch) as they cross the link, flops per recomputed position (Eq. 6, Eq. 8)
     qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
     f_pp = 4 * b * h * h
-    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, dtype=k.KVPR_F16 | qflags)
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, dtype=k.KVPR_F16 | qflags, arch=arch)
     k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
     k.kvpr_store_prefill_kv(ctx, 0, s, w)          # stand-in for prefill: cache = X.[Wk|Wv]+b, computed on the GPU
 
@@ -386,7 +403,7 @@ def main():
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12,
                     "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9, "d2h_GBps": prof.d2h_bytes_per_s / 1e9,
                     "attn_GBps": prof.attn_bytes_per_s / 1e9},
-        "roofline": {"kernel": "gemm_bias_f16 (recompute GEMM)", "bound": "mfma", "achieved": gemm_tflops,
+        "roofline": {"kernel": "gemm_bias_f16 (recompute GEMM%s)" % (", rotary epilogue" if llama else ""), "bound": "mfma", "achieved": gemm_tflops,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
                      "traffic": traffic, "traffic_detail": traffic_detail, "flops_per_launch": gemm_flops, "avg_ms": ms_gemm},
         "roofline_attention": {"kernel": "attention_partial (+combine)", "bound": "hbm", "achieved": attn_gbps,
@@ -419,7 +436,7 @@ def main():
 
     if not args.no_cpu_baseline:
         n_seq = min(args.cpu_seqs, b)
-        o_ref, dt, cores = cpu_baseline(layer, n_seq)
+        o_ref, dt, cores = cpu_baseline(layer, n_seq, llama)
         got = out.float().cpu().numpy()[:n_seq]
         result["cpu_baseline"] = {
             "value": n_seq / dt, "unit": "tokens/s per layer", "cores": cores, "kind": "oracle",
