@@ -78,3 +78,62 @@ def test_full_size_split_invariance(rig):
         torch.cuda.synchronize()
         outs.append(rig["out"].cpu().numpy().copy())
     assert rel_err(outs[1], outs[0]) <= 2e-3 and rel_err(outs[2], outs[0]) <= 2e-3
+
+
+def test_full_size_llama_layer_sampled_sequences(k):
+    """LLaMA-2-7B-shaped layer at the paper's LLaMA batch size (64) and context 1024, in the launch
+    configuration bench.py --model llama2-7b --batch 64 times; whole sequences against the rotary oracle."""
+    from oracle import kvpr_llama_oracle as lo
+    b, s, (h, H, d) = 64, 1024, kvpr_inputs.SHAPES["llama2-7b"]
+    layer = kvpr_inputs.make_layer(1, b, s, h, H)
+    dv = upload_layer(layer)
+    w = k.make_weights(wqkv=dv["wqkv"], wo=dv["wo"])
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, arch=k.KVPR_ARCH_LLAMA)
+    try:
+        k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
+        k.kvpr_store_prefill_kv(ctx, 0, s, w)
+        out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+        refs = {}
+        for n in (0, 37, 63):
+            sub = dict(layer, X=np.ascontiguousarray(layer["X"][:, n:n + 1]), x_new=layer["x_new"][n:n + 1])
+            refs[n] = lo.layer_decode(sub, 0)["o"]
+        for split in (832, 0, 1024):
+            print(f"full-size llama split={split}", flush=True)
+            k.kvpr_layer_decode(ctx, 0, s, split, w, dv["x_new"], out)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.isfinite(got).all()
+            for n, ref in refs.items():
+                assert rel_err(got[n:n + 1], ref) <= 3e-3, (split, n)
+    finally:
+        k.kvpr_destroy(ctx)
+
+
+def test_full_size_4bit_store_sampled_sequences(k):
+    """OPT-6.7B-shaped layer, batch 32, context 1024 over the 4-bit store (bench.py --store-int4 both)."""
+    from oracle import kvpr_int4_oracle as qo
+    b, s, (h, H, d) = 32, 1024, kvpr_inputs.SHAPES["opt-6.7b"]
+    layer = kvpr_inputs.make_layer(0, b, s, h, H)
+    dv = upload_layer(layer)
+    w = k.make_weights(wqkv=dv["wqkv"], bqkv=dv["bqkv"], wo=dv["wo"], bo=dv["bo"])
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, dtype=k.KVPR_F16 | k.KVPR_STORE_INT4)
+    try:
+        k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
+        k.kvpr_store_prefill_kv(ctx, 0, s, w)      # cache = K/V of the activations the store returns, packed
+        out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+        subs = {}
+        for n in (0, 21):
+            x_hat = qo.roundtrip(np.ascontiguousarray(layer["X"][:, n:n + 1])).astype(np.float64)
+            sub = dict(layer, X=x_hat, x_new=layer["x_new"][n:n + 1])
+            kv_hat = qo.roundtrip(ko.stored_kv(sub, "fp16").astype(np.float16)).astype(np.float64)
+            subs[n] = (sub, kv_hat)
+        for split in (576, 0, 1024):
+            print(f"full-size 4-bit store split={split}", flush=True)
+            k.kvpr_layer_decode(ctx, 0, s, split, w, dv["x_new"], out)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.isfinite(got).all()
+            for n, (sub, kv_hat) in subs.items():
+                assert rel_err(got[n:n + 1], ko.layer_decode(sub, split, kv_hat)["o"]) <= 1e-2, (split, n)
+    finally:
+        k.kvpr_destroy(ctx)
