@@ -30,6 +30,9 @@ def _codec_inputs(seed, rows, cols):
         a[1, :64] = np.tile(np.arange(16), 4)             # integers 0..15: exact
         a[2, :64] = np.linspace(-60000, 60000, 64)        # widest span float16 allows
         a[3, :64] = np.float16(1.0) + np.arange(64) * np.float16(2 ** -10)   # span of a few ulps
+    if rows >= 6:
+        a[4, :64] = (np.arange(64) % 23) * 2.0 ** -24                        # subnormal span: the upper clip is live
+        a[5, :64] = (np.arange(64) % 5) * 2.0 ** -24                         # span below 15 ulps: scale rounds to 0
     return a
 
 

@@ -36,6 +36,12 @@ def test_rounding_is_half_to_even_and_clipped():
     codes, _, _ = qo.quantize_rows(_row(x))
     assert codes[0, :6].tolist() == [0, 15, 0, 2, 2, 14]
     assert codes.max() == 15
+    # the clip is live only for subnormal spans: span 22 ulps -> scale = fp16(22/15 ulp) = 1 ulp -> 22 steps -> 15
+    tiny = np.zeros(64)
+    tiny[1], tiny[2] = 22 * 2.0 ** -24, 7 * 2.0 ** -24
+    codes, scale, mn = qo.quantize_rows(_row(tiny))
+    assert scale[0, 0] == np.float16(2.0 ** -24) and codes[0, :3].tolist() == [0, 15, 7]
+    assert qo.dequantize_rows(codes, scale, mn)[0, 1] == np.float16(15 * 2.0 ** -24)
 
 
 def test_constant_group_and_extremes():

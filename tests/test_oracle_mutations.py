@@ -137,3 +137,152 @@ PLAN_MUTATIONS = [
 @pytest.mark.parametrize("name,replace", PLAN_MUTATIONS, ids=[m[0] for m in PLAN_MUTATIONS])
 def test_plan_pins_catch(name, replace):
     assert not plan_pins_hold(_load(PLAN, replace)), name
+
+
+# ---- 4-bit store codec (Sec. 4.4) ----
+def int4_pins_hold(qo) -> bool:
+    try:
+        row = lambda v: np.asarray(v, dtype=np.float16)[None]
+        v = np.tile(np.arange(16), 4)
+        codes, scale, mn = qo.quantize_rows(row(v))
+        if scale[0, 0] != 1.0 or mn[0, 0] != 0.0 or not np.array_equal(codes[0], v):
+            return False
+        if not np.array_equal(qo.dequantize_rows(codes, scale, mn)[0], v.astype(np.float16)):
+            return False
+        kk = np.arange(64) % 16
+        x = -3.0 + 0.5 * kk
+        codes, scale, mn = qo.quantize_rows(row(x))
+        if scale[0, 0] != 0.5 or mn[0, 0] != -3.0 or not np.array_equal(codes[0], kk):
+            return False
+        if not np.array_equal(qo.roundtrip(row(x))[0].astype(np.float64), x):
+            return False
+        y = np.zeros(64)
+        y[:6] = [0.0, 15.0, 0.5, 1.5, 2.5, 14.5]
+        if qo.quantize_rows(row(y))[0][0, :6].tolist() != [0, 15, 0, 2, 2, 14]:
+            return False
+        c = np.full(64, 0.37, dtype=np.float16)
+        if not np.array_equal(qo.roundtrip(c[None])[0], c):
+            return False
+        tiny = np.zeros(64)
+        tiny[1] = 22 * 2.0 ** -24                       # subnormal span: the scale rounds down to one ulp, 22 steps fit
+        if qo.quantize_rows(row(tiny))[0][0, :2].tolist() != [0, 15]:
+            return False
+        rng = np.random.default_rng(0)
+        kv = rng.standard_normal((5, 3, 256)).astype(np.float16)
+        codes, scale, mn = qo.quantize_rows(kv)
+        rec = qo.dequantize_rows(codes, scale, mn)
+        g, r = kv.reshape(5, 3, 4, 64).astype(np.float64), rec.reshape(5, 3, 4, 64).astype(np.float64)
+        if not np.array_equal(r.min(-1), g.min(-1)) or codes.max() != 15 or codes.min() != 0:
+            return False
+        if not np.all(np.abs(r - g) <= 0.5 * scale.astype(np.float64)[..., None] + 2e-3 * np.abs(g) + 1e-3):
+            return False
+        packed = qo.pack_rows(codes, scale, mn)
+        if packed.shape != (5, 3, 144) or qo.packed_bytes(256) != 144:
+            return False
+        if packed[1, 1, 7] != (codes[1, 1, 14] | (codes[1, 1, 15] << 4)):
+            return False
+        meta = packed[1, 1, 128:132].copy().view(np.float16)
+        if meta[0] != scale[1, 1, 0] or meta[1] != mn[1, 1, 0]:
+            return False
+        c2, s2, m2 = qo.unpack_rows(packed, 256)
+        return np.array_equal(c2, codes) and np.array_equal(s2, scale) and np.array_equal(m2, mn)
+    except Exception:
+        return False
+
+
+INT4 = os.path.join(ROOT, "oracle", "kvpr_int4_oracle.py")
+INT4_MUTATIONS = [
+    ("16 levels spread over 16 steps", ("(mx - mn) / np.float32(15.0)", "(mx - mn) / np.float32(16.0)")),
+    ("truncation instead of rounding", ("q = np.rint((g - mn[..., None]) / safe[..., None])", "q = np.floor((g - mn[..., None]) / safe[..., None])")),
+    ("offset from the maximum", ("q = np.rint((g - mn[..., None]) / safe[..., None])", "q = np.rint((g - mx[..., None]) / safe[..., None])")),
+    ("codes clipped to 16", ("codes = np.clip(q, 0, 15)", "codes = np.clip(q, 0, 16)")),
+    ("groups of 32", ("GROUP = 64", "GROUP = 32")),
+    ("nibbles swapped", ("nib = (lo | (hi << 4))", "nib = (hi | (lo << 4))")),
+    ("minimum dropped on the way back", ("x = (prod + mn16.astype(np.float32)[..., None])", "x = (prod + 0 * mn16.astype(np.float32)[..., None])")),
+    ("metadata order swapped", ("meta = np.stack([scale16, mn16], axis=-1)", "meta = np.stack([mn16, scale16], axis=-1)")),
+    ("scale kept in float32", ("scale16 = ((mx - mn) / np.float32(15.0)).astype(np.float16)\n", "scale16 = ((mx - mn) / np.float32(15.0))\n")),
+]
+
+
+def test_int4_unmutated_passes():
+    assert int4_pins_hold(_load(INT4))
+
+
+@pytest.mark.parametrize("name,replace", INT4_MUTATIONS, ids=[m[0] for m in INT4_MUTATIONS])
+def test_int4_pins_catch(name, replace):
+    assert not int4_pins_hold(_load(INT4, replace)), name
+
+
+# ---- rotary / LLaMA-shaped layer ----
+def llama_pins_hold(lo) -> bool:
+    try:
+        from oracle import kvpr_oracle as ko
+        x = np.array([[3.0, 4.0]])
+        if not np.allclose(lo.rope(x, [np.pi / 2], 1), [[-4.0, 3.0]], atol=1e-15):
+            return False
+        x4 = np.array([[1.0, 2.0, 0.0, 0.0]])
+        p = 7.0
+        if not np.allclose(lo.rope(x4, [p], 1), [[np.cos(p), 2 * np.cos(0.01 * p), np.sin(p), 2 * np.sin(0.01 * p)]], atol=1e-15):
+            return False
+        rng = np.random.default_rng(1)
+        H, d = 2, 8
+        q, kx = rng.standard_normal((1, H * d)), rng.standard_normal((1, H * d))
+        sc = lambda m, n: (lo.rope(q, [m], H).reshape(H, d) * lo.rope(kx, [n], H).reshape(H, d)).sum(-1)
+        if not np.allclose(sc(10, 3), sc(107, 100), rtol=1e-11) or not np.array_equal(lo.rope(q, [0], H), q):
+            return False
+        lay = kvpr_inputs.make_layer(3, 2, 20, 128, 2)
+        st = lo.stored_kv(lay, "none")
+        outs = [lo.layer_decode(lay, l, st, "none")["o"] for l in (0, 7, 20)]
+        if not all(np.allclose(o, outs[0], rtol=1e-11, atol=1e-13) for o in outs):
+            return False
+        plain = ko.recompute_kv(lay["X"], lay["Wk"], lay["Wv"])
+        if not np.array_equal(st[..., 128:], plain[..., 128:]) or not np.array_equal(st[0, :, :128], plain[0, :, :128]):
+            return False
+        r = lo.layer_decode(lay, 0, st, "none")
+        t = 13
+        rel = lo.rope(ko.project(lay["x_new"], lay["Wq"])[None], [20 - t], 2)[0]
+        a = (r["q"].reshape(2, 2, 64) * st[t, :, :128].reshape(2, 2, 64)).sum(-1)
+        b = (rel.reshape(2, 2, 64) * plain[t, :, :128].reshape(2, 2, 64)).sum(-1)
+        if not np.allclose(a, b, rtol=1e-10, atol=1e-12):
+            return False
+        # the new token's own key: its score with itself is the unrotated q . k
+        k_new = ko.project(lay["x_new"], lay["Wk"])
+        q_plain = ko.project(lay["x_new"], lay["Wq"])
+        own = (r["q"].reshape(2, 2, 64) * r["kv"][20, :, :128].reshape(2, 2, 64)).sum(-1)
+        if not np.allclose(own, (q_plain.reshape(2, 2, 64) * k_new.reshape(2, 2, 64)).sum(-1), rtol=1e-10, atol=1e-12):
+            return False
+        xc = np.full((2, 16), 3.0)
+        gg = np.linspace(0.5, 2.0, 16)
+        if not np.allclose(lo.rms_norm(xc, gg, eps=0.0), np.broadcast_to(gg, (2, 16)), rtol=1e-15):
+            return False
+        if not np.isclose(lo.silu(1.0), 1.0 / (1.0 + np.exp(-1.0))) or lo.silu(0.0) != 0.0:
+            return False
+        eye = np.eye(4)
+        v = np.array([[0.5, -1.0, 2.0, 0.0]])
+        return bool(np.allclose(lo.gated_ffn(v, eye, 2 * eye, eye), lo.silu(v) * 2 * v))
+    except Exception:
+        return False
+
+
+LLAMA = os.path.join(ROOT, "oracle", "kvpr_llama_oracle.py")
+LLAMA_MUTATIONS = [
+    ("rotation backwards", ("out = np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)", "out = np.concatenate([x1 * c + x2 * s, x2 * c - x1 * s], axis=-1)")),
+    ("adjacent pairs instead of half split", ("x1, x2 = xh[..., : d // 2], xh[..., d // 2:]", "x1, x2 = xh[..., 0::2], xh[..., 1::2]")),
+    ("angle exponent i/d", ("theta = base ** (-2.0 * i / d)", "theta = base ** (-1.0 * i / d)")),
+    ("recomputed rows one position late", ("np.arange(pos0, pos0 + l), n_heads, base)", "np.arange(pos0 + 1, pos0 + l + 1), n_heads, base)")),
+    ("new token rotated with position s - 1", ('    q = rope(project(x_new, layer["Wq"])[None], [s], H, base)[0]', '    q = rope(project(x_new, layer["Wq"])[None], [s - 1], H, base)[0]')),
+    ("new key not rotated with s", ('layer["Wk"], layer["Wv"], H, base, pos0=s))', 'layer["Wk"], layer["Wv"], H, base, pos0=0))')),
+    ("values rotated too", ("    v = project(X_head, Wv)\n", "    v = rope(project(X_head, Wv), np.arange(pos0, pos0 + l), n_heads, base)\n")),
+    ("RMSNorm subtracts the mean", ("    return x / np.sqrt((x * x).mean(axis=-1, keepdims=True) + eps) * _f64(g)", "    x = x - x.mean(axis=-1, keepdims=True)\n    return x / np.sqrt((x * x).mean(axis=-1, keepdims=True) + eps) * _f64(g)")),
+    ("sigmoid of the wrong sign", ("    return x / (1.0 + np.exp(-x))", "    return x / (1.0 + np.exp(x))")),
+    ("gate and up exchanged", ("return project(silu(project(x, Wg)) * project(x, Wu), Wd)", "return project(silu(project(x, Wu)) * project(x, Wg), Wd)")),
+]
+
+
+def test_llama_unmutated_passes():
+    assert llama_pins_hold(_load(LLAMA))
+
+
+@pytest.mark.parametrize("name,replace", LLAMA_MUTATIONS, ids=[m[0] for m in LLAMA_MUTATIONS])
+def test_llama_pins_catch(name, replace):
+    assert not llama_pins_hold(_load(LLAMA, replace)), name
