@@ -15,8 +15,8 @@
 //   - x is tiny (M*K halfs) and comes from L2; one x fragment is reused for the TPW weight tiles, so
 //     the L2->CU traffic for x stays below the HBM traffic for W (with one tile per workgroup it was
 //     twice the weight bytes and capped the kernel at 2.2 TB/s);
-//   - all 4*TPW weight loads of a slab are issued before its MFMAs; per-wave partial tiles are summed
-//     through LDS;
+//   - all 4*TPW weight loads of a slab are issued before the MFMAs of the previous slab (register double
+//     buffering), so a wave always has one slab in flight; per-wave partial tiles are summed through LDS;
 //   - the epilogue adds the bias, optionally applies ReLU and writes float32 for the first
 //     `out_f32_cols` features (q) and float16 for the rest (k|v row of the cache, o, FFN).
 #include "kvpr_internal.h"
@@ -53,10 +53,17 @@ __global__ __launch_bounds__(TG_WAVES * 64) void token_gemm(const _Float16* __re
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[p][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+    // Register double buffering: the loads of this wave's next slab are issued before the MFMAs of the current
+    // one, so each wave always has a whole slab (TPW * 4 KiB of weights) in flight.
     const int slabs = K / SLAB;
-    for (int s = wave; s < slabs; s += TG_WAVES) {
-        const int k0 = s * SLAB;
-        half8 wf[TPW][4], xf[MT][4];
+    half8 wf0[TPW][4], xf0[MT][4], wf1[TPW][4], xf1[MT][4];
+    // workgroups start at different slabs (the sum over k has no order): with every workgroup at the same k all
+    // concurrent reads would share their low address bits (rows are K*2 bytes apart) and crowd a few HBM channels
+    const int rot = (int)((blockIdx.x * 5u) % (unsigned)slabs);
+    auto load = [&](half8 (&wf)[TPW][4], half8 (&xf)[MT][4], int s) {
+        int sr = s + rot;
+        if (sr >= slabs) sr -= slabs;
+        const int k0 = sr * SLAB;
 #pragma unroll
         for (int p = 0; p < TPW; ++p)
 #pragma unroll
@@ -66,6 +73,8 @@ __global__ __launch_bounds__(TG_WAVES * 64) void token_gemm(const _Float16* __re
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j) xf[t][j] = *reinterpret_cast<const half8*>(xp[t] + k0 + j * 32);
+    };
+    auto mac = [&](const half8 (&wf)[TPW][4], const half8 (&xf)[MT][4]) {
 #pragma unroll
         for (int p = 0; p < TPW; ++p)
 #pragma unroll
@@ -73,6 +82,26 @@ __global__ __launch_bounds__(TG_WAVES * 64) void token_gemm(const _Float16* __re
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[p][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[p][j], xf[t][j], acc[p][t], 0, 0, 0);
+    };
+    // two buffers need (TPW + MT) * 32 registers on top of the accumulators: the widest shapes keep a single buffer
+    constexpr bool kDoubleBuffer = (TPW + MT) * 32 + TPW * MT * 4 <= 200;
+    int s = wave;
+    if constexpr (kDoubleBuffer) {
+        if (s < slabs) load(wf0, xf0, s);
+        while (s < slabs) {
+            if (s + TG_WAVES < slabs) load(wf1, xf1, s + TG_WAVES);
+            mac(wf0, xf0);
+            s += TG_WAVES;
+            if (s >= slabs) break;
+            if (s + TG_WAVES < slabs) load(wf0, xf0, s + TG_WAVES);
+            mac(wf1, xf1);
+            s += TG_WAVES;
+        }
+    } else {
+        for (; s < slabs; s += TG_WAVES) {
+            load(wf0, xf0, s);
+            mac(wf0, xf0);
+        }
     }
 
     // ---- sum the waves' partial tiles: element i of (tile p, m-tile t) in lane L is
