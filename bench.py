@@ -100,6 +100,7 @@ def run_stack(args):
     setup_s = time.perf_counter() - t0
     prof = k.kvpr_profile(ctx, b, s)
     k.kvpr_set_profile(ctx, prof, cm, args.granularity)
+    k.kvpr_set_adaptive(ctx, args.adaptive)
     x = rnd((b, h), 1.0)
     x_out = torch.empty_like(x)
     logits = torch.empty((b, vocab), dtype=torch.float32, device="cuda")
@@ -142,6 +143,9 @@ def run_stack(args):
         "h2d_GBps_sustained": link_bytes / wall / 1e9, "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
         "h2d_frac_of_peak": link_bytes / wall / prof.h2d_peak_bytes_per_s,
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12},
+        "adaptive_alpha": args.adaptive,
+        "profile_at_end": {"v_com_GBps": k.kvpr_get_profile(ctx).h2d_bytes_per_s / 1e9,
+                           "v_gpu_TFLOPs": k.kvpr_get_profile(ctx).gemm_flops_per_s / 1e12},
         "breakdown_ms_per_layer": breakdown, "host_enqueue_ms_per_token": host_s * 1e3 / gen,
         "pinned_store_GiB": L * (s + gen + args.warmup + 2) * (x_bpp + kv_bpp) / 2 ** 30, "setup_s": setup_s,
     }
@@ -189,6 +193,7 @@ def run_columns(args):
     setup_s = time.perf_counter() - t0
     prof = k.kvpr_profile(ctx, b, s)
     k.kvpr_set_profile(ctx, prof, cm, args.granularity)
+    k.kvpr_set_adaptive(ctx, args.adaptive)
     x = (torch.randn((nb, b, h), device="cuda") * 1.0).half()
     x_out = torch.empty_like(x)
     seq = s
@@ -298,6 +303,8 @@ def main():
                     help="after the timed region, also measure the chunked-copy extension with this many parts (0 = skip)")
     ap.add_argument("--store-int4", default="none", choices=["none", "kv", "both"],
                     help="keep the host store group-wise 4-bit compressed (Sec. 4.4): the cache only, or the cache and the activations")
+    ap.add_argument("--adaptive", type=float, default=0.0,
+                    help="(stack / columns modes) extension: keep adapting v_com / v_gpu while decoding with this moving-average weight")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
     args = ap.parse_args()

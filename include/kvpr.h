@@ -204,6 +204,21 @@ int kvpr_plan_split_linear(const kvpr_profile_t* prof, int cost_model, int chunk
                            int64_t x_bytes_per_pos, int64_t kv_bytes_per_pos, int64_t flops_per_pos,
                            int granularity, int32_t* l_star, double* t_pred);
 
+/* Extension (the paper profiles once, at start-up, and names run-time adaptation as future work in its
+ * Limitations section): keep the two constants of Eq. 10 current while decoding.
+ * kvpr_adapt_update: host arithmetic.  v' = (1 - alpha) v + alpha (work / seconds) for the link rate
+ * (link_bytes over link_seconds) and the GEMM rate (gemm_flops over gemm_seconds); a sample with no work or
+ * no time is skipped.
+ * kvpr_set_adaptive: alpha in (0, 1] makes every layer that is decoded without a timing request record HIP
+ * events around its copies and its recompute GEMM (no waiting); the next planned split (split = -1) first
+ * folds the samples of all finished layers into the context's profile with kvpr_adapt_update.  alpha = 0
+ * (the default) turns it off.  With a chunked activation copy only the link rate is adapted.
+ * kvpr_get_profile: the context's current profile, after folding in finished samples. */
+int kvpr_adapt_update(kvpr_profile_t* prof, double alpha, int64_t link_bytes, double link_seconds,
+                      int64_t gemm_flops, double gemm_seconds);
+int kvpr_set_adaptive(kvpr_ctx* ctx, double alpha);
+int kvpr_get_profile(kvpr_ctx* ctx, kvpr_profile_t* out);
+
 /* One decode step of one attention layer (Sec. 3.2 row-by-row pipeline with partial
  * recomputation; Eq. 1, 2, 3, 5, 7).  `seq` = cached positions s already in the host
  * store; split in [0, seq], or -1 to use the plan from kvpr_set_profile.

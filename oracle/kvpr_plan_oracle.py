@@ -186,3 +186,21 @@ def plan_split_linear(model: int, chunks: int, s: int, x_bpp: int, kv_bpp: int, 
         if t < best_t:
             best_l, best_t = l, t
     return best_l, best_t
+
+
+# --------------------------------------------------------------------------
+# Extension (the paper profiles once, at start-up, and names run-time adaptation as
+# future work in its Limitations section): exponential moving average of the two
+# constants of Eq. 9 / Eq. 10 over what finished layers actually achieved.
+#   v' = (1 - alpha) * v + alpha * (work / seconds)     for each constant whose sample is valid
+# A sample is valid when it has work > 0 and seconds > 0.
+# --------------------------------------------------------------------------
+def adapt_update(v_com: float, v_gpu: float, alpha: float, link_bytes: int, link_s: float,
+                 flops: int, gemm_s: float):
+    if not 0.0 <= alpha <= 1.0:
+        raise ValueError("alpha outside [0, 1]")
+    if link_bytes > 0 and link_s > 0.0:
+        v_com = (1.0 - alpha) * v_com + alpha * (float(link_bytes) / link_s)
+    if flops > 0 and gemm_s > 0.0:
+        v_gpu = (1.0 - alpha) * v_gpu + alpha * (float(flops) / gemm_s)
+    return v_com, v_gpu

@@ -78,6 +78,9 @@ _SIGS = {
     "kvpr_plan_split_chunked": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "kvpr_cost_linear": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i64, _i64, _i64, C.POINTER(C.c_double)]),
     "kvpr_plan_split_linear": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i64, _i64, _i64, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
+    "kvpr_adapt_update": (_i, [C.POINTER(kvpr_profile_t), C.c_double, _i64, C.c_double, _i64, C.c_double]),
+    "kvpr_set_adaptive": (_i, [_vp, C.c_double]),
+    "kvpr_get_profile": (_i, [_vp, C.POINTER(kvpr_profile_t)]),
     "kvpr_layer_decode": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(kvpr_layer_timing)]),
     "kvpr_layer_decode_timed": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, _i]),
     "kvpr_timing_read": (_i, [_vp, _i, C.POINTER(kvpr_layer_timing)]),
@@ -323,3 +326,18 @@ def kvpr_recompute_gemm_rope(a_dev, w_dev, bias_dev, c_dev, M, N, K, ldc, table_
 def kvpr_rope_token(qk32_dev, table_dev, n_pos, pos, batch, hidden, head_dim, q32_dev, k16_dev, ldk, stream=None):
     _check(lib.kvpr_rope_token(_ptr(qk32_dev), _ptr(table_dev), n_pos, pos, batch, hidden, head_dim, _ptr(q32_dev),
                                _ptr(k16_dev), ldk, _stream(stream)))
+
+
+def kvpr_adapt_update(prof, alpha, link_bytes, link_seconds, gemm_flops, gemm_seconds):
+    _check(lib.kvpr_adapt_update(C.byref(prof), alpha, link_bytes, link_seconds, gemm_flops, gemm_seconds))
+    return prof
+
+
+def kvpr_set_adaptive(ctx, alpha):
+    _check(lib.kvpr_set_adaptive(ctx, alpha))
+
+
+def kvpr_get_profile(ctx) -> kvpr_profile_t:
+    p = kvpr_profile_t()
+    _check(lib.kvpr_get_profile(ctx, C.byref(p)))
+    return p

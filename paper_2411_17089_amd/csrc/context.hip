@@ -79,6 +79,12 @@ struct kvpr_ctx {
     std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
     kvpr_profile_t prof{};
     bool have_prof = false;
+    // run-time adaptation of prof (alpha > 0): a small ring of event sets recorded on untimed layers
+    double adapt_alpha = 0.0;
+    static constexpr int kProbes = 8;
+    LayerEvents probe[kProbes]{};
+    bool probe_made = false, probe_pending[kProbes] = {};
+    int probe_next = 0;
     int cost_model = KVPR_COST_EQ10, granularity = 1;
     int debug = 0;
 
@@ -121,9 +127,12 @@ int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn)
     return KVPR_OK;
 }
 
+int adapt_poll(kvpr_ctx* c);
+
 int resolve_split(kvpr_ctx* c, int seq, int split, int32_t* out) {
     if (split == -1) {
         if (!c->have_prof) return fail(KVPR_E_STATE, "split = -1 needs kvpr_set_profile first");
+        if (int rc = adapt_poll(c)) return rc;
         return kvpr_plan_split_linear(&c->prof, c->cost_model, c->plan_chunks(), seq, (int64_t)c->x_store_bytes(),
                                       (int64_t)c->kv_store_bytes(), c->flops_per_pos(), c->granularity, out, nullptr);
     }
@@ -149,6 +158,22 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     // where copies from / to the store land on the device: the float16 buffers, or the packed staging buffers
     char* x_stage = c->qx ? c->dxq[buf] : (char*)dx;
     char* kv_stage = c->qkv ? c->dkvq[buf] : (char*)dkv;
+
+    // adaptive profile: an untimed layer borrows a probe event set (if one is free) so that its copy and
+    // GEMM durations can be read later without any synchronisation
+    int probe_slot = -1;
+    if (!ev && c->adapt_alpha > 0.0 && c->have_prof) {
+        if (!c->probe_made) {
+            for (auto& le : c->probe)
+                for (int i = 0; i < LayerEvents::count; ++i) KVPR_HIP(hipEventCreate(&le.all()[i]));
+            c->probe_made = true;
+        }
+        if (!c->probe_pending[c->probe_next]) {
+            probe_slot = c->probe_next;
+            c->probe_next = (c->probe_next + 1) % kvpr_ctx::kProbes;
+            ev = &c->probe[probe_slot];
+        }
+    }
 
     if (ev) {
         ev->seq = seq;
@@ -285,6 +310,32 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
 
     if (c->x_rows[layer] == seq) c->x_rows[layer] = seq + 1;
     if (c->kv_rows[layer] == seq) c->kv_rows[layer] = seq + 1;
+    if (probe_slot >= 0) c->probe_pending[probe_slot] = true;
+    return KVPR_OK;
+}
+
+// fold the probes that have finished into the profile (no waiting: unfinished probes stay pending)
+int adapt_poll(kvpr_ctx* c) {
+    if (!(c->adapt_alpha > 0.0) || !c->probe_made) return KVPR_OK;
+    for (int i = 0; i < kvpr_ctx::kProbes; ++i) {
+        if (!c->probe_pending[i]) continue;
+        LayerEvents* ev = &c->probe[i];
+        const hipError_t q1 = hipEventQuery(ev->end), q2 = hipEventQuery(ev->c_kv);
+        if (q1 == hipErrorNotReady || q2 == hipErrorNotReady) continue;
+        if (q1 != hipSuccess || q2 != hipSuccess) return fail(KVPR_E_HIP, "probe event query failed");
+        c->probe_pending[i] = false;
+        float ms_x = 0.f, ms_kv = 0.f, ms_rc = 0.f;
+        KVPR_HIP(hipEventElapsedTime(&ms_x, ev->c0, ev->c_x));
+        KVPR_HIP(hipEventElapsedTime(&ms_kv, ev->c_x, ev->c_kv));
+        KVPR_HIP(hipEventElapsedTime(&ms_rc, ev->r0, ev->r1));
+        const int64_t l = ev->split, s = ev->seq;
+        const int64_t link_bytes = (int64_t)c->x_store_bytes() * l + (int64_t)c->kv_store_bytes() * (s - l);
+        // with a chunked activation copy the GEMM interval includes waiting for chunks: the link sample only
+        const int64_t flops = c->chunks > 1 ? 0 : c->flops_per_pos() * l;
+        if (int rc = kvpr_adapt_update(&c->prof, c->adapt_alpha, link_bytes, ((double)ms_x + (double)ms_kv) * 1e-3, flops,
+                                       (double)ms_rc * 1e-3))
+            return rc;
+    }
     return KVPR_OK;
 }
 
@@ -366,6 +417,9 @@ void destroy_impl(kvpr_ctx* c) {
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
     for (auto& le : c->tev)
         for (int i = 0; i < LayerEvents::count; ++i) (void)hipEventDestroy(le.all()[i]);
+    if (c->probe_made)
+        for (auto& le : c->probe)
+            for (int i = 0; i < LayerEvents::count; ++i) (void)hipEventDestroy(le.all()[i]);
     if (c->copy) (void)hipStreamDestroy(c->copy);
     if (c->store) (void)hipStreamDestroy(c->store);
     delete c;
@@ -562,6 +616,21 @@ extern "C" int kvpr_set_profile(kvpr_ctx* c, const kvpr_profile_t* p, int cost_m
     c->cost_model = cost_model;
     c->granularity = granularity;
     c->have_prof = true;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_set_adaptive(kvpr_ctx* c, double alpha) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(KVPR_E_RANGE, "alpha %g outside [0, 1]", alpha);
+    c->adapt_alpha = alpha;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_get_profile(kvpr_ctx* c, kvpr_profile_t* out) {
+    if (!c || !out) return fail(KVPR_E_INVAL, "ctx / out is null");
+    if (!c->have_prof) return fail(KVPR_E_STATE, "no profile was set");
+    if (int rc = adapt_poll(c)) return rc;
+    *out = c->prof;
     return KVPR_OK;
 }
 

@@ -204,3 +204,16 @@ extern "C" int kvpr_plan_split_linear(const kvpr_profile_t* prof, int cost_model
     if (int rc = check_sizes(z, seq)) return rc;
     return plan_impl(prof, cost_model, chunks, seq, z, granularity, l_star, t_pred);
 }
+
+// Extension: run-time adaptation of the two profiled constants (the paper profiles once, at start-up):
+// exponential moving average over what finished layers achieved.  A sample with no work or no time is skipped.
+extern "C" int kvpr_adapt_update(kvpr_profile_t* prof, double alpha, int64_t link_bytes, double link_seconds,
+                                 int64_t gemm_flops, double gemm_seconds) {
+    if (!prof) return kvpr::fail(KVPR_E_INVAL, "profile is null");
+    if (!(alpha >= 0.0 && alpha <= 1.0)) return kvpr::fail(KVPR_E_RANGE, "alpha %g outside [0, 1]", alpha);
+    if (link_bytes > 0 && link_seconds > 0.0)
+        prof->h2d_bytes_per_s = (1.0 - alpha) * prof->h2d_bytes_per_s + alpha * ((double)link_bytes / link_seconds);
+    if (gemm_flops > 0 && gemm_seconds > 0.0)
+        prof->gemm_flops_per_s = (1.0 - alpha) * prof->gemm_flops_per_s + alpha * ((double)gemm_flops / gemm_seconds);
+    return KVPR_OK;
+}

@@ -110,6 +110,22 @@ def test_linear_planner_bit_exact_against_oracle(k):
     assert k.kvpr_int4_row_bytes(100) == 0 and k.kvpr_int4_row_bytes(0) == 0
 
 
+def test_adaptive_update_bit_exact_against_oracle(k):
+    import random
+    rnd = random.Random(5)
+    for _ in range(300):
+        v_com, v_gpu = rnd.uniform(1e9, 9e10), rnd.uniform(1e13, 2e15)
+        alpha = rnd.choice([0.0, 1.0, 0.5, rnd.random()])
+        lb, ls = rnd.choice([0, rnd.randrange(1, 10 ** 10)]), rnd.choice([0.0, rnd.uniform(1e-5, 1e-1)])
+        fl, gs = rnd.choice([0, rnd.randrange(1, 10 ** 13)]), rnd.choice([0.0, rnd.uniform(1e-5, 1e-2)])
+        prof = k.kvpr_adapt_update(k.make_profile(v_com, v_gpu), alpha, lb, ls, fl, gs)
+        assert (prof.h2d_bytes_per_s, prof.gemm_flops_per_s) == po.adapt_update(v_com, v_gpu, alpha, lb, ls, fl, gs)
+    for alpha in (-0.1, 1.5, float("nan")):
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_adapt_update(k.make_profile(1e9, 1e12), alpha, 1, 1.0, 1, 1.0)
+        assert e.value.code == k.KVPR_E_RANGE
+
+
 def test_rotary_table_against_oracle(k):
     from oracle import kvpr_llama_oracle as lo
     import numpy as np

@@ -253,3 +253,43 @@ def test_profile_reports_sane_rates(k):
         assert e.value.code == k.KVPR_E_RANGE
     finally:
         k.kvpr_destroy(ctx)
+
+
+def test_adaptive_profile_tracks_the_measured_rates(k):
+    """Start from a profile whose link rate is 3x too high: untimed decodes record probes, the planner folds them in
+    and the estimate converges to what the copies actually achieve; results stay correct throughout."""
+    from oracle import kvpr_plan_oracle as po
+    b, s, h, H = 16, 512, 1024, 8
+    rig = Rig(k, 31, b, s, h, H)
+    try:
+        ref = ko.layer_decode(rig.layer, 0, rig.stored)["o"]
+        true = k.kvpr_profile(rig.ctx, b, s)
+        wrong = k.make_profile(3.0 * true.h2d_bytes_per_s, true.gemm_flops_per_s)
+        sizes = (b * h * 2, 2 * b * h * 2, 4 * b * h * h)
+        k.kvpr_set_profile(rig.ctx, wrong, k.KVPR_COST_EQ10, 8)
+        l_wrong, _ = k.kvpr_plan_split_linear(wrong, k.KVPR_COST_EQ10, 1, s, *sizes, 8)
+        # alpha = 0: nothing moves
+        for _ in range(3):
+            o, _ = rig.decode(-1)
+        got = k.kvpr_get_profile(rig.ctx)
+        assert got.h2d_bytes_per_s == wrong.h2d_bytes_per_s and got.gemm_flops_per_s == wrong.gemm_flops_per_s
+        k.kvpr_set_adaptive(rig.ctx, 0.5)
+        for i in range(14):
+            print(f"adaptive decode {i}", flush=True)
+            o, _ = rig.decode(-1)
+            assert rel_err(o, ref) <= TIGHT
+        got = k.kvpr_get_profile(rig.ctx)
+        print("link GB/s: wrong %.1f adapted %.1f profiler %.1f; gemm TF: adapted %.0f profiler %.0f" % (
+            wrong.h2d_bytes_per_s / 1e9, got.h2d_bytes_per_s / 1e9, true.h2d_bytes_per_s / 1e9,
+            got.gemm_flops_per_s / 1e12, true.gemm_flops_per_s / 1e12), flush=True)
+        assert got.h2d_bytes_per_s < 1.6 * true.h2d_bytes_per_s          # came down from 3x
+        assert got.h2d_bytes_per_s > 0.3 * true.h2d_bytes_per_s
+        assert 0.2 * true.gemm_flops_per_s < got.gemm_flops_per_s < 3.0 * true.gemm_flops_per_s
+        l_now, _ = k.kvpr_plan_split_linear(got, k.KVPR_COST_EQ10, 1, s, *sizes, 8)
+        want, _ = po.plan_split_linear(po.COST_EQ10, 1, s, *sizes, got.h2d_bytes_per_s, got.gemm_flops_per_s, 8)
+        assert l_now == want and l_now > l_wrong                          # a slower link: recompute more
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_set_adaptive(rig.ctx, 1.5)
+        assert e.value.code == k.KVPR_E_RANGE
+    finally:
+        rig.close()

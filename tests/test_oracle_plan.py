@@ -190,3 +190,22 @@ def test_compressing_only_the_cache_disables_recomputation():
     assert abs(l_both - l_closed) <= 1
     l_fp16, t_fp16 = po.plan_split(po.COST_EQ10, b, s, h, 2, v_com, v_gpu, 1)
     assert l_both < l_fp16 and t_both < t_fp16       # less to send: the GPU takes a smaller share, the step is shorter
+
+
+def test_adaptive_estimate_closed_forms():
+    # alpha = 1 replaces, alpha = 0 keeps, invalid samples are ignored
+    assert po.adapt_update(10.0, 20.0, 1.0, 30, 2.0, 80, 4.0) == (15.0, 20.0)
+    assert po.adapt_update(10.0, 20.0, 0.0, 30, 2.0, 80, 4.0) == (10.0, 20.0)
+    assert po.adapt_update(10.0, 20.0, 0.5, 0, 2.0, 80, 0.0) == (10.0, 20.0)
+    assert po.adapt_update(10.0, 20.0, 0.25, 30, 2.0, 0, 1.0) == (11.25, 20.0)
+    # constant observations: the error decays as (1 - alpha)^n
+    v, g = 100.0, 7.0
+    for n in range(1, 9):
+        v, g = po.adapt_update(v, g, 0.5, 40, 1.0, 3, 1.0)
+        assert math.isclose(v - 40.0, 60.0 * 0.5 ** n, rel_tol=1e-12)
+        assert math.isclose(g - 3.0, 4.0 * 0.5 ** n, rel_tol=1e-12)
+    # a link that slows down moves the split towards more recomputation
+    l_fast, _ = po.plan_split(po.COST_EQ10, 32, 1024, 4096, 2, 57e9, 1.0e15, 64)
+    v2, _ = po.adapt_update(57e9, 1.0e15, 1.0, 300_000_000, 300_000_000 / 28e9, 0, 0.0)
+    l_slow, _ = po.plan_split(po.COST_EQ10, 32, 1024, 4096, 2, v2, 1.0e15, 64)
+    assert l_slow > l_fast
