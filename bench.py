@@ -420,6 +420,26 @@ def main():
                 "frac": h2d_gbps / (prof.h2d_peak_bytes_per_s / 1e9), "bytes_per_step": h2d_bytes},
     }
 
+    # the attention kernel again, 20 launches back to back between one pair of events on the same stream: the
+    # per-layer event pair above also holds the two event-to-kernel gaps (~10 us of a ~90 us kernel)
+    kv_res = torch.randn((s + 1, b, 2 * h), dtype=torch.float16, device="cuda")
+    q_res = torch.randn((b, h), dtype=torch.float32, device="cuda")
+    z_res = torch.empty((b, h), dtype=torch.float16, device="cuda")
+    ws_res = torch.empty(k.kvpr_attention_workspace_bytes(b, h, H, s + 1), dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
+    e1.record()
+    e1.synchronize()
+    ms_attn_b2b = e0.elapsed_time(e1) / 20
+    del kv_res
+    result["roofline_attention"].update({
+        "back_to_back_avg_ms": ms_attn_b2b, "back_to_back_achieved": attn_bytes / (ms_attn_b2b * 1e-3) / 1e9,
+        "back_to_back_frac": attn_bytes / (ms_attn_b2b * 1e-3) / 1e9 / PEAK_HBM_GBPS})
+
     if args.extension_chunks > 1 and args.chunks == 1 and cm == k.KVPR_COST_EQ10 and args.split < 0:
         # same layer, same number of steps, X[0:l] copied in parts with each part's GEMM started as it lands
         c = args.extension_chunks

@@ -77,7 +77,7 @@ extern "C" {
 #define KVPR_COST_NS   1
 #define KVPR_COST_ROW  2
 /* Extension (not in the paper): steady state of the layer pipeline, where the next layer's
- * transfers overlap this layer's compute: max((M_X + M_KV)/v_com, t_recomp). */
+ * transfers overlap this layer's compute: max((M_X + M_KV)/v_com, t_recomp + layer_other_s). */
 #define KVPR_COST_PIPE 3
 
 /* debug flags for kvpr_set_debug */
@@ -110,6 +110,9 @@ typedef struct {
     double d2h_bytes_per_s;      /* reported only */
     double attn_bytes_per_s;     /* reported only: decode attention's KV read rate           */
     double h2d_peak_bytes_per_s; /* reported only: best rate over a 64 KiB .. 1 GiB sweep    */
+    double layer_other_s;        /* the rest of one layer's GPU work at this batch / context (token projections,
+                                    attention, output projection, FFN if the context has one): used by
+                                    KVPR_COST_PIPE only, where it shares the GPU with the recomputation; 0 = ignore */
 } kvpr_profile_t;
 
 /* Device pointers to one layer's parameters.  FFN / LayerNorm members may be null when ffn_dim == 0.

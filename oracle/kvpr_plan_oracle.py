@@ -23,9 +23,11 @@ Three cost forms are provided:
              charged only to the compute arm, as if it travelled on a second
              link.  Not in the paper; kept because the benchmark spec
              paraphrases the cost this way.
-  COST_PIPE  max((M_X + M_KV)/v_com, t_recomp): steady state when the next layer's
-             transfers overlap this layer's compute (double buffering across layers,
-             Sec. 4 "Implementation").  An extension: the paper does not model it.
+  COST_PIPE  max((M_X + M_KV)/v_com, t_recomp + t_other): steady state when the next
+             layer's transfers overlap this layer's compute (double buffering across
+             layers, Sec. 4 "Implementation"); t_other (default 0) is the rest of a
+             layer's compute, which shares the GPU with the recomputation.  An
+             extension: the paper does not model it.
 
 Readings where the paper is silent: the integer problem is solved exactly by
 enumeration, scanning l upward and keeping the first strict minimum (ties go to
@@ -58,7 +60,7 @@ def flops_recompute(b: int, l: int, h: int) -> int:
 
 
 def cost(model: int, l: int, b: int, s: int, h: int, p: int,
-         v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0) -> float:
+         v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0) -> float:
     """Predicted time of one layer's KV assembly at split l (seconds)."""
     t_act = float(bytes_x(b, l, h, p)) / v_com
     t_kv = float(bytes_kv(b, l, s, h, p)) / v_com
@@ -75,7 +77,7 @@ def cost(model: int, l: int, b: int, s: int, h: int, p: int,
     if model == COST_NS:
         return max(t_rc + t_act, t_kv)
     if model == COST_PIPE:
-        return max(t_act + t_kv, t_rc)
+        return max(t_act + t_kv, t_rc + other)
     raise ValueError(f"unknown cost model {model}")
 
 
@@ -90,11 +92,11 @@ def candidates(s: int, granularity: int = 1):
 
 
 def plan_split(model: int, b: int, s: int, h: int, p: int, v_com: float, v_gpu: float,
-               granularity: int = 1, lat_com: float = 0.0, lat_gpu: float = 0.0):
+               granularity: int = 1, lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0):
     """Eq. 11 by enumeration.  Returns (l*, t(l*))."""
     best_l, best_t = -1, float("inf")
     for l in candidates(s, granularity):
-        t = cost(model, l, b, s, h, p, v_com, v_gpu, lat_com, lat_gpu)
+        t = cost(model, l, b, s, h, p, v_com, v_gpu, lat_com, lat_gpu, other)
         if t < best_t:
             best_l, best_t = l, t
     return best_l, best_t
@@ -141,7 +143,7 @@ def plan_split_chunked(chunks: int, b: int, s: int, h: int, p: int, v_com: float
 # byte rates.  chunks > 1 selects the chunked-copy extension above (Eq. 10 only).
 # --------------------------------------------------------------------------
 def cost_linear(model: int, chunks: int, l: int, s: int, x_bpp: int, kv_bpp: int, flops_pp: int,
-                v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0) -> float:
+                v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0) -> float:
     m_x = x_bpp * l
     m_kv = kv_bpp * (s - l)
     n_kv = flops_pp * l
@@ -173,16 +175,16 @@ def cost_linear(model: int, chunks: int, l: int, s: int, x_bpp: int, kv_bpp: int
     if model == COST_NS:
         return max(gemm + send_x, send_kv)
     if model == COST_PIPE:
-        return max(send_x + send_kv, gemm)
+        return max(send_x + send_kv, gemm + other)
     raise ValueError(f"unknown cost model {model}")
 
 
 def plan_split_linear(model: int, chunks: int, s: int, x_bpp: int, kv_bpp: int, flops_pp: int,
                       v_com: float, v_gpu: float, granularity: int = 1,
-                      lat_com: float = 0.0, lat_gpu: float = 0.0):
+                      lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0):
     best_l, best_t = -1, float("inf")
     for l in candidates(s, granularity):
-        t = cost_linear(model, chunks, l, s, x_bpp, kv_bpp, flops_pp, v_com, v_gpu, lat_com, lat_gpu)
+        t = cost_linear(model, chunks, l, s, x_bpp, kv_bpp, flops_pp, v_com, v_gpu, lat_com, lat_gpu, other)
         if t < best_t:
             best_l, best_t = l, t
     return best_l, best_t

@@ -1099,9 +1099,12 @@ extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out
 
     // v_gpu: the recompute GEMM at M = batch*seq on random operands
     half* wtmp = nullptr;
-    if (hipMalloc((void**)&wtmp, (size_t)2 * h * h * sizeof(half)) != hipSuccess)
+    // big enough for the widest matrix of the layer: [Wq;Wk;Wv], or one FFN matrix ([gate;up] for the gated FFN)
+    const size_t ffn_rows = (size_t)c->d.ffn_dim * (c->llama ? 2 : 1);
+    const size_t wtmp_halfs = std::max((size_t)3 * h, ffn_rows) * h;
+    if (hipMalloc((void**)&wtmp, wtmp_halfs * sizeof(half)) != hipSuccess)
         return fail(KVPR_E_NOMEM, "profiler weight buffer");
-    int rc = kvpr::launch_fill_random(wtmp, (size_t)2 * h * h, 0.035f, 1u, c->compute);
+    int rc = kvpr::launch_fill_random(wtmp, wtmp_halfs, 0.035f, 1u, c->compute);
     if (!rc) rc = kvpr::launch_fill_random(c->dx[0], (size_t)rows * h, 1.7f, 2u, c->compute);
     if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
             // rotary models: positions as if the context's batch held these rows (the rotation costs the same anywhere)
@@ -1118,6 +1121,20 @@ extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out
         if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
                 return kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, c->d.batch, h, c->d.n_heads, c->compute); }, &t);
         if (!rc) p.attn_bytes_per_s = (double)S * c->d.batch * 2 * h * sizeof(half) / t;
+        // the rest of a layer's GPU work besides the recomputation: projections, attention, FFN (random weights)
+        if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
+                const int b = c->d.batch, f = c->d.ffn_dim;
+                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, c->q32, dkv, b, 3 * h, h, h, 2 * (int64_t)h, 0, c->compute)) return r;
+                if (int r = kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, b, h, c->d.n_heads, c->compute)) return r;
+                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, dkv, b, h, h, 0, h, 0, c->compute)) return r;
+                if (f > 0) {
+                    const int f1 = (int)ffn_rows;
+                    half* prod = c->ffn1 + (c->llama ? (size_t)b * 2 * f : 0);
+                    if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, c->ffn1, b, f1, h, 0, f1, 1, c->compute)) return r;
+                    if (int r = kvpr::launch_token_gemm_flags(prod, wtmp, nullptr, nullptr, dkv, b, h, f, 0, h, 0, c->compute)) return r;
+                }
+                return KVPR_OK; }, &t);
+        if (!rc) p.layer_other_s = t;
     }
     (void)hipDeviceSynchronize();
     (void)hipFree(wtmp);

@@ -32,7 +32,7 @@ int check_profile(const kvpr_profile_t* p, int model, int chunks) {
     if (!rate_ok(p->h2d_bytes_per_s) || !rate_ok(p->gemm_flops_per_s))
         return kvpr::fail(KVPR_E_INVAL, "profile rates must be finite and > 0 (v_com=%g, v_gpu=%g)",
                           p->h2d_bytes_per_s, p->gemm_flops_per_s);
-    if (!lat_ok(p->h2d_latency_s) || !lat_ok(p->gemm_latency_s))
+    if (!lat_ok(p->h2d_latency_s) || !lat_ok(p->gemm_latency_s) || !lat_ok(p->layer_other_s))
         return kvpr::fail(KVPR_E_INVAL, "profile latencies must be finite and >= 0");
     return KVPR_OK;
 }
@@ -77,8 +77,8 @@ double cost_at(const kvpr_profile_t* p, int model, int64_t l, int64_t s, const S
             return arm > t_kv ? arm : t_kv;
         }
         case KVPR_COST_PIPE: {
-            const double link = t_act + t_kv;
-            return link > t_rc ? link : t_rc;
+            const double link = t_act + t_kv, gpu = t_rc + p->layer_other_s;
+            return link > gpu ? link : gpu;
         }
         default: return t_act + (t_rc > t_kv ? t_rc : t_kv);
     }

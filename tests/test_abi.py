@@ -52,6 +52,15 @@ def test_planner_bit_exact_against_oracle(k, model, cname):
 def test_planner_ties_and_latency_terms(k):
     prof = k.make_profile(1.0, 4.0)
     assert k.kvpr_plan_split(prof, k.KVPR_COST_NS, 1, 9, 1, 1, 1) == (4, 10.0)     # tie 4/5 -> smallest
+    # steady-state form with the rest of the layer's GPU work on the compute arm
+    for other in (0.0, 4e-4, 3e-3):
+        prof = k.make_profile(57e9, 1.0e15, 0.0, 0.0, other)
+        for s in (256, 1024):
+            assert k.kvpr_plan_split(prof, k.KVPR_COST_PIPE, 32, s, 4096, 2, 8) == \
+                po.plan_split(po.COST_PIPE, 32, s, 4096, 2, 57e9, 1.0e15, 8, 0.0, 0.0, other)
+            for l in (0, s // 2, s):
+                assert k.kvpr_cost(prof, k.KVPR_COST_PIPE, l, 32, s, 4096, 2) == po.cost(po.COST_PIPE, l, 32, s, 4096, 2, 57e9, 1.0e15, 0.0, 0.0, other)
+                assert k.kvpr_cost(prof, k.KVPR_COST_EQ10, l, 32, s, 4096, 2) == po.cost(po.COST_EQ10, l, 32, s, 4096, 2, 57e9, 1.0e15)
     prof = k.make_profile(57e9, 1.2e15, 1e-3, 5e-4)
     for s in (100, 1024):
         want = po.plan_split(po.COST_EQ10, 32, s, 4096, 2, 57e9, 1.2e15, 1, 1e-3, 5e-4)

@@ -247,12 +247,21 @@ def test_profile_reports_sane_rates(k):
         assert 1e12 < p.gemm_flops_per_s < 2.6e15
         assert 1e10 < p.attn_bytes_per_s < 8.5e12
         assert p.h2d_latency_s == 0.0 and p.gemm_latency_s == 0.0
+        assert 2e-6 < p.layer_other_s < 5e-3                   # projections + attention of a small layer
         k.kvpr_set_profile(ctx, p, k.KVPR_COST_EQ10, 1)
         with pytest.raises(k.KvprError) as e:
             k.kvpr_profile(ctx, 8, 300)                      # batch*seq beyond the context
         assert e.value.code == k.KVPR_E_RANGE
     finally:
         k.kvpr_destroy(ctx)
+    # a full decoder layer (both FFN kinds): the FFN is part of the rest-of-layer time
+    for arch, ffn in ((k.KVPR_ARCH_OPT, 4096), (k.KVPR_ARCH_LLAMA, 2816)):
+        ctx = k.kvpr_create(2, 1024, 8, 128, ffn, 8, 300, arch=arch)
+        try:
+            p2 = k.kvpr_profile(ctx, 8, 256)
+            assert p2.layer_other_s > p.layer_other_s * 0.8 and p2.layer_other_s < 5e-3
+        finally:
+            k.kvpr_destroy(ctx)
 
 
 def test_adaptive_profile_tracks_the_measured_rates(k):

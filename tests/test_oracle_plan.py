@@ -209,3 +209,14 @@ def test_adaptive_estimate_closed_forms():
     v2, _ = po.adapt_update(57e9, 1.0e15, 1.0, 300_000_000, 300_000_000 / 28e9, 0, 0.0)
     l_slow, _ = po.plan_split(po.COST_EQ10, 32, 1024, 4096, 2, v2, 1.0e15, 64)
     assert l_slow > l_fast
+
+
+def test_pipelined_form_with_the_rest_of_the_layer():
+    # link 1 B/s, GPU 4 flop/s, b = h = p = 1, s = 9: link(l) = 18 - l, gemm(l) = l; other = 3 -> balance at 18 - l = l + 3
+    toy = dict(b=1, s=9, h=1, p=1, v_com=1.0, v_gpu=4.0)
+    assert [po.cost(po.COST_PIPE, l, **toy, other=3.0) for l in (0, 7, 8, 9)] == [18.0, 11.0, 11.0, 12.0]
+    assert po.plan_split(po.COST_PIPE, **toy, other=3.0) == (7, 11.0)
+    assert po.plan_split(po.COST_PIPE, **toy) == (9, 9.0)                 # without it: recompute everything
+    # the other forms ignore it
+    assert po.cost(po.COST_EQ10, 4, **toy, other=3.0) == po.cost(po.COST_EQ10, 4, **toy)
+    assert po.cost_linear(po.COST_PIPE, 1, 7, 9, 1, 2, 4, 1.0, 4.0, other=3.0) == 11.0
