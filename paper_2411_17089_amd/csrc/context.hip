@@ -48,6 +48,8 @@ struct kvpr_ctx {
     char* dxq[2] = {nullptr, nullptr};   // device staging for packed rows (only when compressed)
     char* dkvq[2] = {nullptr, nullptr};
     std::vector<int> x_rows, kv_rows;    // contiguous prefix of rows known to hold data
+    std::vector<hipEvent_t> ev_slot_store;   // per slot: "the last store-back into this slot's host rows is done"
+    std::vector<bool> slot_store_recorded;
     int nbuf = 0;
     half* dx[2] = {nullptr, nullptr};
     half* dkv[2] = {nullptr, nullptr};
@@ -194,6 +196,8 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
 
     // ---- copy stream: activations first, then the rest of the cache (the order Eq. 10 assumes) ----
     if (c->free_recorded[buf]) KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_free[buf], 0));
+    // the previous token's store-back wrote host row seq-1 of this slot, which the copies below may read
+    if (c->slot_store_recorded[layer]) KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_slot_store[layer], 0));
     if (ev) KVPR_HIP(hipEventRecord(ev->c0, c->copy));
     // chunk boundaries: equal parts of [0, l) rounded down to multiples of 8 positions (whole GEMM tile rows
     // at batch 32); a single chunk is the paper's schedule
@@ -246,6 +250,8 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
         KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xsb, c->qx ? (const void*)(x_stage + (size_t)seq * xsb) : (const void*)x_new,
                                 xsb, hipMemcpyDeviceToHost, c->store));
         KVPR_HIP(hipEventRecord(c->ev_store, c->store));
+        KVPR_HIP(hipEventRecord(c->ev_slot_store[layer], c->store));
+        c->slot_store_recorded[layer] = true;
         if (ev) KVPR_HIP(hipEventRecord(ev->s1, c->store));
         return debug_sync(c);
     };
@@ -392,6 +398,7 @@ void destroy_impl(kvpr_ctx* c) {
     if (c->copy) (void)hipStreamSynchronize(c->copy);
     if (c->store) (void)hipStreamSynchronize(c->store);
     (void)hipStreamSynchronize(c->compute);
+    for (hipEvent_t e : c->ev_slot_store) if (e) (void)hipEventDestroy(e);
     for (auto p : c->hx) if (p) (void)hipHostFree(p);
     for (auto p : c->hkv) if (p) (void)hipHostFree(p);
     for (int i = 0; i < 2; ++i) {
@@ -518,7 +525,10 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     c->hkv.assign(slots, nullptr);
     c->x_rows.assign(slots, 0);
     c->kv_rows.assign(slots, 0);
+    c->ev_slot_store.assign(slots, nullptr);
+    c->slot_store_recorded.assign(slots, false);
     for (int i = 0; i < slots; ++i) {
+        if ((e = hipEventCreateWithFlags(&c->ev_slot_store[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
         if ((e = hipHostMalloc((void**)&c->hx[i], xs_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned X store", e);
         if ((e = hipHostMalloc((void**)&c->hkv[i], kvs_bytes, hipHostMallocDefault)) != hipSuccess) return bail(KVPR_E_NOMEM, "pinned KV store", e);
     }
