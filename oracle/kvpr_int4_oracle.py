@@ -5,7 +5,7 @@ It shares no code with the HIP library and never imports it.
 
 The paper (Sec. 4.4, "KV Cache Compression") says only that the transferred cache is compressed
 with group-wise 4-bit quantization; it fixes neither the group shape nor the rounding.  The
-reading implemented here (and stated in the design notes):
+reading implemented here:
 
   * a group is 64 consecutive columns of one row of one sequence: a cache row [K(h) | V(h)], or, when
     the stored activations are compressed as well, an activation row X(h).  Compressing only the

@@ -16,7 +16,7 @@ in numpy float64, one function per equation of the paper:
   Sec. 3.2, "partial recomputation": the GPU merges recomputed rows [0,l) with
                                transferred rows [l,s)
 
-Readings where the paper is silent (all listed in the design notes):
+Readings where the paper is silent:
   * projections carry a bias (OPT has one); bias 0 gives the paper's equations;
   * heads are contiguous blocks of d_head columns; softmax subtracts the row max;
   * no mask: the one new token attends to all s+1 positions;
