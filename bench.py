@@ -371,9 +371,12 @@ def main():
     ms_act, ms_kv = mean("ms_act_copy"), mean("ms_kv_copy")
     gemm_flops = 4.0 * b * split * h * h
     attn_bytes = 2.0 * b * (s + 1) * h * 2
+    # with a packed cache the event pair brackets only the phase after the cache fence: packed rows [l, s) read once
+    attn_phase_bytes = float(kv_bpp * (s - split)) if qflags & k.KVPR_KV_INT4 else attn_bytes
+    attn_kernel = "attention_partial_ranged over the packed rows (+combine)" if qflags & k.KVPR_KV_INT4 else "attention_partial (+combine)"
     h2d_bytes = float(x_bpp * split + kv_bpp * (s - split))
     gemm_tflops = gemm_flops / (ms_gemm * 1e-3) / 1e12 if split > 0 else 0.0
-    attn_gbps = attn_bytes / (ms_attn * 1e-3) / 1e9
+    attn_gbps = attn_phase_bytes / (ms_attn * 1e-3) / 1e9
     h2d_gbps = h2d_bytes / ((ms_act + ms_kv) * 1e-3) / 1e9
 
     # HBM-side bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a
@@ -413,9 +416,9 @@ def main():
         "roofline": {"kernel": "gemm_bias_f16 (recompute GEMM%s)" % (", rotary epilogue" if llama else ""), "bound": "mfma", "achieved": gemm_tflops,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
                      "traffic": traffic, "traffic_detail": traffic_detail, "flops_per_launch": gemm_flops, "avg_ms": ms_gemm},
-        "roofline_attention": {"kernel": "attention_partial (+combine)", "bound": "hbm", "achieved": attn_gbps,
+        "roofline_attention": {"kernel": attn_kernel, "bound": "hbm", "achieved": attn_gbps,
                                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": attn_gbps / PEAK_HBM_GBPS,
-                               "bytes_per_launch": attn_bytes, "avg_ms": ms_attn},
+                               "bytes_per_launch": attn_phase_bytes, "avg_ms": ms_attn},
         "h2d": {"achieved_GBps": h2d_gbps, "measured_pinned_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
                 "frac": h2d_gbps / (prof.h2d_peak_bytes_per_s / 1e9), "bytes_per_step": h2d_bytes},
     }
@@ -437,6 +440,7 @@ def main():
     ms_attn_b2b = e0.elapsed_time(e1) / 20
     del kv_res
     result["roofline_attention"].update({
+        "back_to_back_kernel": "attention_partial over float16 rows", "back_to_back_bytes": attn_bytes,
         "back_to_back_avg_ms": ms_attn_b2b, "back_to_back_achieved": attn_bytes / (ms_attn_b2b * 1e-3) / 1e9,
         "back_to_back_frac": attn_bytes / (ms_attn_b2b * 1e-3) / 1e9 / PEAK_HBM_GBPS})
 

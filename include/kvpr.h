@@ -141,8 +141,9 @@ typedef struct {
     float ms_total;      /* first enqueue -> output projection and store-back done     */
     double t_bound_s;    /* cost-model prediction for the split used (0 if no profile) */
     int32_t split;       /* the split l actually used                                   */
-    float ms_dequant;    /* dequantisation of the transferred cache rows (0 without KVPR_KV_INT4); the
-                            activations' dequantisation is part of ms_recompute        */
+    float ms_dequant;    /* reserved (0): packed cache rows are dequantised inside the attention kernel; the
+                            activations' dequantisation is part of ms_recompute.  With KVPR_KV_INT4, ms_attn
+                            covers only the attention phase that follows the cache copy       */
 } kvpr_layer_timing;
 
 const char* kvpr_last_error(void);
@@ -287,6 +288,13 @@ int kvpr_recompute_gemm(const void* a_dev, const void* w_dev, const void* bias_d
 int kvpr_decode_attention(const void* q_dev, const void* kv_dev, void* z_dev, void* ws_dev,
                           int S, int batch, int hidden, int n_heads, void* stream);
 size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S);
+/* The same attention (Eq. 2) over a cache whose rows [split, S-1) are still in the packed 4-bit form of the
+ * host store (Sec. 4.4): rows [0, split) and row S-1 are read from kv16_dev (float16 [S, batch, 2*hidden]),
+ * rows [split, S-1) from kvq_dev ([S, batch, kvpr_int4_row_bytes(2*hidden)], indexed by position) and
+ * dequantised in registers to exactly the values kvpr_dequant_int4 gives.  Same workspace size as above.
+ * split in [0, S-1]; kvq_dev may be null when split == S-1. */
+int kvpr_decode_attention_mixed(const void* q_dev, const void* kv16_dev, const void* kvq_dev, void* z_dev, void* ws_dev,
+                                int S, int split, int batch, int hidden, int n_heads, void* stream);
 
 /* y[M, N] = x[M, K] . W[N, K]^T + bias for small M (the decode token's projections).
  * out_f32_cols: the first out_f32_cols columns are written as float32 to y32_dev [M, out_f32_cols]

@@ -92,6 +92,7 @@ _SIGS = {
     "kvpr_recompute_gemm": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp]),
     "kvpr_decode_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "kvpr_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
+    "kvpr_decode_attention_mixed": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "kvpr_token_gemm": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
     "kvpr_rope_table": (_i, [_vp, _i, _i, C.c_double]),
     "kvpr_recompute_gemm_rope": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp, _i, _i, _i, _i, _i, _vp]),
@@ -341,3 +342,8 @@ def kvpr_get_profile(ctx) -> kvpr_profile_t:
     p = kvpr_profile_t()
     _check(lib.kvpr_get_profile(ctx, C.byref(p)))
     return p
+
+
+def kvpr_decode_attention_mixed(q_dev, kv16_dev, kvq_dev, z_dev, ws_dev, S, split, batch, hidden, n_heads, stream=None):
+    _check(lib.kvpr_decode_attention_mixed(_ptr(q_dev), _ptr(kv16_dev), _ptr(kvq_dev), _ptr(z_dev), _ptr(ws_dev), S, split,
+                                           batch, hidden, n_heads, _stream(stream)))

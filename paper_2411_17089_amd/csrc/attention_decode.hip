@@ -16,6 +16,14 @@
 //   - waves are merged through LDS; only when (column groups x batch) workgroups cannot fill the
 //     chip are positions also split across workgroups ("splits"), merged through a float32
 //     workspace and a small combine kernel.
+//
+// Mixed-source variant for a 4-bit host store (Sec. 4.4): attention_partial_ranged takes a range of
+// positions (plus, optionally, one extra position) from either the float16 buffer or the packed staging
+// buffer [position][batch][9h/8 bytes] and always leaves a partial (m, l, acc) in the workspace.  The
+// runtime launches it over the recomputed rows [0, l) and the new row as soon as they exist, and over the
+// packed rows [l, s) once they have landed: those are dequantised in registers (4 bytes of codes per lane
+// and half, value = float16(code * scale + mn) exactly as the standalone codec), so they are never
+// expanded in HBM.  One combine kernel merges all partials.
 #include "kvpr_internal.h"
 #include <math.h>
 
@@ -168,6 +176,146 @@ __global__ __launch_bounds__(256) void attention_combine(const float* __restrict
     *reinterpret_cast<half8*>(z + (int64_t)n * h + c * 8) = out;
 }
 
+// merge the waves' running (max, sum, acc) through LDS; wave 0 returns the workgroup's partial in (m, l, o)
+template <int ATT_WAVES>
+__device__ __forceinline__ bool merge_waves(float (*sm)[10][64], int wave, int lane, float& m_run, float& l_run, float (&acc)[8]) {
+    sm[wave][0][lane] = m_run;
+    sm[wave][1][lane] = l_run;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sm[wave][2 + e][lane] = acc[e];
+    __syncthreads();
+    if (wave != 0) return false;
+    float m_tot = m_run;
+#pragma unroll
+    for (int w = 1; w < ATT_WAVES; ++w) m_tot = fmaxf(m_tot, sm[w][0][lane]);
+    float l_tot = 0.f;
+    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < ATT_WAVES; ++w) {
+        const float mw = sm[w][0][lane];
+        const float wt = (mw == -INFINITY) ? 0.f : exp2f(mw - m_tot);
+        l_tot += sm[w][1][lane] * wt;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] += sm[w][2 + e][lane] * wt;
+    }
+    m_run = m_tot;
+    l_run = l_tot;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = o[e];
+    return true;
+}
+
+// Positions pos0 .. pos0 + n_pos - 1, then extra_pos if it is >= 0.  PACKED = false: rows of kv16 [*, batch, 2h]
+// float16.  PACKED = true: rows of kvq [*, batch, 9h/8] (h bytes of codes: K then V, then h/32 + h/32 (scale, mn)
+// float16 pairs, one per 64 columns).  Always writes partial slot split_base + blockIdx.z.
+template <int D, int UNROLL, int ATT_WAVES, bool PACKED>
+__global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_ranged(
+    const float* __restrict__ q, const _Float16* __restrict__ kv16, const uint8_t* __restrict__ kvq,
+    float* __restrict__ ws_acc, float* __restrict__ ws_ml, int pos0, int n_pos, int extra_pos, int batch, int h,
+    int chunk, int split_base, float scale_log2) {
+    const int cg = blockIdx.x, n = blockIdx.y, sp = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = cg * COLS_PER_GROUP + lane * 8;
+    const bool active = col < h;
+    const int ccol = active ? col : 0;
+    float qf[8];
+    {
+        const float4 q0 = *reinterpret_cast<const float4*>(q + (int64_t)n * h + ccol);
+        const float4 q1 = *reinterpret_cast<const float4*>(q + (int64_t)n * h + ccol + 4);
+        qf[0] = q0.x * scale_log2; qf[1] = q0.y * scale_log2; qf[2] = q0.z * scale_log2; qf[3] = q0.w * scale_log2;
+        qf[4] = q1.x * scale_log2; qf[5] = q1.y * scale_log2; qf[6] = q1.z * scale_log2; qf[7] = q1.w * scale_log2;
+    }
+    const int n_total = n_pos + (extra_pos >= 0 ? 1 : 0);
+    const int j0 = sp * chunk;
+    const int j1 = min(n_total, j0 + chunk);
+    auto position = [&](int j) { return j < n_pos ? pos0 + j : extra_pos; };
+
+    // float16 source
+    const int64_t row_stride = (int64_t)batch * 2 * h;
+    const _Float16* kbase = kv16 + (int64_t)n * 2 * h + ccol;
+    // packed source: byte offsets inside a packed row of this sequence
+    const int64_t qrow_stride = (int64_t)batch * (h + h / 8);
+    const uint8_t* qbase = kvq + (int64_t)n * (h + h / 8);
+    const int k_code = ccol / 2, v_code = (h + ccol) / 2;
+    const int k_meta = h + (ccol / 64) * 4, v_meta = h + ((h + ccol) / 64) * 4;
+
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = j0 + wave * UNROLL; j < j1; j += ATT_WAVES * UNROLL) {
+        float kf[UNROLL][8], vf[UNROLL][8];
+        if (PACKED) {
+            uint32_t kc[UNROLL], vc[UNROLL], km[UNROLL], vm[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint8_t* row = qbase + (int64_t)position(min(j + u, j1 - 1)) * qrow_stride;
+                kc[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + k_code));
+                vc[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + v_code));
+                km[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + k_meta));
+                vm[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + v_meta));
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                union { uint32_t w; _Float16 hh[2]; } a, b;
+                a.w = km[u];
+                b.w = vm[u];
+                const float ks = (float)a.hh[0], kmn = (float)a.hh[1], vs = (float)b.hh[0], vmn = (float)b.hh[1];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    // the value the codec defines: float16(code * scale + mn)
+                    kf[u][e] = (float)(_Float16)((float)((kc[u] >> (4 * e)) & 15u) * ks + kmn);
+                    vf[u][e] = (float)(_Float16)((float)((vc[u] >> (4 * e)) & 15u) * vs + vmn);
+                }
+            }
+        } else {
+            half8 kh[UNROLL], vh[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const _Float16* row = kbase + (int64_t)position(min(j + u, j1 - 1)) * row_stride;
+                kh[u] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(row));
+                vh[u] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(row + h));
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    kf[u][e] = (float)kh[u][e];
+                    vf[u][e] = (float)vh[u][e];
+                }
+        }
+        float sc[UNROLL];
+        float m_new = m_run;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d = fmaf(kf[u][e], qf[e], d);
+            d = head_sum<D>(d);
+            sc[u] = (j + u < j1) ? d : -INFINITY;
+            m_new = fmaxf(m_new, sc[u]);
+        }
+        const float rescale = exp2f(m_run - m_new);
+        l_run *= rescale;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= rescale;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const float p = exp2f(sc[u] - m_new);
+            l_run += p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, vf[u][e], acc[e]);
+        }
+        m_run = m_new;
+    }
+    __shared__ float sm[ATT_WAVES][10][64];
+    if (!merge_waves<ATT_WAVES>(sm, wave, lane, m_run, l_run, acc) || !active) return;
+    const int slot = split_base + sp;
+    float* a = ws_acc + ((int64_t)slot * batch + n) * h + col;
+    *reinterpret_cast<float4*>(a) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(a + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    float* ml = ws_ml + (((int64_t)slot * batch + n) * (h / 8) + col / 8) * 2;
+    *reinterpret_cast<float2*>(ml) = make_float2(m_run, l_run);
+}
+
 int g_attn_target_blocks = 256;   // one workgroup per CU: the fewest position splits that fill the chip
 int g_attn_cfg = 1;       // (unroll, waves per workgroup) choice, see launch_attention
 int g_attn_force_splits = 0;
@@ -235,6 +383,65 @@ int launch_attention(const void* q, const void* kv, void* z, void* ws, int S, in
                            (_Float16*)z, batch, hidden, sp.splits);
         KVPR_HIP(hipGetLastError());
     }
+    return KVPR_OK;
+}
+
+// ---- mixed float16 / packed attention in two phases (see the header comment) ----
+namespace {
+
+struct MixedPlan { SplitPlan a, b; int total; };
+MixedPlan plan_mixed(int batch, int hidden, int S, int split) {
+    MixedPlan p;
+    p.a = plan_splits(batch, hidden, split + 1);                    // rows [0, split) and the new row
+    const int nb = S - 1 - split;                                   // packed rows
+    p.b = nb > 0 ? plan_splits(batch, hidden, nb) : SplitPlan{0, 0};
+    auto cap = [](SplitPlan& sp, int n) {                           // 256 + 256 partial slots fit the workspace bound
+        if (sp.splits > 256) { sp.chunk = (n + 255) / 256; sp.splits = (n + sp.chunk - 1) / sp.chunk; }
+    };
+    cap(p.a, split + 1);
+    if (nb > 0) cap(p.b, nb);
+    p.total = p.a.splits + p.b.splits;
+    return p;
+}
+
+template <bool PACKED>
+int launch_ranged(const void* q, const void* kv16, const void* kvq, float* ws_acc, float* ws_ml, int pos0, int n_pos,
+                  int extra_pos, int batch, int hidden, int d, SplitPlan sp, int split_base, hipStream_t st) {
+    const int groups = (hidden + COLS_PER_GROUP - 1) / COLS_PER_GROUP;
+    const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)d));
+    dim3 grid(groups, batch, sp.splits);
+    if (d == 128)
+        hipLaunchKernelGGL((attention_partial_ranged<128, 8, 4, PACKED>), grid, dim3(256), 0, st, (const float*)q,
+                           (const _Float16*)kv16, (const uint8_t*)kvq, ws_acc, ws_ml, pos0, n_pos, extra_pos, batch, hidden,
+                           sp.chunk, split_base, scale_log2);
+    else
+        hipLaunchKernelGGL((attention_partial_ranged<64, 8, 4, PACKED>), grid, dim3(256), 0, st, (const float*)q,
+                           (const _Float16*)kv16, (const uint8_t*)kvq, ws_acc, ws_ml, pos0, n_pos, extra_pos, batch, hidden,
+                           sp.chunk, split_base, scale_log2);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+}  // namespace
+
+// phase 0: float16 rows [0, split) and row S-1 of kv16.  phase 1: packed rows [split, S-1) of kvq, then the combine
+// into z.  Both phases of one attention must be given the same S, split, batch and hidden.
+int launch_attention_mixed(const void* q, const void* kv16, const void* kvq, void* z, void* ws, int S, int split, int batch,
+                           int hidden, int n_heads, int phase, hipStream_t st) {
+    const int d = hidden / n_heads;
+    const MixedPlan p = plan_mixed(batch, hidden, S, split);
+    float* ws_acc = (float*)ws;
+    float* ws_ml = ws_acc + (int64_t)p.total * batch * hidden;
+    if (phase == 0)
+        return launch_ranged<false>(q, kv16, kvq, ws_acc, ws_ml, 0, split, S - 1, batch, hidden, d, p.a, 0, st);
+    if (p.b.splits > 0)
+        if (int rc = launch_ranged<true>(q, kv16, kvq, ws_acc, ws_ml, split, S - 1 - split, -1, batch, hidden, d, p.b,
+                                         p.a.splits, st))
+            return rc;
+    const int64_t threads = (int64_t)batch * (hidden / 8);
+    hipLaunchKernelGGL(attention_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ws_acc, ws_ml,
+                       (_Float16*)z, batch, hidden, p.total);
+    KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }
 

@@ -294,13 +294,16 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     }
 
     // ---- merge = wait for the transferred rows; then attention over all seq+1 rows (Eq. 2) ----
+    // With a packed cache the attention runs in two phases: the recomputed rows and the new row (float16) before the
+    // wait, the transferred rows straight from their packed form after it (dequantised in registers), one combine.
+    if (c->qkv)
+        if (int rc = kvpr::launch_attention_mixed(c->q32, dkv, kv_stage, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 0, c->compute))
+            return rc;
     KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_kv[buf], 0));
     if (ev) KVPR_HIP(hipEventRecord(ev->d0, c->compute));
-    if (c->qkv && l < seq)
-        if (int rc = kvpr::launch_dequant_int4(kv_stage + (size_t)l * ksb, dkv + (size_t)l * kr, (int64_t)(seq - l) * b, 2 * h, c->compute))
-            return rc;
     if (ev) KVPR_HIP(hipEventRecord(ev->a0, c->compute));
-    if (int rc = kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, seq + 1, b, h, c->d.n_heads, c->compute))
+    if (int rc = c->qkv ? kvpr::launch_attention_mixed(c->q32, dkv, kv_stage, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 1, c->compute)
+                        : kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, seq + 1, b, h, c->d.n_heads, c->compute))
         return rc;
     KVPR_HIP(hipEventRecord(c->ev_free[buf], c->compute));
     c->free_recorded[buf] = true;
@@ -968,6 +971,17 @@ extern "C" int kvpr_decode_attention(const void* q, const void* kv, void* z, voi
         return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
     if (!q || !kv || !z || !ws) return fail(KVPR_E_INVAL, "q / kv / z / ws is null");
     return kvpr::launch_attention(q, kv, z, ws, S, batch, hidden, n_heads, (hipStream_t)stream);
+}
+
+extern "C" int kvpr_decode_attention_mixed(const void* q, const void* kv16, const void* kvq, void* z, void* ws, int S, int split,
+                                           int batch, int hidden, int n_heads, void* stream) {
+    if (S < 1 || batch < 1 || n_heads < 1 || split < 0 || split > S - 1)
+        return fail(KVPR_E_RANGE, "S=%d split=%d batch=%d n_heads=%d out of range", S, split, batch, n_heads);
+    if (hidden % n_heads || (hidden / n_heads != 64 && hidden / n_heads != 128) || hidden % 128)
+        return fail(KVPR_E_INVAL, "head_dim must be 64 or 128 and hidden a multiple of 128");
+    if (!q || !kv16 || !z || !ws || (split < S - 1 && !kvq)) return fail(KVPR_E_INVAL, "q / kv16 / kvq / z / ws is null");
+    if (int rc = kvpr::launch_attention_mixed(q, kv16, kvq, z, ws, S, split, batch, hidden, n_heads, 0, (hipStream_t)stream)) return rc;
+    return kvpr::launch_attention_mixed(q, kv16, kvq, z, ws, S, split, batch, hidden, n_heads, 1, (hipStream_t)stream);
 }
 
 extern "C" int kvpr_token_gemm(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,

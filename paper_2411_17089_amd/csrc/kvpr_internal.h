@@ -23,6 +23,8 @@ int launch_gemm(const void* a, const void* w, const void* bias, void* c, int64_t
 int launch_attention(const void* q, const void* kv, void* z, void* ws, int S, int batch, int hidden,
                      int n_heads, hipStream_t st);
 size_t attention_workspace_bytes(int batch, int hidden, int n_heads, int S);
+int launch_attention_mixed(const void* q, const void* kv16, const void* kvq, void* z, void* ws, int S, int split, int batch,
+                           int hidden, int n_heads, int phase, hipStream_t st);
 int launch_token_gemm(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N,
                       int K, int out_f32_cols, int64_t ld16, void* ws, hipStream_t st);
 size_t token_gemm_workspace_bytes(int M, int N, int K);
