@@ -137,3 +137,37 @@ def test_full_size_4bit_store_sampled_sequences(k):
                 assert rel_err(got[n:n + 1], ko.layer_decode(sub, split, kv_hat)["o"]) <= 1e-2, (split, n)
     finally:
         k.kvpr_destroy(ctx)
+
+
+def test_full_size_stack_two_layers_sampled_sequences(k):
+    """Two OPT-13B-shaped decoder layers at the bench's stack shape (batch 32, context 1024, FFN 20480): the
+    sequences of a batch are independent, so the oracle runs the whole two-layer stack for two of them."""
+    (h, H, d), b, s, n_layers = kvpr_inputs.SHAPES["opt-13b"], 32, 1024, 2
+    ffn = 4 * h
+    layers, ws, keep = [], [], []
+    ctx = k.kvpr_create(n_layers, h, H, d, ffn, b, s + 2)
+    try:
+        for i in range(n_layers):
+            L = kvpr_inputs.make_layer(900 + i, b, s, h, H)
+            L.update(kvpr_inputs.make_ffn(900 + i, h, ffn))
+            layers.append(L)
+            dv = upload_layer(L)
+            keep.append(dv)
+            w = k.make_weights(**{f: dv[f] for f in ("wqkv", "bqkv", "wo", "bo", "ln1_g", "ln1_b", "w1", "b1", "w2", "b2", "ln2_g", "ln2_b")})
+            ws.append(w)
+            k.kvpr_store_write(ctx, i, 0, s, L["X"], None)
+            k.kvpr_store_prefill_kv(ctx, i, s, w)
+        x_in = kvpr_inputs._draw(np.random.default_rng(899), (b, h), 1.0)
+        out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+        splits = [768, 1024]
+        print("full-size two-layer stack", flush=True)
+        k.kvpr_decode_step(ctx, s, ws, torch.from_numpy(x_in).cuda(), out, splits)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.isfinite(got).all()
+        for n in (5, 30):
+            sub = [dict(L, X=np.ascontiguousarray(L["X"][:, n:n + 1])) for L in layers]
+            ref, _ = ko.decoder_stack_decode(sub, x_in[n:n + 1], splits)
+            assert rel_err(got[n:n + 1], ref) <= 5e-3, n
+    finally:
+        k.kvpr_destroy(ctx)

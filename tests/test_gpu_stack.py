@@ -159,3 +159,23 @@ def test_greedy_next_matches_oracle(k):
     k.kvpr_greedy_next(flat, wz, None, 2, 128, 300, lg, tk, None)
     torch.cuda.synchronize()
     assert tk.cpu().tolist() == [0, 0]
+
+
+def test_full_depth_reduced_width(k):
+    """The bench's stack depth (40 layers) at reduced width: errors must not build up through the residual stream."""
+    n_layers, b, s, h, H, ffn = 40, 4, 256, 512, 4, 2048
+    st = Stack(k, n_layers, b, s, h, H, ffn, seed0=700)
+    try:
+        rng = np.random.default_rng(3)
+        splits = [int(v) for v in rng.integers(0, s + 1, n_layers)]
+        splits[0], splits[1], splits[2] = 0, s, 192
+        print("full depth, reduced width: 40 layers", flush=True)
+        got_splits, _ = k.kvpr_decode_step(st.ctx, s, st.w, dev(st.x_in), st.x_out, splits)
+        torch.cuda.synchronize()
+        assert got_splits == splits
+        ref, _ = ko.decoder_stack_decode(st.layers, st.x_in, splits, st.stored)
+        got = st.x_out.cpu().numpy()
+        assert np.isfinite(got).all()
+        assert rel_err(got, ref) <= 1e-2
+    finally:
+        st.close()
