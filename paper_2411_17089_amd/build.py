@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvpr.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-HIP_SOURCES = ["context.hip", "gemm_recompute.hip", "gemm_token.hip", "attention_decode.hip", "elementwise.hip", "store_int4.hip"]
+HIP_SOURCES = ["context.hip", "store.hip", "profiler.hip", "kernels_abi.hip", "gemm_recompute.hip", "gemm_token.hip", "attention_decode.hip", "elementwise.hip", "store_int4.hip"]
 HOST_SOURCES = ["planner.cpp"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-result"]

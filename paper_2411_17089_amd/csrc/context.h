@@ -1,0 +1,89 @@
+// Runtime state shared by the translation units of libkvpr (not part of the ABI): the context, its
+// per-layer timing events, and the few helpers more than one file needs.
+#pragma once
+#include "kvpr_internal.h"
+
+#include <vector>
+
+namespace kvpr {
+
+typedef _Float16 half;
+
+// events bracketing each category of one layer (timing enabled)
+struct LayerEvents {
+    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, d0, a0, a1, o1, s0, s1, end;
+    int seq = -1, split = -1;            // what the slot last recorded
+    hipEvent_t* all() { return &start; }
+    static constexpr int count = 15;
+};
+
+}  // namespace kvpr
+
+using kvpr::half;
+using kvpr::LayerEvents;
+
+struct kvpr_ctx {
+    kvpr_model_desc d{};
+    hipStream_t compute = nullptr, copy = nullptr, store = nullptr;
+    std::vector<char*> hx, hkv;          // pinned, per layer: float16 rows, or packed 4-bit rows (Sec. 4.4)
+    bool qx = false, qkv = false;        // which of the two arrays the store keeps 4-bit compressed
+    char* dxq[2] = {nullptr, nullptr};   // device staging for packed rows (only when compressed)
+    char* dkvq[2] = {nullptr, nullptr};
+    std::vector<int> x_rows, kv_rows;    // contiguous prefix of rows known to hold data
+    std::vector<hipEvent_t> ev_slot_store;   // per slot: "the last store-back into this slot's host rows is done"
+    std::vector<bool> slot_store_recorded;
+    int nbuf = 0;
+    half* dx[2] = {nullptr, nullptr};
+    half* dkv[2] = {nullptr, nullptr};
+    float* q32 = nullptr;
+    half* z16 = nullptr;
+    // rotary models (KVPR_ARCH_LLAMA): q|k of the decode token before rotation, and the (cos, sin) table
+    bool llama = false;
+    float* qk32 = nullptr;
+    float2* rope_tab = nullptr;          // [max_seq][head_dim / 2]
+    void* attn_ws = nullptr;
+    // hidden-state scratch of the full decoder layer
+    half *hid = nullptr, *xn = nullptr, *attn_out = nullptr, *ffn1 = nullptr, *ffn2 = nullptr;
+    // fences (timing disabled)
+    hipEvent_t ev_x[2]{}, ev_kv[2]{}, ev_free[2]{}, ev_proj = nullptr, ev_store = nullptr, ev_begin = nullptr;
+    static constexpr int kMaxChunks = 32;
+    hipEvent_t ev_chunk[2][kMaxChunks]{};   // per device buffer: "activation chunk j has landed"
+    int chunks = 1;                          // 1 = the paper's schedule: all of X[0:l], then one GEMM
+    // column-by-column schedule with offloaded weights (n_gpu_batches > 0)
+    int nb = 0;                              // GPU batches per layer; the store then has n_layers * nb slots
+    hipStream_t wstream = nullptr;           // weight loads
+    std::vector<half*> hw;                   // pinned weight blob per layer
+    half* dw[2] = {nullptr, nullptr};        // device weight blobs (ping-pong across layers)
+    half* hid_all = nullptr;                 // [nb, batch, hidden] hidden states of all GPU batches
+    hipEvent_t ev_wkv[2]{}, ev_wall[2]{}, ev_wfree[2]{};
+    bool wfree_recorded[2] = {false, false};
+    std::vector<bool> w_written;
+    int slots() const { return nb > 0 ? d.n_layers * nb : d.n_layers; }
+    bool free_recorded[2] = {false, false};
+    std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
+    kvpr_profile_t prof{};
+    bool have_prof = false;
+    // run-time adaptation of prof (alpha > 0): a small ring of event sets recorded on untimed layers
+    double adapt_alpha = 0.0;
+    static constexpr int kProbes = 8;
+    LayerEvents probe[kProbes]{};
+    bool probe_made = false, probe_pending[kProbes] = {};
+    int probe_next = 0;
+    int cost_model = KVPR_COST_EQ10, granularity = 1;
+    int debug = 0;
+
+    size_t x_row_halfs() const { return (size_t)d.batch * d.hidden; }
+    size_t kv_row_halfs() const { return (size_t)d.batch * 2 * d.hidden; }
+    // bytes of one position (all sequences of the batch) as the host store holds it and as it crosses the link
+    size_t x_store_bytes() const { return qx ? d.batch * kvpr::int4_row_bytes(d.hidden) : x_row_halfs() * sizeof(half); }
+    size_t kv_store_bytes() const { return qkv ? d.batch * kvpr::int4_row_bytes(2 * d.hidden) : kv_row_halfs() * sizeof(half); }
+    int64_t flops_per_pos() const { return 4 * (int64_t)d.batch * d.hidden * d.hidden; }   // Eq. 8
+    int plan_chunks() const { return (chunks > 1 && cost_model == KVPR_COST_EQ10) ? chunks : 1; }
+};
+
+namespace kvpr {
+
+// wqkv / wo always; FFN and norm parameters when a full decoder layer is about to run
+int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn);
+
+}  // namespace kvpr

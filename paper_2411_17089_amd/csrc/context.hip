@@ -1,6 +1,6 @@
-// Runtime module (Sec. 3.3): pinned host store, copy / store streams, event-fenced overlap of
-// transfer and recomputation, profiler, per-layer decode and the layer-pipelined decode step.
-#include "kvpr_internal.h"
+// Runtime module (Sec. 3.3): context life cycle, copy / store streams, event-fenced overlap of transfer and
+// recomputation, per-layer decode, the layer-pipelined decode step and the column-by-column schedule.
+#include "context.h"
 
 #include <algorithm>
 #include <cmath>
@@ -26,78 +26,21 @@ int fail(int code, const char* fmt, ...) {
 
 using kvpr::fail;
 
-namespace {
+namespace kvpr {
 
-typedef _Float16 half;
+int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn) {
+    if (!w) return fail(KVPR_E_INVAL, "weights are null");
+    if (!w->wqkv || !w->wo) return fail(KVPR_E_INVAL, "wqkv / wo must not be null");
+    if (need_ffn && (!w->w1 || !w->w2 || !w->ln1_g || !w->ln2_g))
+        return fail(KVPR_E_INVAL, "FFN / norm weights must not be null for a full decoder layer");
+    if (need_ffn && !c->llama && (!w->ln1_b || !w->ln2_b))
+        return fail(KVPR_E_INVAL, "LayerNorm offsets must not be null for a full decoder layer");
+    return KVPR_OK;
+}
 
-// events bracketing each category of one layer (timing enabled)
-struct LayerEvents {
-    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, d0, a0, a1, o1, s0, s1, end;
-    int seq = -1, split = -1;            // what the slot last recorded
-    hipEvent_t* all() { return &start; }
-    static constexpr int count = 15;
-};
+}  // namespace kvpr
 
-}  // namespace
-
-struct kvpr_ctx {
-    kvpr_model_desc d{};
-    hipStream_t compute = nullptr, copy = nullptr, store = nullptr;
-    std::vector<char*> hx, hkv;          // pinned, per layer: float16 rows, or packed 4-bit rows (Sec. 4.4)
-    bool qx = false, qkv = false;        // which of the two arrays the store keeps 4-bit compressed
-    char* dxq[2] = {nullptr, nullptr};   // device staging for packed rows (only when compressed)
-    char* dkvq[2] = {nullptr, nullptr};
-    std::vector<int> x_rows, kv_rows;    // contiguous prefix of rows known to hold data
-    std::vector<hipEvent_t> ev_slot_store;   // per slot: "the last store-back into this slot's host rows is done"
-    std::vector<bool> slot_store_recorded;
-    int nbuf = 0;
-    half* dx[2] = {nullptr, nullptr};
-    half* dkv[2] = {nullptr, nullptr};
-    float* q32 = nullptr;
-    half* z16 = nullptr;
-    // rotary models (KVPR_ARCH_LLAMA): q|k of the decode token before rotation, and the (cos, sin) table
-    bool llama = false;
-    float* qk32 = nullptr;
-    float2* rope_tab = nullptr;          // [max_seq][head_dim / 2]
-    void* attn_ws = nullptr;
-    // hidden-state scratch of the full decoder layer
-    half *hid = nullptr, *xn = nullptr, *attn_out = nullptr, *ffn1 = nullptr, *ffn2 = nullptr;
-    // fences (timing disabled)
-    hipEvent_t ev_x[2]{}, ev_kv[2]{}, ev_free[2]{}, ev_proj = nullptr, ev_store = nullptr, ev_begin = nullptr;
-    static constexpr int kMaxChunks = 32;
-    hipEvent_t ev_chunk[2][kMaxChunks]{};   // per device buffer: "activation chunk j has landed"
-    int chunks = 1;                          // 1 = the paper's schedule: all of X[0:l], then one GEMM
-    // column-by-column schedule with offloaded weights (n_gpu_batches > 0)
-    int nb = 0;                              // GPU batches per layer; the store then has n_layers * nb slots
-    hipStream_t wstream = nullptr;           // weight loads
-    std::vector<half*> hw;                   // pinned weight blob per layer
-    half* dw[2] = {nullptr, nullptr};        // device weight blobs (ping-pong across layers)
-    half* hid_all = nullptr;                 // [nb, batch, hidden] hidden states of all GPU batches
-    hipEvent_t ev_wkv[2]{}, ev_wall[2]{}, ev_wfree[2]{};
-    bool wfree_recorded[2] = {false, false};
-    std::vector<bool> w_written;
-    int slots() const { return nb > 0 ? d.n_layers * nb : d.n_layers; }
-    bool free_recorded[2] = {false, false};
-    std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
-    kvpr_profile_t prof{};
-    bool have_prof = false;
-    // run-time adaptation of prof (alpha > 0): a small ring of event sets recorded on untimed layers
-    double adapt_alpha = 0.0;
-    static constexpr int kProbes = 8;
-    LayerEvents probe[kProbes]{};
-    bool probe_made = false, probe_pending[kProbes] = {};
-    int probe_next = 0;
-    int cost_model = KVPR_COST_EQ10, granularity = 1;
-    int debug = 0;
-
-    size_t x_row_halfs() const { return (size_t)d.batch * d.hidden; }
-    size_t kv_row_halfs() const { return (size_t)d.batch * 2 * d.hidden; }
-    // bytes of one position (all sequences of the batch) as the host store holds it and as it crosses the link
-    size_t x_store_bytes() const { return qx ? d.batch * kvpr::int4_row_bytes(d.hidden) : x_row_halfs() * sizeof(half); }
-    size_t kv_store_bytes() const { return qkv ? d.batch * kvpr::int4_row_bytes(2 * d.hidden) : kv_row_halfs() * sizeof(half); }
-    int64_t flops_per_pos() const { return 4 * (int64_t)d.batch * d.hidden * d.hidden; }   // Eq. 8
-    int plan_chunks() const { return (chunks > 1 && cost_model == KVPR_COST_EQ10) ? chunks : 1; }
-};
+using kvpr::check_weights;
 
 namespace {
 
@@ -119,15 +62,6 @@ int ensure_timing_events(kvpr_ctx* c, int slots) {
     return KVPR_OK;
 }
 
-int check_weights(const kvpr_ctx* c, const kvpr_layer_weights* w, bool need_ffn) {
-    if (!w) return fail(KVPR_E_INVAL, "weights are null");
-    if (!w->wqkv || !w->wo) return fail(KVPR_E_INVAL, "wqkv / wo must not be null");
-    if (need_ffn && (!w->w1 || !w->w2 || !w->ln1_g || !w->ln2_g))
-        return fail(KVPR_E_INVAL, "FFN / norm weights must not be null for a full decoder layer");
-    if (need_ffn && !c->llama && (!w->ln1_b || !w->ln2_b))
-        return fail(KVPR_E_INVAL, "LayerNorm offsets must not be null for a full decoder layer");
-    return KVPR_OK;
-}
 
 int adapt_poll(kvpr_ctx* c);
 
@@ -647,84 +581,6 @@ extern "C" int kvpr_get_profile(kvpr_ctx* c, kvpr_profile_t* out) {
     return KVPR_OK;
 }
 
-extern "C" int kvpr_store_write(kvpr_ctx* c, int layer, int t0, int t1, const void* x_host, const void* kv_host) {
-    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
-    if (layer < 0 || layer >= c->slots()) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->slots());
-    if (t0 < 0 || t1 < t0 || t1 > c->d.max_seq) return fail(KVPR_E_RANGE, "rows [%d, %d) outside [0, %d]", t0, t1, c->d.max_seq);
-    // the copy/store streams may still be touching the store
-    KVPR_HIP(hipStreamSynchronize(c->copy));
-    KVPR_HIP(hipStreamSynchronize(c->store));
-    const size_t xr = c->x_row_halfs(), kr = c->kv_row_halfs();
-    const size_t xsb = c->x_store_bytes(), ksb = c->kv_store_bytes();
-    const size_t n = (size_t)(t1 - t0);
-    // an array kept compressed is packed on the GPU (one codec implementation): float16 rows up, packed rows down
-    auto write_packed = [&](const void* src, half* dev, char* stage, char* dst, size_t row_halfs, size_t row_store_bytes,
-                            int cols) -> int {
-        KVPR_HIP(hipDeviceSynchronize());
-        KVPR_HIP(hipMemcpy(dev, src, n * row_halfs * sizeof(half), hipMemcpyHostToDevice));
-        if (int rc = kvpr::launch_quant_int4(dev, stage, (int64_t)n * c->d.batch, cols, c->compute)) return rc;
-        KVPR_HIP(hipMemcpyAsync(dst, stage, n * row_store_bytes, hipMemcpyDeviceToHost, c->compute));
-        KVPR_HIP(hipStreamSynchronize(c->compute));
-        return KVPR_OK;
-    };
-    if (x_host && n > 0) {
-        if (c->qx) {
-            if (int rc = write_packed(x_host, c->dx[0], c->dxq[0], c->hx[layer] + (size_t)t0 * xsb, xr, xsb, c->d.hidden)) return rc;
-        } else {
-            memcpy(c->hx[layer] + (size_t)t0 * xsb, x_host, n * xsb);
-        }
-    }
-    if (x_host && t0 <= c->x_rows[layer]) c->x_rows[layer] = std::max(c->x_rows[layer], t1);
-    if (kv_host && n > 0) {
-        if (c->qkv) {
-            if (int rc = write_packed(kv_host, c->dkv[0], c->dkvq[0], c->hkv[layer] + (size_t)t0 * ksb, kr, ksb, 2 * c->d.hidden)) return rc;
-        } else {
-            memcpy(c->hkv[layer] + (size_t)t0 * ksb, kv_host, n * ksb);
-        }
-    }
-    if (kv_host && t0 <= c->kv_rows[layer]) c->kv_rows[layer] = std::max(c->kv_rows[layer], t1);
-    return KVPR_OK;
-}
-
-extern "C" int kvpr_store_ptrs(kvpr_ctx* c, int layer, void** x_host, void** kv_host) {
-    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
-    if (layer < 0 || layer >= c->slots()) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->slots());
-    if (x_host) *x_host = c->hx[layer];
-    if (kv_host) *kv_host = c->hkv[layer];
-    // the caller may now write any row directly: treat all rows as holding data
-    c->x_rows[layer] = c->d.max_seq;
-    c->kv_rows[layer] = c->d.max_seq;
-    return KVPR_OK;
-}
-
-extern "C" int kvpr_store_prefill_kv(kvpr_ctx* c, int layer, int seq, const kvpr_layer_weights* w) {
-    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
-    if (layer < 0 || layer >= c->slots()) return fail(KVPR_E_RANGE, "layer %d outside [0, %d)", layer, c->slots());
-    if (seq < 0 || seq > c->d.max_seq) return fail(KVPR_E_RANGE, "seq %d outside [0, %d]", seq, c->d.max_seq);
-    if (int rc = check_weights(c, w, false)) return rc;
-    if (c->x_rows[layer] < seq) return fail(KVPR_E_STATE, "layer %d: only %d activation rows written", layer, c->x_rows[layer]);
-    if (seq == 0) return KVPR_OK;
-    const int h = c->d.hidden;
-    const size_t xsb = c->x_store_bytes(), ksb = c->kv_store_bytes();
-    KVPR_HIP(hipDeviceSynchronize());
-    // the activations as the store returns them (dequantised if it keeps them packed)
-    KVPR_HIP(hipMemcpyAsync(c->qx ? (void*)c->dxq[0] : (void*)c->dx[0], c->hx[layer], (size_t)seq * xsb, hipMemcpyHostToDevice, c->compute));
-    if (c->qx)
-        if (int rc = kvpr::launch_dequant_int4(c->dxq[0], c->dx[0], (int64_t)seq * c->d.batch, h, c->compute)) return rc;
-    const half* wkv = (const half*)w->wqkv + (size_t)h * h;
-    const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
-    if (int rc = c->llama ? kvpr::launch_gemm_rope(c->dx[0], wkv, bkv, c->dkv[0], (int64_t)seq * c->d.batch, 2 * h, h, 2 * (int64_t)h,
-                                                   c->rope_tab, h, c->d.head_dim, c->d.batch, 0, c->compute)
-                          : kvpr::launch_gemm(c->dx[0], wkv, bkv, c->dkv[0], (int64_t)seq * c->d.batch, 2 * h, h, 2 * (int64_t)h, c->compute))
-        return rc;
-    if (c->qkv)
-        if (int rc = kvpr::launch_quant_int4(c->dkv[0], c->dkvq[0], (int64_t)seq * c->d.batch, 2 * h, c->compute)) return rc;
-    KVPR_HIP(hipMemcpyAsync(c->hkv[layer], c->qkv ? (const void*)c->dkvq[0] : (const void*)c->dkv[0], (size_t)seq * ksb,
-                            hipMemcpyDeviceToHost, c->compute));
-    KVPR_HIP(hipStreamSynchronize(c->compute));
-    c->kv_rows[layer] = std::max(c->kv_rows[layer], seq);
-    return KVPR_OK;
-}
 
 extern "C" int kvpr_layer_decode(kvpr_ctx* c, int layer, int seq, int split, const kvpr_layer_weights* w,
                                  const void* x_new_dev, void* out_dev, kvpr_layer_timing* timing) {
@@ -946,223 +802,5 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
         for (int i = 0; i < S; ++i)
             if (int rc = read_timing(c, &c->tev[i], seq, ls[i], &per_slot[i])) return rc;
     }
-    return KVPR_OK;
-}
-
-// ---- individual kernels ----
-extern "C" int kvpr_recompute_gemm(const void* a, const void* w, const void* bias, void* cdev, int64_t M, int N, int K,
-                                   int64_t ldc, void* stream) {
-    if (M < 0 || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%lld N=%d K=%d out of range", (long long)M, N, K);
-    if (K % 64 || N % 8 || ldc < N || ldc % 4) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 4 == 0");
-    if (M == 0) return KVPR_OK;
-    if (!a || !w || !cdev) return fail(KVPR_E_INVAL, "a / w / c is null");
-    return kvpr::launch_gemm(a, w, bias, cdev, M, N, K, ldc, (hipStream_t)stream);
-}
-
-extern "C" size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S) {
-    if (batch < 1 || hidden < 1 || S < 1) return 0;
-    return kvpr::attention_workspace_bytes(batch, hidden, n_heads, S);
-}
-
-extern "C" int kvpr_decode_attention(const void* q, const void* kv, void* z, void* ws, int S, int batch, int hidden,
-                                     int n_heads, void* stream) {
-    if (S < 1 || batch < 1 || n_heads < 1) return fail(KVPR_E_RANGE, "S=%d batch=%d n_heads=%d out of range", S, batch, n_heads);
-    if (hidden % n_heads || (hidden / n_heads != 64 && hidden / n_heads != 128))
-        return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
-    if (!q || !kv || !z || !ws) return fail(KVPR_E_INVAL, "q / kv / z / ws is null");
-    return kvpr::launch_attention(q, kv, z, ws, S, batch, hidden, n_heads, (hipStream_t)stream);
-}
-
-extern "C" int kvpr_decode_attention_mixed(const void* q, const void* kv16, const void* kvq, void* z, void* ws, int S, int split,
-                                           int batch, int hidden, int n_heads, void* stream) {
-    if (S < 1 || batch < 1 || n_heads < 1 || split < 0 || split > S - 1)
-        return fail(KVPR_E_RANGE, "S=%d split=%d batch=%d n_heads=%d out of range", S, split, batch, n_heads);
-    if (hidden % n_heads || (hidden / n_heads != 64 && hidden / n_heads != 128) || hidden % 128)
-        return fail(KVPR_E_INVAL, "head_dim must be 64 or 128 and hidden a multiple of 128");
-    if (!q || !kv16 || !z || !ws || (split < S - 1 && !kvq)) return fail(KVPR_E_INVAL, "q / kv16 / kvq / z / ws is null");
-    if (int rc = kvpr::launch_attention_mixed(q, kv16, kvq, z, ws, S, split, batch, hidden, n_heads, 0, (hipStream_t)stream)) return rc;
-    return kvpr::launch_attention_mixed(q, kv16, kvq, z, ws, S, split, batch, hidden, n_heads, 1, (hipStream_t)stream);
-}
-
-extern "C" int kvpr_token_gemm(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
-                               int out_f32_cols, int64_t ld16, void* stream) {
-    if (M < 1 || M > 64 || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%d (1..64) N=%d K=%d out of range", M, N, K);
-    if (K % 128) return fail(KVPR_E_INVAL, "K must be a multiple of 128");
-    if (out_f32_cols < 0 || out_f32_cols > N) return fail(KVPR_E_RANGE, "out_f32_cols outside [0, N]");
-    if (!x || !w || (out_f32_cols > 0 && !y32) || (out_f32_cols < N && !y16)) return fail(KVPR_E_INVAL, "null pointer");
-    if (out_f32_cols < N && ld16 < N - out_f32_cols) return fail(KVPR_E_INVAL, "ld16 too small");
-    return kvpr::launch_token_gemm_flags(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, 0, (hipStream_t)stream);
-}
-
-// ---- rotary models ----
-extern "C" int kvpr_rope_table(float* out_host, int n_pos, int head_dim, double base) {
-    if (!out_host) return fail(KVPR_E_INVAL, "out_host is null");
-    if (n_pos < 1 || (head_dim != 64 && head_dim != 128)) return fail(KVPR_E_RANGE, "n_pos=%d head_dim=%d: need n_pos >= 1, head_dim 64 or 128", n_pos, head_dim);
-    if (!(base > 0.0) || !std::isfinite(base)) return fail(KVPR_E_INVAL, "base must be finite and > 0");
-    const int half_d = head_dim / 2;
-    for (int i = 0; i < half_d; ++i) {
-        const double theta = std::pow(base, -2.0 * i / head_dim);
-        for (int p = 0; p < n_pos; ++p) {
-            out_host[((size_t)p * half_d + i) * 2] = (float)std::cos(p * theta);
-            out_host[((size_t)p * half_d + i) * 2 + 1] = (float)std::sin(p * theta);
-        }
-    }
-    return KVPR_OK;
-}
-
-extern "C" int kvpr_recompute_gemm_rope(const void* a, const void* w, const void* bias, void* cdev, int64_t M, int N, int K,
-                                        int64_t ldc, const void* table_dev, int n_pos, int rope_cols, int head_dim, int batch,
-                                        int pos0, void* stream) {
-    if (M < 0 || M >= ((int64_t)1 << 31) || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%lld N=%d K=%d out of range", (long long)M, N, K);
-    if (K % 64 || N % 8 || ldc < N || ldc % 4) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 4 == 0");
-    if (head_dim != 64 && head_dim != 128) return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
-    if (rope_cols < 0 || rope_cols > N || rope_cols % 128) return fail(KVPR_E_INVAL, "rope_cols must be a multiple of 128 in [0, N]");
-    if (batch < 1 || pos0 < 0 || n_pos < 1) return fail(KVPR_E_RANGE, "batch=%d pos0=%d n_pos=%d out of range", batch, pos0, n_pos);
-    if (M == 0) return KVPR_OK;
-    if (pos0 + (M - 1) / batch >= n_pos) return fail(KVPR_E_RANGE, "rows reach position %lld, the table has %d", (long long)(pos0 + (M - 1) / batch), n_pos);
-    if (!a || !w || !cdev || !table_dev) return fail(KVPR_E_INVAL, "a / w / c / table is null");
-    return kvpr::launch_gemm_rope(a, w, bias, cdev, M, N, K, ldc, table_dev, rope_cols, head_dim, batch, pos0, (hipStream_t)stream);
-}
-
-extern "C" int kvpr_rope_token(const void* qk32, const void* table_dev, int n_pos, int pos, int batch, int hidden, int head_dim,
-                               void* q32, void* k16, int64_t ldk, void* stream) {
-    if (batch < 1 || hidden < 1 || pos < 0 || pos >= n_pos) return fail(KVPR_E_RANGE, "batch=%d hidden=%d pos=%d n_pos=%d out of range", batch, hidden, pos, n_pos);
-    if ((head_dim != 64 && head_dim != 128) || hidden % head_dim) return fail(KVPR_E_INVAL, "head_dim must be 64 or 128 and divide hidden");
-    if (ldk < hidden) return fail(KVPR_E_INVAL, "ldk too small");
-    if (!qk32 || !table_dev || !q32 || !k16) return fail(KVPR_E_INVAL, "null pointer");
-    return kvpr::launch_rope_token(qk32, table_dev, pos, batch, hidden, head_dim, q32, k16, ldk, (hipStream_t)stream);
-}
-
-extern "C" size_t kvpr_int4_row_bytes(int cols) {
-    if (cols < 64 || cols % 64) return 0;
-    return kvpr::int4_row_bytes(cols);
-}
-
-static int check_codec_args(const void* src, const void* dst, int64_t rows, int cols) {
-    if (rows < 0 || cols < 64 || cols % 64) return fail(KVPR_E_RANGE, "rows=%lld cols=%d: need rows >= 0 and cols a positive multiple of 64", (long long)rows, cols);
-    if (rows * (int64_t)(cols / 8) > ((int64_t)1 << 38)) return fail(KVPR_E_RANGE, "rows * cols too large");
-    if (rows > 0 && (!src || !dst)) return fail(KVPR_E_INVAL, "src / dst is null");
-    return KVPR_OK;
-}
-
-extern "C" int kvpr_quant_int4(const void* src, void* dst, int64_t rows, int cols, void* stream) {
-    if (int rc = check_codec_args(src, dst, rows, cols)) return rc;
-    return kvpr::launch_quant_int4(src, dst, rows, cols, (hipStream_t)stream);
-}
-
-extern "C" int kvpr_dequant_int4(const void* src, void* dst, int64_t rows, int cols, void* stream) {
-    if (int rc = check_codec_args(src, dst, rows, cols)) return rc;
-    return kvpr::launch_dequant_int4(src, dst, rows, cols, (hipStream_t)stream);
-}
-
-// ---- profiler (Sec. 3.1) ----
-namespace {
-
-template <class F>
-int time_median(hipStream_t st, int reps, F fn, double* seconds) {
-    hipEvent_t e0, e1;
-    KVPR_HIP(hipEventCreate(&e0));
-    KVPR_HIP(hipEventCreate(&e1));
-    int rc = fn();                                   // warm-up
-    if (rc == KVPR_OK && hipStreamSynchronize(st) != hipSuccess) rc = fail(KVPR_E_HIP, "profiler warm-up failed");
-    std::vector<float> ms(reps);
-    for (int r = 0; r < reps && rc == KVPR_OK; ++r) {
-        if (hipEventRecord(e0, st) != hipSuccess) { rc = fail(KVPR_E_HIP, "event record failed"); break; }
-        rc = fn();
-        if (rc != KVPR_OK) break;
-        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-            hipEventElapsedTime(&ms[r], e0, e1) != hipSuccess)
-            rc = fail(KVPR_E_HIP, "profiler timing failed");
-    }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (rc != KVPR_OK) return rc;
-    std::sort(ms.begin(), ms.end());
-    *seconds = (double)ms[reps / 2] * 1e-3;
-    return KVPR_OK;
-}
-
-}  // namespace
-
-extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out) {
-    if (!c || !out) return fail(KVPR_E_INVAL, "ctx / out is null");
-    if (batch < 1 || seq < 1) return fail(KVPR_E_RANGE, "batch and seq must be >= 1");
-    const int64_t rows = (int64_t)batch * seq;
-    if (rows > (int64_t)c->d.batch * (c->d.max_seq - 1))
-        return fail(KVPR_E_RANGE, "batch*seq = %lld exceeds the context's batch*(max_seq-1)", (long long)rows);
-    const int h = c->d.hidden;
-    // the link is measured on what a full cache copy of [seq, batch] moves: packed rows if the store keeps them packed
-    const size_t kv_bytes = c->qkv ? (size_t)rows * kvpr::int4_row_bytes(2 * h) : (size_t)rows * 2 * h * sizeof(half);
-    const size_t cap_bytes = (size_t)c->d.max_seq * c->kv_store_bytes();
-    KVPR_HIP(hipDeviceSynchronize());
-    kvpr_profile_t p{};
-    double t = 0;
-    char* hkv = c->hkv[0];
-    half* dkv = c->dkv[0];
-    char* kv_stage = c->qkv ? c->dkvq[0] : (char*)dkv;
-
-    // v_com: one pinned copy of the size of the whole cache of [seq, batch]
-    if (int rc = time_median(c->copy, 5, [&]() -> int {
-            KVPR_HIP(hipMemcpyAsync(kv_stage, hkv, kv_bytes, hipMemcpyHostToDevice, c->copy));
-            return KVPR_OK; }, &t)) return rc;
-    p.h2d_bytes_per_s = (double)kv_bytes / t;
-    // d2h: the same bytes back to where they came from (the store keeps its contents)
-    if (int rc = time_median(c->store, 3, [&]() -> int {
-            KVPR_HIP(hipMemcpyAsync(hkv, kv_stage, kv_bytes, hipMemcpyDeviceToHost, c->store));
-            return KVPR_OK; }, &t)) return rc;
-    p.d2h_bytes_per_s = (double)kv_bytes / t;
-    // best H2D rate over a size sweep
-    p.h2d_peak_bytes_per_s = p.h2d_bytes_per_s;
-    for (size_t sz = (size_t)64 << 10; sz <= std::min(cap_bytes, (size_t)1 << 30); sz *= 4) {
-        if (int rc = time_median(c->copy, 5, [&]() -> int {
-                KVPR_HIP(hipMemcpyAsync(kv_stage, hkv, sz, hipMemcpyHostToDevice, c->copy));
-                return KVPR_OK; }, &t)) return rc;
-        p.h2d_peak_bytes_per_s = std::max(p.h2d_peak_bytes_per_s, (double)sz / t);
-    }
-    KVPR_HIP(hipDeviceSynchronize());
-
-    // v_gpu: the recompute GEMM at M = batch*seq on random operands
-    half* wtmp = nullptr;
-    // big enough for the widest matrix of the layer: [Wq;Wk;Wv], or one FFN matrix ([gate;up] for the gated FFN)
-    const size_t ffn_rows = (size_t)c->d.ffn_dim * (c->llama ? 2 : 1);
-    const size_t wtmp_halfs = std::max((size_t)3 * h, ffn_rows) * h;
-    if (hipMalloc((void**)&wtmp, wtmp_halfs * sizeof(half)) != hipSuccess)
-        return fail(KVPR_E_NOMEM, "profiler weight buffer");
-    int rc = kvpr::launch_fill_random(wtmp, wtmp_halfs, 0.035f, 1u, c->compute);
-    if (!rc) rc = kvpr::launch_fill_random(c->dx[0], (size_t)rows * h, 1.7f, 2u, c->compute);
-    if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
-            // rotary models: positions as if the context's batch held these rows (the rotation costs the same anywhere)
-            return c->llama ? kvpr::launch_gemm_rope(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->rope_tab, h,
-                                                     c->d.head_dim, c->d.batch, 0, c->compute)
-                            : kvpr::launch_gemm(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->compute); }, &t);
-    if (!rc) p.gemm_flops_per_s = 4.0 * (double)rows * h * h / t;
-    // attention read rate over the cache just produced (context batch, S = rows / batch positions)
-    const int S = (int)(rows / c->d.batch);
-    if (!rc && S >= 1) {
-        rc = kvpr::launch_fill_random(c->z16, (size_t)c->d.batch * h, 1.0f, 3u, c->compute);   // any finite q source
-        if (!rc) rc = hipMemsetAsync(c->q32, 0, (size_t)c->d.batch * h * sizeof(float), c->compute) == hipSuccess
-                          ? KVPR_OK : fail(KVPR_E_HIP, "memset failed");
-        if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
-                return kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, c->d.batch, h, c->d.n_heads, c->compute); }, &t);
-        if (!rc) p.attn_bytes_per_s = (double)S * c->d.batch * 2 * h * sizeof(half) / t;
-        // the rest of a layer's GPU work besides the recomputation: projections, attention, FFN (random weights)
-        if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
-                const int b = c->d.batch, f = c->d.ffn_dim;
-                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, c->q32, dkv, b, 3 * h, h, h, 2 * (int64_t)h, 0, c->compute)) return r;
-                if (int r = kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, b, h, c->d.n_heads, c->compute)) return r;
-                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, dkv, b, h, h, 0, h, 0, c->compute)) return r;
-                if (f > 0) {
-                    const int f1 = (int)ffn_rows;
-                    half* prod = c->ffn1 + (c->llama ? (size_t)b * 2 * f : 0);
-                    if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, c->ffn1, b, f1, h, 0, f1, 1, c->compute)) return r;
-                    if (int r = kvpr::launch_token_gemm_flags(prod, wtmp, nullptr, nullptr, dkv, b, h, f, 0, h, 0, c->compute)) return r;
-                }
-                return KVPR_OK; }, &t);
-        if (!rc) p.layer_other_s = t;
-    }
-    (void)hipDeviceSynchronize();
-    (void)hipFree(wtmp);
-    if (rc) return rc;
-    *out = p;
     return KVPR_OK;
 }

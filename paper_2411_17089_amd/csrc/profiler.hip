@@ -1,0 +1,123 @@
+// Profiler module (Sec. 3.1): measures, on this machine and for this context's shape, the constants the
+// scheduler needs (pinned H2D rate, recompute GEMM rate) and a few rates that are only reported.
+#include "context.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+using kvpr::fail;
+using kvpr::check_weights;
+
+// ---- profiler (Sec. 3.1) ----
+namespace {
+
+template <class F>
+int time_median(hipStream_t st, int reps, F fn, double* seconds) {
+    hipEvent_t e0, e1;
+    KVPR_HIP(hipEventCreate(&e0));
+    KVPR_HIP(hipEventCreate(&e1));
+    int rc = fn();                                   // warm-up
+    if (rc == KVPR_OK && hipStreamSynchronize(st) != hipSuccess) rc = fail(KVPR_E_HIP, "profiler warm-up failed");
+    std::vector<float> ms(reps);
+    for (int r = 0; r < reps && rc == KVPR_OK; ++r) {
+        if (hipEventRecord(e0, st) != hipSuccess) { rc = fail(KVPR_E_HIP, "event record failed"); break; }
+        rc = fn();
+        if (rc != KVPR_OK) break;
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms[r], e0, e1) != hipSuccess)
+            rc = fail(KVPR_E_HIP, "profiler timing failed");
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != KVPR_OK) return rc;
+    std::sort(ms.begin(), ms.end());
+    *seconds = (double)ms[reps / 2] * 1e-3;
+    return KVPR_OK;
+}
+
+}  // namespace
+
+extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out) {
+    if (!c || !out) return fail(KVPR_E_INVAL, "ctx / out is null");
+    if (batch < 1 || seq < 1) return fail(KVPR_E_RANGE, "batch and seq must be >= 1");
+    const int64_t rows = (int64_t)batch * seq;
+    if (rows > (int64_t)c->d.batch * (c->d.max_seq - 1))
+        return fail(KVPR_E_RANGE, "batch*seq = %lld exceeds the context's batch*(max_seq-1)", (long long)rows);
+    const int h = c->d.hidden;
+    // the link is measured on what a full cache copy of [seq, batch] moves: packed rows if the store keeps them packed
+    const size_t kv_bytes = c->qkv ? (size_t)rows * kvpr::int4_row_bytes(2 * h) : (size_t)rows * 2 * h * sizeof(half);
+    const size_t cap_bytes = (size_t)c->d.max_seq * c->kv_store_bytes();
+    KVPR_HIP(hipDeviceSynchronize());
+    kvpr_profile_t p{};
+    double t = 0;
+    char* hkv = c->hkv[0];
+    half* dkv = c->dkv[0];
+    char* kv_stage = c->qkv ? c->dkvq[0] : (char*)dkv;
+
+    // v_com: one pinned copy of the size of the whole cache of [seq, batch]
+    if (int rc = time_median(c->copy, 5, [&]() -> int {
+            KVPR_HIP(hipMemcpyAsync(kv_stage, hkv, kv_bytes, hipMemcpyHostToDevice, c->copy));
+            return KVPR_OK; }, &t)) return rc;
+    p.h2d_bytes_per_s = (double)kv_bytes / t;
+    // d2h: the same bytes back to where they came from (the store keeps its contents)
+    if (int rc = time_median(c->store, 3, [&]() -> int {
+            KVPR_HIP(hipMemcpyAsync(hkv, kv_stage, kv_bytes, hipMemcpyDeviceToHost, c->store));
+            return KVPR_OK; }, &t)) return rc;
+    p.d2h_bytes_per_s = (double)kv_bytes / t;
+    // best H2D rate over a size sweep
+    p.h2d_peak_bytes_per_s = p.h2d_bytes_per_s;
+    for (size_t sz = (size_t)64 << 10; sz <= std::min(cap_bytes, (size_t)1 << 30); sz *= 4) {
+        if (int rc = time_median(c->copy, 5, [&]() -> int {
+                KVPR_HIP(hipMemcpyAsync(kv_stage, hkv, sz, hipMemcpyHostToDevice, c->copy));
+                return KVPR_OK; }, &t)) return rc;
+        p.h2d_peak_bytes_per_s = std::max(p.h2d_peak_bytes_per_s, (double)sz / t);
+    }
+    KVPR_HIP(hipDeviceSynchronize());
+
+    // v_gpu: the recompute GEMM at M = batch*seq on random operands
+    half* wtmp = nullptr;
+    // big enough for the widest matrix of the layer: [Wq;Wk;Wv], or one FFN matrix ([gate;up] for the gated FFN)
+    const size_t ffn_rows = (size_t)c->d.ffn_dim * (c->llama ? 2 : 1);
+    const size_t wtmp_halfs = std::max((size_t)3 * h, ffn_rows) * h;
+    if (hipMalloc((void**)&wtmp, wtmp_halfs * sizeof(half)) != hipSuccess)
+        return fail(KVPR_E_NOMEM, "profiler weight buffer");
+    int rc = kvpr::launch_fill_random(wtmp, wtmp_halfs, 0.035f, 1u, c->compute);
+    if (!rc) rc = kvpr::launch_fill_random(c->dx[0], (size_t)rows * h, 1.7f, 2u, c->compute);
+    if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
+            // rotary models: positions as if the context's batch held these rows (the rotation costs the same anywhere)
+            return c->llama ? kvpr::launch_gemm_rope(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->rope_tab, h,
+                                                     c->d.head_dim, c->d.batch, 0, c->compute)
+                            : kvpr::launch_gemm(c->dx[0], wtmp, nullptr, dkv, rows, 2 * h, h, 2 * (int64_t)h, c->compute); }, &t);
+    if (!rc) p.gemm_flops_per_s = 4.0 * (double)rows * h * h / t;
+    // attention read rate over the cache just produced (context batch, S = rows / batch positions)
+    const int S = (int)(rows / c->d.batch);
+    if (!rc && S >= 1) {
+        rc = kvpr::launch_fill_random(c->z16, (size_t)c->d.batch * h, 1.0f, 3u, c->compute);   // any finite q source
+        if (!rc) rc = hipMemsetAsync(c->q32, 0, (size_t)c->d.batch * h * sizeof(float), c->compute) == hipSuccess
+                          ? KVPR_OK : fail(KVPR_E_HIP, "memset failed");
+        if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
+                return kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, c->d.batch, h, c->d.n_heads, c->compute); }, &t);
+        if (!rc) p.attn_bytes_per_s = (double)S * c->d.batch * 2 * h * sizeof(half) / t;
+        // the rest of a layer's GPU work besides the recomputation: projections, attention, FFN (random weights)
+        if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
+                const int b = c->d.batch, f = c->d.ffn_dim;
+                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, c->q32, dkv, b, 3 * h, h, h, 2 * (int64_t)h, 0, c->compute)) return r;
+                if (int r = kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, b, h, c->d.n_heads, c->compute)) return r;
+                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, dkv, b, h, h, 0, h, 0, c->compute)) return r;
+                if (f > 0) {
+                    const int f1 = (int)ffn_rows;
+                    half* prod = c->ffn1 + (c->llama ? (size_t)b * 2 * f : 0);
+                    if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, c->ffn1, b, f1, h, 0, f1, 1, c->compute)) return r;
+                    if (int r = kvpr::launch_token_gemm_flags(prod, wtmp, nullptr, nullptr, dkv, b, h, f, 0, h, 0, c->compute)) return r;
+                }
+                return KVPR_OK; }, &t);
+        if (!rc) p.layer_other_s = t;
+    }
+    (void)hipDeviceSynchronize();
+    (void)hipFree(wtmp);
+    if (rc) return rc;
+    *out = p;
+    return KVPR_OK;
+}
