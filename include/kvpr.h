@@ -150,11 +150,17 @@ const char* kvpr_last_error(void);
 
 /* Create a context for `desc`.  compute_stream is a hipStream_t (may be null = the
  * null stream) owned by the caller; all kernels are launched on it.  Allocates the
- * pinned host store: n_layers * max_seq * batch * 3*hidden * 2 bytes, and device
- * staging buffers for min(n_layers, 2) layers.  KVPR_E_NOMEM if that fails. */
+ * pinned host store: n_layers * max_seq * batch * 3*hidden * 2 bytes (9/32 of that for
+ * an array kept 4-bit compressed), and device staging buffers for min(n_layers, 2)
+ * layers (float16 X and KV, plus packed copies of the arrays kept compressed).
+ * KVPR_E_NOMEM if that fails.  kvpr_destroy waits for the context's streams and
+ * frees everything the context owns. */
 int kvpr_create(const kvpr_model_desc* desc, void* compute_stream, kvpr_ctx** out);
 int kvpr_destroy(kvpr_ctx* ctx);
+/* Debug modes (KVPR_DEBUG_*), results are unchanged by them. */
 int kvpr_set_debug(kvpr_ctx* ctx, int flags);
+/* Gives the context the constants of Eq. 10 (from kvpr_profile or the caller), the cost form and the
+ * granularity of l that split = -1 plans with.  Validates the profile like kvpr_plan_split. */
 int kvpr_set_profile(kvpr_ctx* ctx, const kvpr_profile_t* prof, int cost_model, int granularity);
 
 /* Host store (Sec. 3.3 "pinned memory").  Copies rows [t0, t1) of `layer` from
