@@ -371,13 +371,32 @@ def main():
     ms_act, ms_kv = mean("ms_act_copy"), mean("ms_kv_copy")
     gemm_flops = 4.0 * b * split * h * h
     attn_bytes = 2.0 * b * (s + 1) * h * 2
-    # with a packed cache the event pair brackets only the phase after the cache fence: packed rows [l, s) read once
-    attn_phase_bytes = float(kv_bpp * (s - split)) if qflags & k.KVPR_KV_INT4 else attn_bytes
-    attn_kernel = "attention_partial_ranged over the packed rows (+combine)" if qflags & k.KVPR_KV_INT4 else "attention_partial (+combine)"
+    # ms_attn sums the two attention phases; with a packed cache the transferred rows are read in packed form
+    attn_phase_bytes = float(2 * b * (split + 1) * h * 2 + kv_bpp * (s - split)) if qflags & k.KVPR_KV_INT4 else attn_bytes
+    attn_kernel = ("attention_partial_ranged x2 (+combine)" if (qflags & k.KVPR_KV_INT4 or split >= 128)
+                   else "attention_partial (+combine)")
     h2d_bytes = float(x_bpp * split + kv_bpp * (s - split))
     gemm_tflops = gemm_flops / (ms_gemm * 1e-3) / 1e12 if split > 0 else 0.0
     attn_gbps = attn_phase_bytes / (ms_attn * 1e-3) / 1e9
     h2d_gbps = h2d_bytes / ((ms_act + ms_kv) * 1e-3) / 1e9
+
+    # the attention kernel again, 20 launches back to back between one pair of events on the same stream: the
+    # per-layer event pair above also holds the two event-to-kernel gaps (~10 us of a ~90 us kernel)
+    kv_res = torch.randn((s + 1, b, 2 * h), dtype=torch.float16, device="cuda")
+    q_res = torch.randn((b, h), dtype=torch.float32, device="cuda")
+    z_res = torch.empty((b, h), dtype=torch.float16, device="cuda")
+    ws_res = torch.empty(k.kvpr_attention_workspace_bytes(b, h, H, s + 1), dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
+    e1.record()
+    e1.synchronize()
+    ms_attn_b2b = e0.elapsed_time(e1) / 20
+    del kv_res
+    attn_gbps_b2b = attn_bytes / (ms_attn_b2b * 1e-3) / 1e9
 
     # HBM-side bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a
     # known-size copy); only valid for the shape and split they were taken at
@@ -409,40 +428,23 @@ def main():
         "latency_over_bound": mean("ms_assemble") / (t_bound_split * 1e3),
         "step_over_bound": ms_step / (t_bound_split * 1e3),
         "breakdown_ms": {"act_copy": ms_act, "kv_copy": ms_kv, "recompute": ms_gemm, "proj": mean("ms_proj"),
-                         "attn": ms_attn, "out": mean("ms_out"), "store": mean("ms_store"), "kv_dequant": mean("ms_dequant")},
+                         "attn": ms_attn, "out": mean("ms_out"), "store": mean("ms_store"), "attn_early": mean("ms_attn_early")},
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12,
                     "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9, "d2h_GBps": prof.d2h_bytes_per_s / 1e9,
                     "attn_GBps": prof.attn_bytes_per_s / 1e9},
         "roofline": {"kernel": "gemm_bias_f16 (recompute GEMM%s)" % (", rotary epilogue" if llama else ""), "bound": "mfma", "achieved": gemm_tflops,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
                      "traffic": traffic, "traffic_detail": traffic_detail, "flops_per_launch": gemm_flops, "avg_ms": ms_gemm},
-        "roofline_attention": {"kernel": attn_kernel, "bound": "hbm", "achieved": attn_gbps,
-                               "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": attn_gbps / PEAK_HBM_GBPS,
-                               "bytes_per_launch": attn_phase_bytes, "avg_ms": ms_attn},
+        # the attention kernel by itself: one pass over all s+1 float16 rows, 20 launches between one pair of events
+        # (the in-layer figures below are event pairs around single ~30-90 us launches and carry ~10 us of gap each)
+        "roofline_attention": {"kernel": "attention_partial (+combine), float16 cache, back to back", "bound": "hbm",
+                               "achieved": attn_gbps_b2b, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                               "frac": attn_gbps_b2b / PEAK_HBM_GBPS, "bytes_per_launch": attn_bytes, "avg_ms": ms_attn_b2b,
+                               "in_layer": {"kernels": attn_kernel, "ms": ms_attn, "ms_before_cache_fence": mean("ms_attn_early"),
+                                            "bytes": attn_phase_bytes, "GBps": attn_gbps}},
         "h2d": {"achieved_GBps": h2d_gbps, "measured_pinned_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
                 "frac": h2d_gbps / (prof.h2d_peak_bytes_per_s / 1e9), "bytes_per_step": h2d_bytes},
     }
-
-    # the attention kernel again, 20 launches back to back between one pair of events on the same stream: the
-    # per-layer event pair above also holds the two event-to-kernel gaps (~10 us of a ~90 us kernel)
-    kv_res = torch.randn((s + 1, b, 2 * h), dtype=torch.float16, device="cuda")
-    q_res = torch.randn((b, h), dtype=torch.float32, device="cuda")
-    z_res = torch.empty((b, h), dtype=torch.float16, device="cuda")
-    ws_res = torch.empty(k.kvpr_attention_workspace_bytes(b, h, H, s + 1), dtype=torch.uint8, device="cuda")
-    for _ in range(3):
-        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(20):
-        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
-    e1.record()
-    e1.synchronize()
-    ms_attn_b2b = e0.elapsed_time(e1) / 20
-    del kv_res
-    result["roofline_attention"].update({
-        "back_to_back_kernel": "attention_partial over float16 rows", "back_to_back_bytes": attn_bytes,
-        "back_to_back_avg_ms": ms_attn_b2b, "back_to_back_achieved": attn_bytes / (ms_attn_b2b * 1e-3) / 1e9,
-        "back_to_back_frac": attn_bytes / (ms_attn_b2b * 1e-3) / 1e9 / PEAK_HBM_GBPS})
 
     if args.extension_chunks > 1 and args.chunks == 1 and cm == k.KVPR_COST_EQ10 and args.split < 0:
         # same layer, same number of steps, X[0:l] copied in parts with each part's GEMM started as it lands

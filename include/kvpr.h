@@ -134,16 +134,17 @@ typedef struct {
     float ms_kv_copy;    /* H2D of KV[l:s]                                             */
     float ms_recompute;  /* recompute GEMM (Eq. 7)                                     */
     float ms_proj;       /* new-token q/k/v projection (Eq. 1, Eq. 5)                  */
-    float ms_attn;       /* decode attention (Eq. 2)                                   */
+    float ms_attn;       /* decode attention (Eq. 2): both phases when it ran in two           */
     float ms_out;        /* output projection (Eq. 3)                                  */
     float ms_store;      /* D2H of the new X / KV rows                                 */
     float ms_assemble;   /* first enqueue -> both KV halves resident: what Eq. 10 models */
     float ms_total;      /* first enqueue -> output projection and store-back done     */
     double t_bound_s;    /* cost-model prediction for the split used (0 if no profile) */
     int32_t split;       /* the split l actually used                                   */
-    float ms_dequant;    /* reserved (0): packed cache rows are dequantised inside the attention kernel; the
-                            activations' dequantisation is part of ms_recompute.  With KVPR_KV_INT4, ms_attn
-                            covers only the attention phase that follows the cache copy       */
+    float ms_attn_early; /* the part of ms_attn that ran before the cache fence: attention over the recomputed
+                            rows and the new row, issued while the cache copy is still in flight (always with
+                            KVPR_KV_INT4, whose transferred rows are then read in packed form; with a float16
+                            cache only in kvpr_layer_decode[_timed] at split >= 128); 0 when one launch did it all */
 } kvpr_layer_timing;
 
 const char* kvpr_last_error(void);
@@ -298,7 +299,9 @@ size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S)
  * host store (Sec. 4.4): rows [0, split) and row S-1 are read from kv16_dev (float16 [S, batch, 2*hidden]),
  * rows [split, S-1) from kvq_dev ([S, batch, kvpr_int4_row_bytes(2*hidden)], indexed by position) and
  * dequantised in registers to exactly the values kvpr_dequant_int4 gives.  Same workspace size as above.
- * split in [0, S-1]; kvq_dev may be null when split == S-1. */
+ * split in [0, S-1].  With kvq_dev null every row comes from kv16_dev: the same two launches (rows [0, split)
+ * and S-1, then rows [split, S-1)) and one combine, which is how kvpr_layer_decode overlaps the attention
+ * over the recomputed rows with the tail of the cache copy. */
 int kvpr_decode_attention_mixed(const void* q_dev, const void* kv16_dev, const void* kvq_dev, void* z_dev, void* ws_dev,
                                 int S, int split, int batch, int hidden, int n_heads, void* stream);
 

@@ -424,8 +424,9 @@ int launch_ranged(const void* q, const void* kv16, const void* kvq, float* ws_ac
 
 }  // namespace
 
-// phase 0: float16 rows [0, split) and row S-1 of kv16.  phase 1: packed rows [split, S-1) of kvq, then the combine
-// into z.  Both phases of one attention must be given the same S, split, batch and hidden.
+// phase 0: float16 rows [0, split) and row S-1 of kv16.  phase 1: rows [split, S-1), packed from kvq if it is not null
+// and float16 from kv16 otherwise, then the combine into z.  Both phases of one attention must be given the same S,
+// split, batch and hidden.
 int launch_attention_mixed(const void* q, const void* kv16, const void* kvq, void* z, void* ws, int S, int split, int batch,
                            int hidden, int n_heads, int phase, hipStream_t st) {
     const int d = hidden / n_heads;
@@ -435,8 +436,10 @@ int launch_attention_mixed(const void* q, const void* kv16, const void* kvq, voi
     if (phase == 0)
         return launch_ranged<false>(q, kv16, kvq, ws_acc, ws_ml, 0, split, S - 1, batch, hidden, d, p.a, 0, st);
     if (p.b.splits > 0)
-        if (int rc = launch_ranged<true>(q, kv16, kvq, ws_acc, ws_ml, split, S - 1 - split, -1, batch, hidden, d, p.b,
-                                         p.a.splits, st))
+        if (int rc = kvq ? launch_ranged<true>(q, kv16, kvq, ws_acc, ws_ml, split, S - 1 - split, -1, batch, hidden, d, p.b,
+                                               p.a.splits, st)
+                         : launch_ranged<false>(q, kv16, kvq, ws_acc, ws_ml, split, S - 1 - split, -1, batch, hidden, d, p.b,
+                                                p.a.splits, st))
             return rc;
     const int64_t threads = (int64_t)batch * (hidden / 8);
     hipLaunchKernelGGL(attention_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ws_acc, ws_ml,

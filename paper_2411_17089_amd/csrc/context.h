@@ -11,10 +11,10 @@ typedef _Float16 half;
 
 // events bracketing each category of one layer (timing enabled)
 struct LayerEvents {
-    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, d0, a0, a1, o1, s0, s1, end;
+    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, e0, e1, a0, a1, o1, s0, s1, end;   // e0..e1: early attention phase
     int seq = -1, split = -1;            // what the slot last recorded
     hipEvent_t* all() { return &start; }
-    static constexpr int count = 15;
+    static constexpr int count = 16;
 };
 
 }  // namespace kvpr

@@ -230,14 +230,20 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     // ---- merge = wait for the transferred rows; then attention over all seq+1 rows (Eq. 2) ----
     // With a packed cache the attention runs in two phases: the recomputed rows and the new row (float16) before the
     // wait, the transferred rows straight from their packed form after it (dequantised in registers), one combine.
-    if (c->qkv)
-        if (int rc = kvpr::launch_attention_mixed(c->q32, dkv, kv_stage, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 0, c->compute))
+    // A float16 cache takes the same two phases in the latency-oriented single-layer call when enough rows are
+    // recomputed: most of the attention then runs under the tail of the cache copy.  (In the layer pipeline the
+    // attention is off the critical path and stays one launch.)
+    const bool two_phase = c->qkv || (fence_copy_to_start && l >= 128);
+    const void* packed = c->qkv ? kv_stage : nullptr;
+    if (ev) KVPR_HIP(hipEventRecord(ev->e0, c->compute));
+    if (two_phase)
+        if (int rc = kvpr::launch_attention_mixed(c->q32, dkv, packed, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 0, c->compute))
             return rc;
+    if (ev) KVPR_HIP(hipEventRecord(ev->e1, c->compute));
     KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_kv[buf], 0));
-    if (ev) KVPR_HIP(hipEventRecord(ev->d0, c->compute));
     if (ev) KVPR_HIP(hipEventRecord(ev->a0, c->compute));
-    if (int rc = c->qkv ? kvpr::launch_attention_mixed(c->q32, dkv, kv_stage, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 1, c->compute)
-                        : kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, seq + 1, b, h, c->d.n_heads, c->compute))
+    if (int rc = two_phase ? kvpr::launch_attention_mixed(c->q32, dkv, packed, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 1, c->compute)
+                           : kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, seq + 1, b, h, c->d.n_heads, c->compute))
         return rc;
     KVPR_HIP(hipEventRecord(c->ev_free[buf], c->compute));
     c->free_recorded[buf] = true;
@@ -299,10 +305,13 @@ int read_timing(kvpr_ctx* c, LayerEvents* ev, int seq, int l, kvpr_layer_timing*
     if (int rc = ms(ev->start, ev->r1, &to_gemm)) return rc;
     if (int rc = ms(ev->start, ev->c_kv, &to_kv)) return rc;
     if (int rc = ms(ev->start, ev->end, &r.ms_total)) return rc;
-    if (int rc = ms(ev->d0, ev->a0, &r.ms_dequant)) return rc;
-    if (int rc = ms(ev->start, ev->a0, &to_deq)) return rc;
-    // both halves resident as float16: with a compressed cache that is the end of its dequantisation
-    r.ms_assemble = (c->qkv && l < seq) ? to_deq : std::max(to_gemm, to_kv);
+    // attention = the phase before the cache fence (empty unless it ran in two phases) + the phase after it
+    float ms_early = 0.f;
+    if (int rc = ms(ev->e0, ev->e1, &ms_early)) return rc;
+    r.ms_attn += ms_early;
+    r.ms_attn_early = ms_early;
+    (void)to_deq;
+    r.ms_assemble = std::max(to_gemm, to_kv);
     r.split = l;
     if (c->have_prof)
         if (int rc = kvpr_cost_linear(&c->prof, c->cost_model, c->plan_chunks(), l, seq, (int64_t)c->x_store_bytes(),

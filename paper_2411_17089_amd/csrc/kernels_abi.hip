@@ -34,7 +34,7 @@ extern "C" int kvpr_decode_attention_mixed(const void* q, const void* kv16, cons
         return fail(KVPR_E_RANGE, "S=%d split=%d batch=%d n_heads=%d out of range", S, split, batch, n_heads);
     if (hidden % n_heads || (hidden / n_heads != 64 && hidden / n_heads != 128) || hidden % 128)
         return fail(KVPR_E_INVAL, "head_dim must be 64 or 128 and hidden a multiple of 128");
-    if (!q || !kv16 || !z || !ws || (split < S - 1 && !kvq)) return fail(KVPR_E_INVAL, "q / kv16 / kvq / z / ws is null");
+    if (!q || !kv16 || !z || !ws) return fail(KVPR_E_INVAL, "q / kv16 / z / ws is null");
     if (int rc = kvpr::launch_attention_mixed(q, kv16, kvq, z, ws, S, split, batch, hidden, n_heads, 0, (hipStream_t)stream)) return rc;
     return kvpr::launch_attention_mixed(q, kv16, kvq, z, ws, S, split, batch, hidden, n_heads, 1, (hipStream_t)stream);
 }

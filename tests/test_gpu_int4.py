@@ -90,6 +90,11 @@ def test_mixed_attention_kernel_matches_oracle(k, S, b, h, H, split):
     k.kvpr_decode_attention(dev(q, torch.float32), full, z2, ws, S, b, h, H)
     torch.cuda.synchronize()
     assert rel_err(got, z2.cpu().numpy()) <= 1e-3
+    # all-float16 two-phase form (no packed source): same rows from one buffer, same result as the single launch
+    z3 = torch.empty_like(z)
+    k.kvpr_decode_attention_mixed(dev(q, torch.float32), full, None, z3, ws, S, split, b, h, H)
+    torch.cuda.synchronize()
+    assert rel_err(z3.cpu().numpy(), z2.cpu().numpy()) <= 1e-3
 
 
 class QRig:
