@@ -171,3 +171,31 @@ def test_full_size_stack_two_layers_sampled_sequences(k):
             assert rel_err(got[n:n + 1], ref) <= 5e-3, n
     finally:
         k.kvpr_destroy(ctx)
+
+
+def test_full_size_longest_context_sampled_sequences(k):
+    """The longest context of the sweep: OPT-30B-shaped layer (hidden 7168, 56 heads), batch 16, context 4096
+    (1.75 GiB of cache in the host store); whole sequences against the oracle at three splits."""
+    (h, H, d), b, s = kvpr_inputs.SHAPES["opt-30b"], 16, 4096
+    layer = kvpr_inputs.make_layer(4, b, s, h, H)
+    dv = upload_layer(layer)
+    w = k.make_weights(wqkv=dv["wqkv"], bqkv=dv["bqkv"], wo=dv["wo"], bo=dv["bo"])
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2)
+    try:
+        k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
+        k.kvpr_store_prefill_kv(ctx, 0, s, w)
+        out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+        refs = {}
+        for n in (3, 15):
+            sub = dict(layer, X=np.ascontiguousarray(layer["X"][:, n:n + 1]), x_new=layer["x_new"][n:n + 1])
+            refs[n] = ko.layer_decode(sub, 0)["o"]
+        for split in (3008, 0, 4096):
+            print(f"full-size longest context split={split}", flush=True)
+            k.kvpr_layer_decode(ctx, 0, s, split, w, dv["x_new"], out)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.isfinite(got).all()
+            for n, ref in refs.items():
+                assert rel_err(got[n:n + 1], ref) <= 3e-3, (split, n)
+    finally:
+        k.kvpr_destroy(ctx)
