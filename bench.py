@@ -305,6 +305,8 @@ def main():
                     help="keep the host store group-wise 4-bit compressed (Sec. 4.4): the cache only, or the cache and the activations")
     ap.add_argument("--adaptive", type=float, default=0.0,
                     help="(stack / columns modes) extension: keep adapting v_com / v_gpu while decoding with this moving-average weight")
+    ap.add_argument("--calibrate", type=int, default=6,
+                    help="untimed decodes that refine the profiled v_com / v_gpu inside the real pipeline before planning (0 = plan from kvpr_profile alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
     args = ap.parse_args()
@@ -346,14 +348,27 @@ def main():
     k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
     k.kvpr_store_prefill_kv(ctx, 0, s, w)          # stand-in for prefill: cache = X.[Wk|Wv]+b, computed on the GPU
 
-    prof = k.kvpr_profile(ctx, b, s)
-    k.kvpr_set_profile(ctx, prof, cm, args.granularity)
+    prof0 = k.kvpr_profile(ctx, b, s)
+    k.kvpr_set_profile(ctx, prof0, cm, args.granularity)
     k.kvpr_set_chunks(ctx, args.chunks)
+    # Refine the two constants in place: a few untimed decodes at the planned split with the run-time adaptation on.
+    # The GEMM inside the real pipeline (fresh activations, cache copy in flight, GPU coming out of an idle stretch)
+    # runs up to 15 % below its isolated rate on the wider shapes; the plan should use what the pipeline delivers.
+    prof = prof0
+    if args.calibrate > 0 and args.split < 0:
+        k.kvpr_set_adaptive(ctx, 0.5)
+        for _ in range(args.calibrate):
+            k.kvpr_layer_decode(ctx, 0, s, -1, w, x_new, out)
+            torch.cuda.synchronize()
+        prof = k.kvpr_get_profile(ctx)
+        k.kvpr_set_adaptive(ctx, 0.0)
     pchunks = args.chunks if cm == k.KVPR_COST_EQ10 else 1
+    # the split comes from the calibrated constants; every "bound" below is the cost model with the start-up profile's
+    # constants (isolated copy rate, GEMM under a concurrent copy), so that the ratios are not measured against themselves
     l_star, t_bound = k.kvpr_plan_split_linear(prof, cm, pchunks, s, x_bpp, kv_bpp, f_pp, args.granularity)
     split = l_star if args.split < 0 else args.split
-    t_bound_split = k.kvpr_cost_linear(prof, cm, pchunks, split, s, x_bpp, kv_bpp, f_pp)
-    l_eq10, t_eq10 = k.kvpr_plan_split_linear(prof, k.KVPR_COST_EQ10, 1, s, x_bpp, kv_bpp, f_pp, args.granularity)
+    t_bound_split = k.kvpr_cost_linear(prof0, cm, pchunks, split, s, x_bpp, kv_bpp, f_pp)
+    l_eq10, t_eq10 = k.kvpr_plan_split_linear(prof0, k.KVPR_COST_EQ10, 1, s, x_bpp, kv_bpp, f_pp, args.granularity)
 
     for _ in range(args.warmup):
         k.kvpr_layer_decode(ctx, 0, s, split, w, x_new, out)
@@ -430,7 +445,9 @@ def main():
         "breakdown_ms": {"act_copy": ms_act, "kv_copy": ms_kv, "recompute": ms_gemm, "proj": mean("ms_proj"),
                          "attn": ms_attn, "out": mean("ms_out"), "store": mean("ms_store"), "attn_early": mean("ms_attn_early")},
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12,
-                    "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9, "d2h_GBps": prof.d2h_bytes_per_s / 1e9,
+                    "before_calibration": {"v_com_GBps": prof0.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof0.gemm_flops_per_s / 1e12},
+                    "calibration_decodes": args.calibrate if args.split < 0 else 0,
+                    "v_gpu_alone_TFLOPs": prof.gemm_alone_flops_per_s / 1e12, "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9, "d2h_GBps": prof.d2h_bytes_per_s / 1e9,
                     "attn_GBps": prof.attn_bytes_per_s / 1e9},
         "roofline": {"kernel": "gemm_bias_f16 (recompute GEMM%s)" % (", rotary epilogue" if llama else ""), "bound": "mfma", "achieved": gemm_tflops,
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
@@ -450,7 +467,8 @@ def main():
         # same layer, same number of steps, X[0:l] copied in parts with each part's GEMM started as it lands
         c = args.extension_chunks
         k.kvpr_set_chunks(ctx, c)
-        l_c, t_c = k.kvpr_plan_split_linear(prof, k.KVPR_COST_EQ10, c, s, x_bpp, kv_bpp, f_pp, args.granularity)
+        l_c, _ = k.kvpr_plan_split_linear(prof, k.KVPR_COST_EQ10, c, s, x_bpp, kv_bpp, f_pp, args.granularity)
+        t_c = k.kvpr_cost_linear(prof0, k.KVPR_COST_EQ10, c, l_c, s, x_bpp, kv_bpp, f_pp)
         for _ in range(args.warmup):
             k.kvpr_layer_decode(ctx, 0, s, l_c, w, x_new, out)
         torch.cuda.synchronize()

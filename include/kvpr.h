@@ -104,12 +104,17 @@ typedef struct {
  * plus figures that are only reported. */
 typedef struct {
     double h2d_bytes_per_s;      /* v_com: pinned host->device rate at the full-KV copy size */
-    double gemm_flops_per_s;     /* v_gpu: recompute GEMM rate at M = batch*seq              */
+    double gemm_flops_per_s;     /* v_gpu: recompute GEMM rate at M = batch*seq, measured while a cache-sized
+                                    host-to-device copy is in flight (the condition of Eq. 10's max term) */
     double h2d_latency_s;        /* optional fixed cost per non-empty copy (0 = paper's linear model) */
     double gemm_latency_s;       /* optional fixed cost per non-empty GEMM (0 = paper's linear model) */
     double d2h_bytes_per_s;      /* reported only */
     double attn_bytes_per_s;     /* reported only: decode attention's KV read rate           */
     double h2d_peak_bytes_per_s; /* reported only: best rate over a 64 KiB .. 1 GiB sweep    */
+    double gemm_alone_flops_per_s; /* reported only: the same GEMM with nothing else running             */
+    int64_t gemm_round_flops;    /* extension of Eq. 9 (0 = the paper's divisible work): the recompute GEMM runs in
+                                    rounds of one 256 x 256 tile per compute unit; N_KV is charged rounded up to a
+                                    multiple of this many flops.  kvpr_profile fills it (n_CU * 2*256*256*hidden) */
     double layer_other_s;        /* the rest of one layer's GPU work at this batch / context (token projections,
                                     attention, output projection, FFN if the context has one): used by
                                     KVPR_COST_PIPE only, where it shares the GPU with the recomputation; 0 = ignore */
@@ -179,7 +184,7 @@ int kvpr_store_prefill_kv(kvpr_ctx* ctx, int layer, int seq, const kvpr_layer_we
 
 /* Profiler (Sec. 3.1): measures on this machine, for this ctx's hidden size, the pinned
  * H2D rate at the size of a full KV copy of [seq, batch] and the recompute GEMM rate at
- * M = batch*seq (median of 5 after warm-up).  Synchronises.  batch*seq must not exceed
+ * M = batch*seq (median of 5 after warm-up; the GEMM once alone and once under a concurrent copy).  Synchronises.  batch*seq must not exceed
  * the context's batch*max_seq. */
 int kvpr_profile(kvpr_ctx* ctx, int batch, int seq, kvpr_profile_t* out);
 

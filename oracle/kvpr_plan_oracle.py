@@ -143,10 +143,15 @@ def plan_split_chunked(chunks: int, b: int, s: int, h: int, p: int, v_com: float
 # byte rates.  chunks > 1 selects the chunked-copy extension above (Eq. 10 only).
 # --------------------------------------------------------------------------
 def cost_linear(model: int, chunks: int, l: int, s: int, x_bpp: int, kv_bpp: int, flops_pp: int,
-                v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0) -> float:
+                v_com: float, v_gpu: float, lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0,
+                round_flops: int = 0) -> float:
+    """round_flops > 0 (an extension of Eq. 9): the GPU does the recomputation in indivisible rounds of that
+    many flops (one tile per compute unit), so N_KV is charged rounded up to whole rounds."""
     m_x = x_bpp * l
     m_kv = kv_bpp * (s - l)
     n_kv = flops_pp * l
+    if round_flops > 0:
+        n_kv = -(-n_kv // round_flops) * round_flops
     send_x = float(m_x) / v_com
     send_kv = float(m_kv) / v_com
     gemm = float(n_kv) / v_gpu
@@ -181,10 +186,10 @@ def cost_linear(model: int, chunks: int, l: int, s: int, x_bpp: int, kv_bpp: int
 
 def plan_split_linear(model: int, chunks: int, s: int, x_bpp: int, kv_bpp: int, flops_pp: int,
                       v_com: float, v_gpu: float, granularity: int = 1,
-                      lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0):
+                      lat_com: float = 0.0, lat_gpu: float = 0.0, other: float = 0.0, round_flops: int = 0):
     best_l, best_t = -1, float("inf")
     for l in candidates(s, granularity):
-        t = cost_linear(model, chunks, l, s, x_bpp, kv_bpp, flops_pp, v_com, v_gpu, lat_com, lat_gpu, other)
+        t = cost_linear(model, chunks, l, s, x_bpp, kv_bpp, flops_pp, v_com, v_gpu, lat_com, lat_gpu, other, round_flops)
         if t < best_t:
             best_l, best_t = l, t
     return best_l, best_t

@@ -32,7 +32,8 @@ class kvpr_model_desc(C.Structure):
 class kvpr_profile_t(C.Structure):
     _fields_ = [(n, C.c_double) for n in
                 ("h2d_bytes_per_s", "gemm_flops_per_s", "h2d_latency_s", "gemm_latency_s",
-                 "d2h_bytes_per_s", "attn_bytes_per_s", "h2d_peak_bytes_per_s", "layer_other_s")]
+                 "d2h_bytes_per_s", "attn_bytes_per_s", "h2d_peak_bytes_per_s", "gemm_alone_flops_per_s")] + \
+               [("gemm_round_flops", C.c_int64), ("layer_other_s", C.c_double)]
 
 
 class kvpr_layer_weights(C.Structure):
@@ -175,8 +176,8 @@ def kvpr_profile(ctx, batch, seq) -> kvpr_profile_t:
     return p
 
 
-def make_profile(v_com, v_gpu, lat_com=0.0, lat_gpu=0.0, other=0.0) -> kvpr_profile_t:
-    return kvpr_profile_t(v_com, v_gpu, lat_com, lat_gpu, 0.0, 0.0, 0.0, other)
+def make_profile(v_com, v_gpu, lat_com=0.0, lat_gpu=0.0, other=0.0, round_flops=0) -> kvpr_profile_t:
+    return kvpr_profile_t(v_com, v_gpu, lat_com, lat_gpu, 0.0, 0.0, 0.0, 0.0, round_flops, other)
 
 
 def kvpr_plan_split(prof, cost_model, batch, seq, hidden, elem_bytes=2, granularity=1):

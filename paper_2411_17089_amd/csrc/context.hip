@@ -280,7 +280,9 @@ int adapt_poll(kvpr_ctx* c) {
         const int64_t l = ev->split, s = ev->seq;
         const int64_t link_bytes = (int64_t)c->x_store_bytes() * l + (int64_t)c->kv_store_bytes() * (s - l);
         // with a chunked activation copy the GEMM interval includes waiting for chunks: the link sample only
-        const int64_t flops = c->chunks > 1 ? 0 : c->flops_per_pos() * l;
+        // (whole rounds of work when the profile says the GEMM works in rounds, as the cost model charges them)
+        int64_t flops = c->chunks > 1 ? 0 : c->flops_per_pos() * l;
+        if (const int64_t r = c->prof.gemm_round_flops; r > 0) flops = (flops + r - 1) / r * r;
         if (int rc = kvpr_adapt_update(&c->prof, c->adapt_alpha, link_bytes, ((double)ms_x + (double)ms_kv) * 1e-3, flops,
                                        (double)ms_rc * 1e-3))
             return rc;

@@ -18,7 +18,10 @@
 //  * Epilogue: bias + conversion in registers, C tile staged through LDS, global stores of whole
 //    512-byte row pieces (the direct 8-byte stores of the first version cost ~15 % of the kernel).
 //  * Workgroup ids are remapped so that the workgroups an XCD runs concurrently (ids equal mod 8)
-//    form a compact block of tiles sharing A/W panels in that XCD's L2.
+//    form a compact block of tiles sharing A/W panels in that XCD's L2.  Across XCDs there are two
+//    mappings: each XCD takes a contiguous share of the tile rows (W is re-read by all XCDs and lives in
+//    the memory-side cache; best while W is small), or each XCD takes a band of tile columns and all
+//    walk the tile rows together (the A panels in flight are shared by the eight XCDs; best for large W).
 //  * Tail rows in M / N are clamped on load (they re-read the last valid row) and skipped on store.
 //  * Rotary models (HD = head width 64 or 128): the cache holds K after the rotary embedding, so the
 //    recomputed K columns are rotated in the epilogue with the position of their row
@@ -44,6 +47,7 @@ constexpr int ROW_BYTES = 64;   // one LDS row of a stage
 struct RopeArgs {
     const float2* table;
     int cols, batch, pos0;
+    int xcd_split_n;     // tile -> workgroup mapping (not a rotary parameter; rides in the same argument block)
 };
 
 template <int VM, int LGKM0>
@@ -70,15 +74,31 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int pid = blockIdx.x;
-    const int logical = (pid & 7) * tiles_per_xcd + (pid >> 3);
-    if (logical >= tiles_m * tiles_n) return;
-    const int group_sz = GROUP_M * tiles_n;
-    const int group = logical / group_sz;
-    const int first_m = group * GROUP_M;
-    const int gm = min(tiles_m - first_m, GROUP_M);
-    const int in_group = logical - group * group_sz;
-    const int tile_m = first_m + in_group % gm;
-    const int tile_n = in_group / gm;
+    int tile_m, tile_n;
+    if (rope.xcd_split_n) {
+        // every XCD owns a band of tile columns and all XCDs walk the tile rows together: the A panels in use are
+        // shared by the eight XCDs (one HBM fetch, then memory-side cache hits) and W can stay in that cache
+        const int xcd = pid & 7, i = pid >> 3;
+        const int n_lo = xcd * tiles_n / 8, width = (xcd + 1) * tiles_n / 8 - n_lo;
+        if (i >= width * tiles_m) return;
+        const int group_sz = GROUP_M * width;
+        const int group = i / group_sz;
+        const int first_m = group * GROUP_M;
+        const int gm = min(tiles_m - first_m, GROUP_M);
+        const int in_group = i - group * group_sz;
+        tile_m = first_m + in_group % gm;
+        tile_n = n_lo + in_group / gm;
+    } else {
+        const int logical = (pid & 7) * tiles_per_xcd + (pid >> 3);
+        if (logical >= tiles_m * tiles_n) return;
+        const int group_sz = GROUP_M * tiles_n;
+        const int group = logical / group_sz;
+        const int first_m = group * GROUP_M;
+        const int gm = min(tiles_m - first_m, GROUP_M);
+        const int in_group = logical - group * group_sz;
+        tile_m = first_m + in_group % gm;
+        tile_n = in_group / gm;
+    }
     const int64_t m0 = (int64_t)tile_m * BM;
     const int n0 = tile_n * BN;
 
@@ -276,9 +296,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     }
 }
 
+int g_gemm_xcd_split_n = -1;   // -1 = default choice
+
 template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M, int HD = 0>
 int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
-                hipStream_t st, RopeArgs rope = RopeArgs{nullptr, 0, 1, 0}) {
+                hipStream_t st, RopeArgs rope = RopeArgs{nullptr, 0, 1, 0, 0}) {
     auto kern = gemm_bias_f16<BM, BN, WM, WN, NSTAGE, GROUP_M, HD>;
     constexpr int stage_bytes = NSTAGE * (BM + BN) * ROW_BYTES, c_bytes = BM * (BN * 2 + 16);
     constexpr int lds_bytes = stage_bytes > c_bytes ? stage_bytes : c_bytes;
@@ -290,7 +312,14 @@ int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t
     }
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
     const int64_t total = (int64_t)tiles_m * tiles_n;
-    const int tiles_per_xcd = (int)((total + 7) / 8);
+    // Which mapping: measured on MI355X, giving every XCD a band of W wins once W no longer sits comfortably in the
+    // memory-side cache next to the A panels in flight (N = 14336, K = 7168, 196 MiB: +12 %), and loses 1-2 % when W
+    // is small (64 MiB at K = 4096); equal at 100 MiB.
+    const bool big_w = (int64_t)N * K * 2 > ((int64_t)128 << 20);
+    rope.xcd_split_n = g_gemm_xcd_split_n >= 0 ? g_gemm_xcd_split_n : (big_w ? 1 : 0);
+    if (tiles_n < 8) rope.xcd_split_n = 0;
+    const int max_width = (tiles_n + 7) / 8;
+    const int tiles_per_xcd = rope.xcd_split_n ? max_width * tiles_m : (int)((total + 7) / 8);
     const unsigned grid = (unsigned)(tiles_per_xcd * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds_bytes, st, (const _Float16*)a, (const _Float16*)w,
                        (const _Float16*)bias, (_Float16*)c, M, N, K, ldc, tiles_m, tiles_n, tiles_per_xcd, rope);
@@ -318,7 +347,7 @@ int launch_gemm(const void* a, const void* w, const void* bias, void* c, int64_t
 int launch_gemm_rope(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
                      const void* table, int rope_cols, int head_dim, int batch, int pos0, hipStream_t st) {
     if (M == 0) return KVPR_OK;
-    const RopeArgs r{(const float2*)table, rope_cols, batch, pos0};
+    const RopeArgs r{(const float2*)table, rope_cols, batch, pos0, 0};
     if (head_dim == 64) return launch_tile<256, 256, 4, 2, 4, 8, 64>(a, w, bias, c, M, N, K, ldc, st, r);
     return launch_tile<256, 256, 4, 2, 4, 8, 128>(a, w, bias, c, M, N, K, ldc, st, r);
 }
@@ -327,5 +356,10 @@ int launch_gemm_rope(const void* a, const void* w, const void* bias, void* c, in
 
 extern "C" int kvpr_debug_set_gemm_variant(int v) {
     kvpr::g_gemm_variant = v;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_debug_set_gemm_mapping(int xcd_split_n) {
+    kvpr::g_gemm_xcd_split_n = xcd_split_n;
     return KVPR_OK;
 }

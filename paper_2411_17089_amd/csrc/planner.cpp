@@ -34,6 +34,7 @@ int check_profile(const kvpr_profile_t* p, int model, int chunks) {
                           p->h2d_bytes_per_s, p->gemm_flops_per_s);
     if (!lat_ok(p->h2d_latency_s) || !lat_ok(p->gemm_latency_s) || !lat_ok(p->layer_other_s))
         return kvpr::fail(KVPR_E_INVAL, "profile latencies must be finite and >= 0");
+    if (p->gemm_round_flops < 0) return kvpr::fail(KVPR_E_INVAL, "gemm_round_flops must be >= 0");
     return KVPR_OK;
 }
 
@@ -43,7 +44,7 @@ int check_sizes(const Sizes& z, int seq) {
     if (z.x_bpp < 0 || z.kv_bpp < 0 || z.flops_pp < 0)
         return kvpr::fail(KVPR_E_RANGE, "per-position sizes must be >= 0");
     const long double lim = 9007199254740992.0L;
-    if ((long double)z.x_bpp * seq >= lim || (long double)z.kv_bpp * seq >= lim || (long double)z.flops_pp * seq >= lim)
+    if ((long double)z.x_bpp * seq >= lim || (long double)z.kv_bpp * seq >= lim || (long double)z.flops_pp * seq >= lim / 2)
         return kvpr::fail(KVPR_E_RANGE, "problem too large for exact byte / flop counts");
     return KVPR_OK;
 }
@@ -60,11 +61,18 @@ int paper_sizes(int batch, int seq, int hidden, int elem_bytes, Sizes* z) {
     return KVPR_OK;
 }
 
+// Eq. 8, charged in whole rounds of work when the profile says the GPU works in rounds
+int64_t recompute_flops(const kvpr_profile_t* p, int64_t l, const Sizes& z) {
+    const int64_t n = z.flops_pp * l;
+    const int64_t r = p->gemm_round_flops;
+    return r > 0 ? (n + r - 1) / r * r : n;
+}
+
 // Eq. 10 (or a variant) at one split
 double cost_at(const kvpr_profile_t* p, int model, int64_t l, int64_t s, const Sizes& z) {
     double t_act = (double)(z.x_bpp * l) / p->h2d_bytes_per_s;
     double t_kv = (double)(z.kv_bpp * (s - l)) / p->h2d_bytes_per_s;
-    double t_rc = (double)(z.flops_pp * l) / p->gemm_flops_per_s;   // Eq. 9
+    double t_rc = (double)recompute_flops(p, l, z) / p->gemm_flops_per_s;   // Eq. 9
     if (l > 0) {
         t_act = t_act + p->h2d_latency_s;
         t_rc = t_rc + p->gemm_latency_s;
@@ -89,7 +97,7 @@ double cost_at(const kvpr_profile_t* p, int model, int64_t l, int64_t s, const S
 double cost_chunked_at(const kvpr_profile_t* p, int chunks, int64_t l, int64_t s, const Sizes& z) {
     const double t_act = (double)(z.x_bpp * l) / p->h2d_bytes_per_s;
     double t_kv = (double)(z.kv_bpp * (s - l)) / p->h2d_bytes_per_s;
-    const double t_rc = (double)(z.flops_pp * l) / p->gemm_flops_per_s;
+    const double t_rc = (double)recompute_flops(p, l, z) / p->gemm_flops_per_s;
     if (l < s) t_kv = t_kv + p->h2d_latency_s;
     double done = 0.0;                                   // end of the GEMM of the parts so far
     if (l > 0) {

@@ -29,7 +29,7 @@ int main() {
     for (double vc : rates)
         for (double vg : rates)
             for (double other : {0.0, 1e-3, nan}) {
-                kvpr_profile_t p{vc, vg, 1e-5, 2e-5, 0, 0, 0, other};
+                kvpr_profile_t p{vc, vg, 1e-5, 2e-5, 0, 0, 0, 0, (other > 0) ? (int64_t)1 << 33 : 0, other};
                 for (int model = -1; model <= 4; ++model)
                     for (int s : seqs)
                         for (int g : grans) {
@@ -50,7 +50,7 @@ int main() {
             }
     int32_t l;
     tally(kvpr_plan_split(nullptr, 0, 1, 1, 64, 2, 1, &l, nullptr));
-    kvpr_profile_t good{1e9, 1e12, 0, 0, 0, 0, 0, 0};
+    kvpr_profile_t good{1e9, 1e12, 0, 0, 0, 0, 0, 0, 0, 0};
     tally(kvpr_plan_split(&good, 0, 1, 1, 64, 2, 1, nullptr, nullptr));
     tally(kvpr_plan_split(&good, 0, 2000000000, 2000000000, 2000000000, 2, 1, &l, nullptr));
     tally(kvpr_cost(&good, 0, 0, 1, 1, 64, 2, nullptr));

@@ -220,3 +220,23 @@ def test_pipelined_form_with_the_rest_of_the_layer():
     # the other forms ignore it
     assert po.cost(po.COST_EQ10, 4, **toy, other=3.0) == po.cost(po.COST_EQ10, 4, **toy)
     assert po.cost_linear(po.COST_PIPE, 1, 7, 9, 1, 2, 4, 1.0, 4.0, other=3.0) == 11.0
+
+
+def test_recomputation_charged_in_whole_rounds():
+    # 60 flop per position, rounds of 100 flop, GPU 10 flop/s: l = 2 -> 120 flop -> 2 rounds = 200 flop = 20 s
+    # (link 3 B/s, x 9 B/pos, cache 18 B/pos, s = 8: send_x = 6, send_kv = 36) -> Eq. 10: 6 + max(20, 36) = 42
+    assert po.cost_linear(po.COST_EQ10, 1, 2, 8, 9, 18, 60, 3.0, 10.0, round_flops=100) == 42.0
+    # l = 6: 360 flop -> 4 rounds = 400 flop = 40 s; send_x = 18, send_kv = 12 -> 18 + 40 = 58 (54 without rounds)
+    assert po.cost_linear(po.COST_EQ10, 1, 6, 8, 9, 18, 60, 3.0, 10.0, round_flops=100) == 58.0
+    # work that is a whole number of rounds costs the same either way; l = 5 -> 300 flop = 3 rounds
+    assert po.cost_linear(po.COST_EQ10, 1, 5, 8, 9, 18, 60, 3.0, 10.0, round_flops=100) == \
+        po.cost_linear(po.COST_EQ10, 1, 5, 8, 9, 18, 60, 3.0, 10.0)
+    # the plan prefers splits that fill their last round: at the OPT-13B shape (40 tile columns, batch 32) 768
+    # positions are 15 full rounds of 256 tiles, 832 are 16.25
+    b, h, s = 32, 5120, 1024
+    fp, rf = 4 * b * h * h, 256 * 2 * 256 * 256 * h
+    v_com, v_gpu = 56e9, 1.10e15
+    l_plain, _ = po.plan_split_linear(po.COST_EQ10, 1, s, b * h * 2, 2 * b * h * 2, fp, v_com, v_gpu, 64)
+    l_round, t_round = po.plan_split_linear(po.COST_EQ10, 1, s, b * h * 2, 2 * b * h * 2, fp, v_com, v_gpu, 64, round_flops=rf)
+    assert (fp * l_round) % rf == 0 or t_round <= po.cost_linear(po.COST_EQ10, 1, l_plain, s, b * h * 2, 2 * b * h * 2, fp, v_com, v_gpu, round_flops=rf)
+    assert l_round == 768 and l_plain == 832

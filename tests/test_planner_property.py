@@ -19,16 +19,17 @@ sizes = st.integers(min_value=0, max_value=2 ** 36)
 
 @settings(max_examples=400, deadline=None)
 @given(model=st.integers(0, 3), chunks=st.integers(1, 32), s=st.integers(0, 600), x_bpp=sizes, kv_bpp=sizes, fpp=sizes,
-       v_com=rates, v_gpu=rates, lat_com=lats, lat_gpu=lats, other=lats, g=st.integers(1, 700))
-def test_linear_planner_equals_oracle(k, model, chunks, s, x_bpp, kv_bpp, fpp, v_com, v_gpu, lat_com, lat_gpu, other, g):
+       v_com=rates, v_gpu=rates, lat_com=lats, lat_gpu=lats, other=lats, g=st.integers(1, 700),
+       rf=st.one_of(st.just(0), st.integers(1, 2 ** 40)))
+def test_linear_planner_equals_oracle(k, model, chunks, s, x_bpp, kv_bpp, fpp, v_com, v_gpu, lat_com, lat_gpu, other, g, rf):
     if model != po.COST_EQ10:
         chunks = 1
-    prof = k.make_profile(v_com, v_gpu, lat_com, lat_gpu, other)
-    want = po.plan_split_linear(model, chunks, s, x_bpp, kv_bpp, fpp, v_com, v_gpu, g, lat_com, lat_gpu, other)
+    prof = k.make_profile(v_com, v_gpu, lat_com, lat_gpu, other, rf)
+    want = po.plan_split_linear(model, chunks, s, x_bpp, kv_bpp, fpp, v_com, v_gpu, g, lat_com, lat_gpu, other, rf)
     assert k.kvpr_plan_split_linear(prof, model, chunks, s, x_bpp, kv_bpp, fpp, g) == want
     for l in {0, s // 2, s}:
         assert k.kvpr_cost_linear(prof, model, chunks, l, s, x_bpp, kv_bpp, fpp) == \
-            po.cost_linear(model, chunks, l, s, x_bpp, kv_bpp, fpp, v_com, v_gpu, lat_com, lat_gpu, other)
+            po.cost_linear(model, chunks, l, s, x_bpp, kv_bpp, fpp, v_com, v_gpu, lat_com, lat_gpu, other, rf)
 
 
 @settings(max_examples=200, deadline=None)
