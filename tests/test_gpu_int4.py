@@ -292,3 +292,34 @@ def test_decoder_stack_and_columns_over_compressed_store(k):
             assert rel_err(got[q], oracle(q, [splits[j * nb + q] for j in range(n_layers)])) <= TOL, q
     finally:
         k.kvpr_destroy(ctx)
+
+
+def test_store_write_in_pieces_and_row_bookkeeping(k):
+    """Rows written in several calls (and a hole refused at decode time) land packed exactly as one call would."""
+    b, s, h, H = 3, 40, 256, 2
+    lay = kvpr_inputs.make_layer(41, b, s, h, H)
+    stored = ko.stored_kv(lay, "fp16").astype(np.float16)
+    ctx = k.kvpr_create(1, h, H, h // H, 0, b, s + 2, dtype=k.KVPR_F16 | k.KVPR_STORE_INT4)
+    try:
+        X = np.ascontiguousarray(lay["X"])
+        for t0, t1 in ((0, 7), (7, 8), (8, 33)):
+            k.kvpr_store_write(ctx, 0, t0, t1, np.ascontiguousarray(X[t0:t1]), np.ascontiguousarray(stored[t0:t1]))
+        d = upload_layer(lay)
+        w = k.make_weights(wqkv=d["wqkv"], bqkv=d["bqkv"], wo=d["wo"], bo=d["bo"])
+        out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+        with pytest.raises(k.KvprError) as e:                       # rows [33, 40) were never written
+            k.kvpr_layer_decode(ctx, 0, s, 10, w, d["x_new"], out)
+        assert e.value.code == k.KVPR_E_STATE
+        k.kvpr_store_write(ctx, 0, 33, s, np.ascontiguousarray(X[33:]), np.ascontiguousarray(stored[33:]))
+        xp, kvp = k.kvpr_store_ptrs(ctx, 0)
+        xb, kb = k.kvpr_int4_row_bytes(h), k.kvpr_int4_row_bytes(2 * h)
+        xs = np.ctypeslib.as_array(ctypes.cast(xp, ctypes.POINTER(ctypes.c_uint8)), (s * b * xb,)).reshape(s, b, xb)
+        kvs = np.ctypeslib.as_array(ctypes.cast(kvp, ctypes.POINTER(ctypes.c_uint8)), (s * b * kb,)).reshape(s, b, kb)
+        assert np.array_equal(xs, qo.pack_rows(*qo.quantize_rows(X)))
+        assert np.array_equal(kvs, qo.pack_rows(*qo.quantize_rows(stored)))
+        k.kvpr_layer_decode(ctx, 0, s, 10, w, d["x_new"], out)
+        torch.cuda.synchronize()
+        ref = ko.layer_decode(dict(lay, X=qo.roundtrip(X).astype(np.float64)), 10, qo.roundtrip(stored).astype(np.float64))["o"]
+        assert rel_err(out.cpu().numpy(), ref) <= TOL
+    finally:
+        k.kvpr_destroy(ctx)
