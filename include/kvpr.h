@@ -53,8 +53,9 @@ extern "C" {
 #define KVPR_F16 1
 /* Flags or-ed into kvpr_model_desc.dtype: keep the host store group-wise 4-bit compressed
  * (Sec. 4.4 "KV Cache Compression").  KV_INT4 compresses the cache rows, X_INT4 the stored
- * activations; KVPR_STORE_INT4 sets both.  All arithmetic stays float16 / float32: rows are
- * dequantised on the GPU after the copy, new rows are quantised on the GPU before the store-back.
+ * activations; KVPR_STORE_INT4 sets both.  All arithmetic stays float16 / float32: activation rows
+ * are dequantised on the GPU after the copy, cache rows inside the attention kernel, and new rows
+ * are quantised on the GPU before the store-back.
  * Compressing the cache alone makes a position's activations (2h bytes) larger than its cache
  * (9h/8 bytes), and Eq. 10 then never chooses to recompute; with both, the 1 : 2 ratio of Eq. 6
  * is kept (9h/16 against 9h/8 bytes per position and sequence). */
