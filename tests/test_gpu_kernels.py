@@ -46,6 +46,29 @@ def test_recompute_gemm_matches_oracle(k, variant, M, N, K):
     assert np.mean(got[:, :N].astype(np.float64) != ko.round_fp16(ref)) < 0.05
 
 
+@pytest.mark.parametrize("mapping", [0, 1])
+@pytest.mark.parametrize("M,N,K", [(700, 2304, 256), (2100, 2048, 128), (5000, 4104, 64), (300, 3328, 192)])
+def test_recompute_gemm_tile_mappings(k, mapping, M, N, K):
+    """Both workgroup-to-tile mappings (XCDs split the tile rows / the tile columns) on shapes with 8-17 tile
+    columns, uneven column bands and ragged tails in M and N: every element written once, none outside."""
+    print(f"gemm mapping={mapping} M={M} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(M + N + mapping)
+    A = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    bias = (rng.standard_normal(N) * 0.1).astype(np.float16)
+    ldc = N + 8
+    c = torch.full((M + 3, ldc), float("nan"), dtype=torch.float16, device="cuda")
+    k.lib.kvpr_debug_set_gemm_mapping(mapping)
+    try:
+        k.kvpr_recompute_gemm(dev(A), dev(W), dev(bias), c, M, N, K, ldc)
+        torch.cuda.synchronize()
+    finally:
+        k.lib.kvpr_debug_set_gemm_mapping(-1)
+    got = c.cpu().numpy()
+    assert np.isnan(got[:M, N:]).all() and np.isnan(got[M:]).all()
+    assert rel_err(got[:M, :N], ko.project(A, W.T, bias)) <= TIGHT
+
+
 def test_recompute_gemm_no_bias_and_empty(k):
     rng = np.random.default_rng(1)
     A = rng.standard_normal((70, 128)).astype(np.float16)
