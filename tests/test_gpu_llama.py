@@ -48,6 +48,25 @@ def test_rotary_recompute_gemm_matches_oracle(k, l, b, h, H, pos0):
     assert e.value.code == k.KVPR_E_RANGE
 
 
+def test_rotary_gemm_with_column_band_mapping(k):
+    """The rotary epilogue under the mapping that gives every XCD a band of tile columns (8 tile columns here)."""
+    l, b, h, H, pos0 = 50, 7, 1024, 8, 3
+    d = h // H
+    lay = kvpr_inputs.make_layer(77, b, l, h, H)
+    table = dev(k.kvpr_rope_table(pos0 + l, d), torch.float32)
+    wkv = dev(np.concatenate([lay["Wk"].T, lay["Wv"].T], 0))
+    want = lo.recompute_kv(lay["X"], lay["Wk"], lay["Wv"], H, pos0=pos0).reshape(l * b, 2 * h)
+    for mapping in (1, 0):
+        out = torch.full((l * b, 2 * h), float("nan"), dtype=torch.float16, device="cuda")
+        k.lib.kvpr_debug_set_gemm_mapping(mapping)
+        try:
+            k.kvpr_recompute_gemm_rope(dev(lay["X"]), wkv, None, out, l * b, 2 * h, h, 2 * h, table, pos0 + l, h, d, b, pos0)
+            torch.cuda.synchronize()
+        finally:
+            k.lib.kvpr_debug_set_gemm_mapping(-1)
+        assert rel_err(out.cpu().numpy(), want) <= 2e-3, mapping
+
+
 def test_rotary_token_projection_matches_oracle(k):
     b, h, H, pos = 5, 512, 4, 37
     rng = np.random.default_rng(3)
