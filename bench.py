@@ -437,6 +437,9 @@ def main():
                    "store_int4": args.store_int4},
         "ms_per_layer": ms_step,
         "ms_assemble": mean("ms_assemble"), "ms_total_events": mean("ms_total"),
+        # per-step spread (event time first enqueue -> end of the step): the link of these boxes has occasional slow stretches
+        "ms_total_events_min_median_max": [float(np.min([t.ms_total for t in tim])), float(np.median([t.ms_total for t in tim])),
+                                           float(np.max([t.ms_total for t in tim]))],
         "cost_model_bound_ms": t_bound_split * 1e3,
         "eq10_bound_ms_at_its_own_optimum": t_eq10 * 1e3, "eq10_l_star": l_eq10,
         "step_over_eq10_bound": ms_step / (t_eq10 * 1e3),
