@@ -303,6 +303,20 @@ int kvpr_recompute_gemm(const void* a_dev, const void* w_dev, const void* bias_d
 int kvpr_decode_attention(const void* q_dev, const void* kv_dev, void* z_dev, void* ws_dev,
                           int S, int batch, int hidden, int n_heads, void* stream);
 size_t kvpr_attention_workspace_bytes(int batch, int hidden, int n_heads, int S);
+/* kvpr_decode_attention for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results as kvpr_decode_attention, but the partial results of a launch that splits the positions
+ * across workgroups go to a static device array of KVPR_ATTENTION_STATIC_SCRATCH_BYTES that every GPU the
+ * library runs on holds until the process ends.  The call allocates and frees nothing.  A shape whose
+ * partials (splits * batch * hidden * 5 bytes, splits as kvpr_decode_attention chooses them; 0 when one
+ * workgroup per sequence and column group suffices) exceed the array is refused with KVPR_E_RANGE; the
+ * split choice keeps them below 1.3 MiB for every shape, so only a forced split count gets there.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two threads)
+ * race; calls on one stream are ordered.  Nothing in the array needs clearing between calls: every slot
+ * that a launch reads was written by that launch. */
+#define KVPR_ATTENTION_STATIC_SCRATCH_BYTES (2u << 20)
+int kvpr_decode_attention_static(const void* q_dev, const void* kv_dev, void* z_dev,
+                                 int S, int batch, int hidden, int n_heads, void* stream);
 /* The same attention (Eq. 2) over a cache whose rows [split, S-1) are still in the packed 4-bit form of the
  * host store (Sec. 4.4): rows [0, split) and row S-1 are read from kv16_dev (float16 [S, batch, 2*hidden]),
  * rows [split, S-1) from kvq_dev ([S, batch, kvpr_int4_row_bytes(2*hidden)], indexed by position) and

@@ -22,6 +22,7 @@ KVPR_KV_INT4, KVPR_X_INT4, KVPR_STORE_INT4 = 0x100, 0x200, 0x300
 KVPR_COST_EQ10, KVPR_COST_NS, KVPR_COST_ROW, KVPR_COST_PIPE = 0, 1, 2, 3
 KVPR_DEBUG_SYNC, KVPR_DEBUG_POISON = 1, 2
 KVPR_ARCH_OPT, KVPR_ARCH_LLAMA = 0, 1
+KVPR_ATTENTION_STATIC_SCRATCH_BYTES = 2 << 20
 
 
 class kvpr_model_desc(C.Structure):
@@ -93,6 +94,7 @@ _SIGS = {
     "kvpr_recompute_gemm": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp]),
     "kvpr_decode_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "kvpr_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
+    "kvpr_decode_attention_static": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "kvpr_decode_attention_mixed": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "kvpr_token_gemm": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
     "kvpr_rope_table": (_i, [_vp, _i, _i, C.c_double]),
@@ -292,6 +294,10 @@ def kvpr_attention_workspace_bytes(batch, hidden, n_heads, S) -> int:
 
 def kvpr_decode_attention(q_dev, kv_dev, z_dev, ws_dev, S, batch, hidden, n_heads, stream=None):
     _check(lib.kvpr_decode_attention(_ptr(q_dev), _ptr(kv_dev), _ptr(z_dev), _ptr(ws_dev), S, batch, hidden, n_heads, _stream(stream)))
+
+
+def kvpr_decode_attention_static(q_dev, kv_dev, z_dev, S, batch, hidden, n_heads, stream=None):
+    _check(lib.kvpr_decode_attention_static(_ptr(q_dev), _ptr(kv_dev), _ptr(z_dev), S, batch, hidden, n_heads, _stream(stream)))
 
 
 def kvpr_token_gemm(x_dev, w_dev, bias_dev, y32_dev, y16_dev, M, N, K, out_f32_cols, ld16, stream=None):

@@ -26,6 +26,7 @@
 // expanded in HBM.  One combine kernel merges all partials.
 #include "kvpr_internal.h"
 #include <math.h>
+#include <mutex>
 
 namespace kvpr {
 namespace {
@@ -343,14 +344,24 @@ size_t attention_workspace_bytes(int batch, int hidden, int n_heads, int S) {
     return (size_t)(splits * batch * (int64_t)hidden * 4 + splits * batch * (int64_t)(hidden / 8) * 8);
 }
 
-int launch_attention(const void* q, const void* kv, void* z, void* ws, int S, int batch, int hidden, int n_heads,
-                     hipStream_t st) {
-    const int d = hidden / n_heads;
+namespace {
+
+// the split choice launch_attention makes, with the workspace bound applied
+SplitPlan attention_plan(int batch, int hidden, int S) {
     SplitPlan sp = plan_splits(batch, hidden, S);
     if (sp.splits > 512) {                            // workspace bound above
         sp.chunk = (S + 511) / 512;
         sp.splits = (S + sp.chunk - 1) / sp.chunk;
     }
+    return sp;
+}
+
+}  // namespace
+
+int launch_attention(const void* q, const void* kv, void* z, void* ws, int S, int batch, int hidden, int n_heads,
+                     hipStream_t st) {
+    const int d = hidden / n_heads;
+    const SplitPlan sp = attention_plan(batch, hidden, S);
     const int groups = (hidden + COLS_PER_GROUP - 1) / COLS_PER_GROUP;
     float* ws_acc = (float*)ws;
     float* ws_ml = ws_acc + (int64_t)sp.splits * batch * hidden;
@@ -449,6 +460,52 @@ int launch_attention_mixed(const void* q, const void* kv16, const void* kvq, voi
 }
 
 }  // namespace kvpr
+
+// ---- decode attention for callers that cannot allocate ----
+// The partial results of a launch that splits the positions across workgroups live in a file-scope device array
+// instead of a caller workspace.  Every GPU holds its own copy of the array at its own address; the address is
+// looked up once per device (with that device current) and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[KVPR_ATTENTION_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int scratch_for_current_device(void** out) {
+    int dev = -1;
+    KVPR_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return kvpr::fail(KVPR_E_RANGE, "device %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        KVPR_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return kvpr::fail(KVPR_E_HIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return KVPR_OK;
+}
+
+}  // namespace
+
+extern "C" int kvpr_decode_attention_static(const void* q, const void* kv, void* z, int S, int batch, int hidden,
+                                            int n_heads, void* stream) {
+    if (S < 1 || batch < 1 || n_heads < 1) return kvpr::fail(KVPR_E_RANGE, "S=%d batch=%d n_heads=%d out of range", S, batch, n_heads);
+    if (hidden % n_heads || (hidden / n_heads != 64 && hidden / n_heads != 128))
+        return kvpr::fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
+    if (!q || !kv || !z) return kvpr::fail(KVPR_E_INVAL, "q / kv / z is null");
+    // what this launch would keep in the workspace: (acc[h] float32 + (m, l) per 8 columns) per split and sequence
+    const kvpr::SplitPlan sp = kvpr::attention_plan(batch, hidden, S);
+    const int64_t need = sp.splits > 1 ? (int64_t)sp.splits * batch * ((int64_t)hidden * 4 + (int64_t)(hidden / 8) * 8) : 0;
+    if (need > (int64_t)KVPR_ATTENTION_STATIC_SCRATCH_BYTES)
+        return kvpr::fail(KVPR_E_RANGE, "this shape needs %lld bytes of partial results, the static scratch holds %lld: use "
+                          "kvpr_decode_attention with a workspace", (long long)need, (long long)KVPR_ATTENTION_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (int rc = scratch_for_current_device(&ws)) return rc;
+    return kvpr::launch_attention(q, kv, z, ws, S, batch, hidden, n_heads, (hipStream_t)stream);
+}
 
 extern "C" int kvpr_debug_set_attention_kernel(int v) {
     kvpr::g_attn_cfg = v;
