@@ -153,6 +153,12 @@ typedef struct {
                             rows and the new row, issued while the cache copy is still in flight (always with
                             KVPR_KV_INT4, whose transferred rows are then read in packed form; with a float16
                             cache only in kvpr_layer_decode[_timed] at split >= 128); 0 when one launch did it all */
+    float ms_recompute_start; /* first enqueue -> the recompute GEMM may begin (its fences have passed)           */
+    float ms_weights_landed;  /* column schedule, first batch of a layer: first enqueue of this slot -> the layer's
+                                 whole weight blob has landed (negative: it had landed before); valid only when
+                                 weights_landed_valid != 0.  ms_recompute_start < ms_weights_landed shows the
+                                 recomputation running while Wq / Wo / FFN weights are still on the link */
+    int32_t weights_landed_valid;
 } kvpr_layer_timing;
 
 const char* kvpr_last_error(void);
@@ -292,7 +298,8 @@ int kvpr_greedy_next(const void* hidden_dev, const void* w_lm_dev, const void* e
 /* ---- individual kernels, exposed for parity tests and roofline measurement ---- */
 
 /* C[M, N] (row stride ldc halfs) = A[M, K] . W[N, K]^T + bias[N]   (Eq. 7 when W = [Wk^T ; Wv^T]).
- * float16 in, float32 accumulate on MFMA, float16 out.  K % 64 == 0, N % 8 == 0, ldc >= N, ldc % 4 == 0.
+ * float16 in, float32 accumulate on MFMA, float16 out.  K % 64 == 0, N % 8 == 0, ldc >= N, ldc % 8 == 0
+ * (rows are written in 16-byte pieces; c_dev 16-byte aligned).
  * bias may be null.  M == 0 is a no-op.  stream is a hipStream_t. */
 int kvpr_recompute_gemm(const void* a_dev, const void* w_dev, const void* bias_dev, void* c_dev,
                         int64_t M, int N, int K, int64_t ldc, void* stream);

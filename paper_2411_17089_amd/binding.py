@@ -45,7 +45,9 @@ class kvpr_layer_weights(C.Structure):
 class kvpr_layer_timing(C.Structure):
     _fields_ = [(n, C.c_float) for n in
                 ("ms_act_copy", "ms_kv_copy", "ms_recompute", "ms_proj", "ms_attn", "ms_out", "ms_store",
-                 "ms_assemble", "ms_total")] + [("t_bound_s", C.c_double), ("split", C.c_int32), ("ms_attn_early", C.c_float)]
+                 "ms_assemble", "ms_total")] + [("t_bound_s", C.c_double), ("split", C.c_int32), ("ms_attn_early", C.c_float),
+                                     ("ms_recompute_start", C.c_float), ("ms_weights_landed", C.c_float),
+                                     ("weights_landed_valid", C.c_int32)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -11,10 +11,11 @@ typedef _Float16 half;
 
 // events bracketing each category of one layer (timing enabled)
 struct LayerEvents {
-    hipEvent_t start, c0, c_x, c_kv, p0, p1, r0, r1, e0, e1, a0, a1, o1, s0, s1, end;   // e0..e1: early attention phase
+    // e0..e1: early attention phase; w_all: the layer's whole weight blob has landed (offloaded weights only)
+    enum Id { start, c0, c_x, c_kv, p0, p1, r0, r1, e0, e1, a0, a1, o1, s0, s1, end, w_all, count };
+    hipEvent_t at[count]{};
     int seq = -1, split = -1;            // what the slot last recorded
-    hipEvent_t* all() { return &start; }
-    static constexpr int count = 16;
+    bool has_w_all = false;              // w_all was recorded for the step being timed
 };
 
 }  // namespace kvpr
@@ -60,6 +61,8 @@ struct kvpr_ctx {
     std::vector<bool> w_written;
     int slots() const { return nb > 0 ? d.n_layers * nb : d.n_layers; }
     bool free_recorded[2] = {false, false};
+    hipEvent_t ev_buf_store[2]{};        // per device buffer: "the last store-back that read a row of this buffer is done"
+    bool buf_store_recorded[2] = {false, false};
     std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
     kvpr_profile_t prof{};
     bool have_prof = false;

@@ -56,7 +56,7 @@ int debug_sync(kvpr_ctx* c) {
 int ensure_timing_events(kvpr_ctx* c, int slots) {
     while ((int)c->tev.size() < slots) {
         LayerEvents le{};
-        for (int i = 0; i < LayerEvents::count; ++i) KVPR_HIP(hipEventCreate(&le.all()[i]));
+        for (int i = 0; i < LayerEvents::count; ++i) KVPR_HIP(hipEventCreate(&le.at[i]));
         c->tev.push_back(le);
     }
     return KVPR_OK;
@@ -101,7 +101,7 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     if (!ev && c->adapt_alpha > 0.0 && c->have_prof) {
         if (!c->probe_made) {
             for (auto& le : c->probe)
-                for (int i = 0; i < LayerEvents::count; ++i) KVPR_HIP(hipEventCreate(&le.all()[i]));
+                for (int i = 0; i < LayerEvents::count; ++i) KVPR_HIP(hipEventCreate(&le.at[i]));
             c->probe_made = true;
         }
         if (!c->probe_pending[c->probe_next]) {
@@ -114,7 +114,7 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     if (ev) {
         ev->seq = seq;
         ev->split = l;
-        KVPR_HIP(hipEventRecord(ev->start, c->compute));
+        KVPR_HIP(hipEventRecord(ev->at[LayerEvents::start], c->compute));
     }
     if (c->debug & KVPR_DEBUG_POISON) {
         if (int rc = kvpr::launch_fill_u16(dkv, (size_t)(seq + 1) * kr, 0x7E00, c->compute)) return rc;
@@ -130,9 +130,11 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
 
     // ---- copy stream: activations first, then the rest of the cache (the order Eq. 10 assumes) ----
     if (c->free_recorded[buf]) KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_free[buf], 0));
+    // ... and the previous user's store-back, which reads its new row out of this device buffer
+    if (c->buf_store_recorded[buf]) KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_buf_store[buf], 0));
     // the previous token's store-back wrote host row seq-1 of this slot, which the copies below may read
     if (c->slot_store_recorded[layer]) KVPR_HIP(hipStreamWaitEvent(c->copy, c->ev_slot_store[layer], 0));
-    if (ev) KVPR_HIP(hipEventRecord(ev->c0, c->copy));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::c0], c->copy));
     // chunk boundaries: equal parts of [0, l) rounded down to multiples of 8 positions (whole GEMM tile rows
     // at batch 32); a single chunk is the paper's schedule
     int nchunk = (l > 0) ? std::min(c->chunks, std::max(1, l / 8)) : 0;
@@ -145,18 +147,18 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
         if (nchunk > 1) KVPR_HIP(hipEventRecord(c->ev_chunk[buf][j], c->copy));
     }
     KVPR_HIP(hipEventRecord(c->ev_x[buf], c->copy));
-    if (ev) KVPR_HIP(hipEventRecord(ev->c_x, c->copy));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::c_x], c->copy));
     if (l < seq)
         KVPR_HIP(hipMemcpyAsync(kv_stage + (size_t)l * ksb, c->hkv[layer] + (size_t)l * ksb, (size_t)(seq - l) * ksb,
                                 hipMemcpyHostToDevice, c->copy));
     KVPR_HIP(hipEventRecord(c->ev_kv[buf], c->copy));
-    if (ev) KVPR_HIP(hipEventRecord(ev->c_kv, c->copy));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::c_kv], c->copy));
     if (int rc = debug_sync(c)) return rc;
 
     // ---- new token's q (float32) and k|v row `seq` of the device cache (Eq. 1, Eq. 5), then the store-back ----
     auto project_and_store = [&]() -> int {
         if (wf) KVPR_HIP(hipStreamWaitEvent(c->compute, wf->all_ready, 0));
-        if (ev) KVPR_HIP(hipEventRecord(ev->p0, c->compute));
+        if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::p0], c->compute));
         if (c->llama) {
             // q and k stay float32 until they are rotated with position seq; v goes straight into the cache row
             if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->qk32, dkv + (size_t)seq * kr + h, b, 3 * h, h,
@@ -175,10 +177,10 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
         if (c->qx)
             if (int rc = kvpr::launch_quant_int4(x_new, x_stage + (size_t)seq * xsb, b, h, c->compute)) return rc;
         KVPR_HIP(hipEventRecord(c->ev_proj, c->compute));
-        if (ev) KVPR_HIP(hipEventRecord(ev->p1, c->compute));
+        if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::p1], c->compute));
         // store stream: write the new rows back to the host store
         KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_proj, 0));
-        if (ev) KVPR_HIP(hipEventRecord(ev->s0, c->store));
+        if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::s0], c->store));
         KVPR_HIP(hipMemcpyAsync(c->hkv[layer] + (size_t)seq * ksb, kv_stage + (size_t)seq * ksb, ksb, hipMemcpyDeviceToHost,
                                 c->store));
         KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xsb, c->qx ? (const void*)(x_stage + (size_t)seq * xsb) : (const void*)x_new,
@@ -186,14 +188,16 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
         KVPR_HIP(hipEventRecord(c->ev_store, c->store));
         KVPR_HIP(hipEventRecord(c->ev_slot_store[layer], c->store));
         c->slot_store_recorded[layer] = true;
-        if (ev) KVPR_HIP(hipEventRecord(ev->s1, c->store));
+        KVPR_HIP(hipEventRecord(c->ev_buf_store[buf], c->store));
+        c->buf_store_recorded[buf] = true;
+        if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::s1], c->store));
         return debug_sync(c);
     };
     // ---- recompute rows [0, l) as soon as their activations have landed (Eq. 7) ----
     auto recompute = [&]() -> int {
         if (wf) KVPR_HIP(hipStreamWaitEvent(c->compute, wf->kv_ready, 0));
         if (nchunk <= 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_x[buf], 0));
-        if (ev) KVPR_HIP(hipEventRecord(ev->r0, c->compute));
+        if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::r0], c->compute));
         if (l > 0) {
             const half* wkv = (const half*)w->wqkv + (size_t)h * h;
             const half* bkv = w->bqkv ? (const half*)w->bqkv + h : nullptr;
@@ -213,7 +217,7 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
                     return rc;
             }
         }
-        if (ev) KVPR_HIP(hipEventRecord(ev->r1, c->compute));
+        if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::r1], c->compute));
         return debug_sync(c);
     };
     if (wf) {
@@ -235,26 +239,26 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     // attention is off the critical path and stays one launch.)
     const bool two_phase = c->qkv || (fence_copy_to_start && l >= 128);
     const void* packed = c->qkv ? kv_stage : nullptr;
-    if (ev) KVPR_HIP(hipEventRecord(ev->e0, c->compute));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::e0], c->compute));
     if (two_phase)
         if (int rc = kvpr::launch_attention_mixed(c->q32, dkv, packed, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 0, c->compute))
             return rc;
-    if (ev) KVPR_HIP(hipEventRecord(ev->e1, c->compute));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::e1], c->compute));
     KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_kv[buf], 0));
-    if (ev) KVPR_HIP(hipEventRecord(ev->a0, c->compute));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::a0], c->compute));
     if (int rc = two_phase ? kvpr::launch_attention_mixed(c->q32, dkv, packed, c->z16, c->attn_ws, seq + 1, l, b, h, c->d.n_heads, 1, c->compute)
                            : kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, seq + 1, b, h, c->d.n_heads, c->compute))
         return rc;
     KVPR_HIP(hipEventRecord(c->ev_free[buf], c->compute));
     c->free_recorded[buf] = true;
-    if (ev) KVPR_HIP(hipEventRecord(ev->a1, c->compute));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::a1], c->compute));
 
     // ---- output projection (Eq. 3) ----
     if (int rc = kvpr::launch_token_gemm_flags(c->z16, w->wo, w->bo, nullptr, out, b, h, h, 0, h, 0, c->compute))
         return rc;
-    if (ev) KVPR_HIP(hipEventRecord(ev->o1, c->compute));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::o1], c->compute));
     KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_store, 0));
-    if (ev) KVPR_HIP(hipEventRecord(ev->end, c->compute));
+    if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::end], c->compute));
     if (int rc = debug_sync(c)) return rc;
 
     if (c->x_rows[layer] == seq) c->x_rows[layer] = seq + 1;
@@ -269,14 +273,14 @@ int adapt_poll(kvpr_ctx* c) {
     for (int i = 0; i < kvpr_ctx::kProbes; ++i) {
         if (!c->probe_pending[i]) continue;
         LayerEvents* ev = &c->probe[i];
-        const hipError_t q1 = hipEventQuery(ev->end), q2 = hipEventQuery(ev->c_kv);
+        const hipError_t q1 = hipEventQuery(ev->at[LayerEvents::end]), q2 = hipEventQuery(ev->at[LayerEvents::c_kv]);
         if (q1 == hipErrorNotReady || q2 == hipErrorNotReady) continue;
         if (q1 != hipSuccess || q2 != hipSuccess) return fail(KVPR_E_HIP, "probe event query failed");
         c->probe_pending[i] = false;
         float ms_x = 0.f, ms_kv = 0.f, ms_rc = 0.f;
-        KVPR_HIP(hipEventElapsedTime(&ms_x, ev->c0, ev->c_x));
-        KVPR_HIP(hipEventElapsedTime(&ms_kv, ev->c_x, ev->c_kv));
-        KVPR_HIP(hipEventElapsedTime(&ms_rc, ev->r0, ev->r1));
+        KVPR_HIP(hipEventElapsedTime(&ms_x, ev->at[LayerEvents::c0], ev->at[LayerEvents::c_x]));
+        KVPR_HIP(hipEventElapsedTime(&ms_kv, ev->at[LayerEvents::c_x], ev->at[LayerEvents::c_kv]));
+        KVPR_HIP(hipEventElapsedTime(&ms_rc, ev->at[LayerEvents::r0], ev->at[LayerEvents::r1]));
         const int64_t l = ev->split, s = ev->seq;
         const int64_t link_bytes = (int64_t)c->x_store_bytes() * l + (int64_t)c->kv_store_bytes() * (s - l);
         // with a chunked activation copy the GEMM interval includes waiting for chunks: the link sample only
@@ -296,23 +300,28 @@ int read_timing(kvpr_ctx* c, LayerEvents* ev, int seq, int l, kvpr_layer_timing*
         return KVPR_OK;
     };
     kvpr_layer_timing r{};
-    float to_gemm = 0.f, to_kv = 0.f, to_deq = 0.f;
-    if (int rc = ms(ev->c0, ev->c_x, &r.ms_act_copy)) return rc;
-    if (int rc = ms(ev->c_x, ev->c_kv, &r.ms_kv_copy)) return rc;
-    if (int rc = ms(ev->r0, ev->r1, &r.ms_recompute)) return rc;
-    if (int rc = ms(ev->p0, ev->p1, &r.ms_proj)) return rc;
-    if (int rc = ms(ev->a0, ev->a1, &r.ms_attn)) return rc;
-    if (int rc = ms(ev->a1, ev->o1, &r.ms_out)) return rc;
-    if (int rc = ms(ev->s0, ev->s1, &r.ms_store)) return rc;
-    if (int rc = ms(ev->start, ev->r1, &to_gemm)) return rc;
-    if (int rc = ms(ev->start, ev->c_kv, &to_kv)) return rc;
-    if (int rc = ms(ev->start, ev->end, &r.ms_total)) return rc;
+    float to_gemm = 0.f, to_kv = 0.f;
+    if (int rc = ms(ev->at[LayerEvents::c0], ev->at[LayerEvents::c_x], &r.ms_act_copy)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::c_x], ev->at[LayerEvents::c_kv], &r.ms_kv_copy)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::r0], ev->at[LayerEvents::r1], &r.ms_recompute)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::p0], ev->at[LayerEvents::p1], &r.ms_proj)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::a0], ev->at[LayerEvents::a1], &r.ms_attn)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::a1], ev->at[LayerEvents::o1], &r.ms_out)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::s0], ev->at[LayerEvents::s1], &r.ms_store)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::start], ev->at[LayerEvents::r1], &to_gemm)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::start], ev->at[LayerEvents::c_kv], &to_kv)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::start], ev->at[LayerEvents::end], &r.ms_total)) return rc;
     // attention = the phase before the cache fence (empty unless it ran in two phases) + the phase after it
     float ms_early = 0.f;
-    if (int rc = ms(ev->e0, ev->e1, &ms_early)) return rc;
+    if (int rc = ms(ev->at[LayerEvents::e0], ev->at[LayerEvents::e1], &ms_early)) return rc;
     r.ms_attn += ms_early;
     r.ms_attn_early = ms_early;
-    (void)to_deq;
+    if (int rc = ms(ev->at[LayerEvents::start], ev->at[LayerEvents::r0], &r.ms_recompute_start)) return rc;
+    if (ev->has_w_all) {
+        if (int rc = ms(ev->at[LayerEvents::start], ev->at[LayerEvents::w_all], &r.ms_weights_landed)) return rc;
+        r.weights_landed_valid = 1;
+        ev->has_w_all = false;
+    }
     r.ms_assemble = std::max(to_gemm, to_kv);
     r.split = l;
     if (c->have_prof)
@@ -357,6 +366,7 @@ void destroy_impl(kvpr_ctx* c) {
         if (c->ev_x[i]) (void)hipEventDestroy(c->ev_x[i]);
         if (c->ev_kv[i]) (void)hipEventDestroy(c->ev_kv[i]);
         if (c->ev_free[i]) (void)hipEventDestroy(c->ev_free[i]);
+        if (c->ev_buf_store[i]) (void)hipEventDestroy(c->ev_buf_store[i]);
         for (hipEvent_t e : c->ev_chunk[i]) if (e) (void)hipEventDestroy(e);
     }
     if (c->wstream) (void)hipStreamSynchronize(c->wstream);
@@ -371,10 +381,10 @@ void destroy_impl(kvpr_ctx* c) {
     hipEvent_t evs[] = {c->ev_proj, c->ev_store, c->ev_begin};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
     for (auto& le : c->tev)
-        for (int i = 0; i < LayerEvents::count; ++i) (void)hipEventDestroy(le.all()[i]);
+        for (int i = 0; i < LayerEvents::count; ++i) (void)hipEventDestroy(le.at[i]);
     if (c->probe_made)
         for (auto& le : c->probe)
-            for (int i = 0; i < LayerEvents::count; ++i) (void)hipEventDestroy(le.all()[i]);
+            for (int i = 0; i < LayerEvents::count; ++i) (void)hipEventDestroy(le.at[i]);
     if (c->copy) (void)hipStreamDestroy(c->copy);
     if (c->store) (void)hipStreamDestroy(c->store);
     delete c;
@@ -387,8 +397,9 @@ extern "C" const char* kvpr_last_error(void) { return kvpr::g_err; }
 namespace {
 
 // element offsets (in halfs) of one layer's parameters inside a weight blob; the host (pinned) and
-// device blobs share the layout so that a range of the blob is one contiguous copy.  [Wk;Wv] and
-// the q|k|v bias come right after Wq: the range [wkv, wo) is what the recomputation needs.
+// device blobs share the layout so that a range of the blob is one contiguous copy.  [Wk;Wv], the
+// q|k|v bias and the parameters of the norm in front of the attention block come right after Wq: the
+// range [wkv, wo) is all that the pre-attention norm and the recomputation need.
 struct BlobLayout {
     size_t wq, wkv, bqkv, wo, bo, ln1_g, ln1_b, ln2_g, ln2_b, w1, b1, w2, b2, total;
     BlobLayout(size_t h, size_t f, bool gated) {
@@ -397,9 +408,10 @@ struct BlobLayout {
         wq = take(h * h);          // rows [0, h) of wqkv
         wkv = take(2 * h * h);     // rows [h, 3h): contiguous with wq because h*h is a multiple of 64
         bqkv = take(3 * h);
+        ln1_g = take(h); ln1_b = take(h);
         wo = take(h * h);
         bo = take(h);
-        ln1_g = take(h); ln1_b = take(h); ln2_g = take(h); ln2_b = take(h);
+        ln2_g = take(h); ln2_b = take(h);
         w1 = take((gated ? 2 : 1) * f * h); b1 = take(f);   // gated FFN: [gate; up] stacked
         w2 = take(h * f); b2 = take(h);
         total = o;
@@ -490,6 +502,7 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
         if ((e = hipEventCreateWithFlags(&c->ev_x[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
         if ((e = hipEventCreateWithFlags(&c->ev_kv[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
         if ((e = hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+        if ((e = hipEventCreateWithFlags(&c->ev_buf_store[i], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
         for (int j = 0; j < kvpr_ctx::kMaxChunks; ++j)
             if ((e = hipEventCreateWithFlags(&c->ev_chunk[i][j], hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
     }
@@ -635,9 +648,9 @@ extern "C" int kvpr_timing_read(kvpr_ctx* c, int slot, kvpr_layer_timing* timing
     if (slot < 0 || slot >= (int)c->tev.size() || c->tev[slot].seq < 0)
         return fail(KVPR_E_STATE, "timing slot %d holds no recording", slot);
     LayerEvents* ev = &c->tev[slot];
-    KVPR_HIP(hipEventSynchronize(ev->end));
-    KVPR_HIP(hipEventSynchronize(ev->c_kv));
-    KVPR_HIP(hipEventSynchronize(ev->s1));
+    KVPR_HIP(hipEventSynchronize(ev->at[LayerEvents::end]));
+    KVPR_HIP(hipEventSynchronize(ev->at[LayerEvents::c_kv]));
+    KVPR_HIP(hipEventSynchronize(ev->at[LayerEvents::s1]));
     return read_timing(c, ev, ev->seq, ev->split, timing);
 }
 
@@ -770,7 +783,7 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
         if (int rc = ensure_timing_events(c, S)) return rc;
     const BlobLayout BL(h, f, c->llama);
     const size_t bh = (size_t)b * h;
-    const size_t kv_part = (BL.wo - BL.wkv) * sizeof(half);       // [Wk;Wv] rows and the q|k|v bias
+    const size_t kv_part = (BL.wo - BL.wkv) * sizeof(half);       // [Wk;Wv] rows, the q|k|v bias, the first norm's parameters
     // weights of layer j into device blob j % 2: the part the recomputation needs first (fine-grained MHA
     // pipeline, Sec. 3.3), then Wq and everything else
     auto load_weights = [&](int j) -> int {
@@ -781,6 +794,11 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
         KVPR_HIP(hipMemcpyAsync(c->dw[wb] + BL.wq, c->hw[j] + BL.wq, (BL.wkv - BL.wq) * sizeof(half), hipMemcpyHostToDevice, c->wstream));
         KVPR_HIP(hipMemcpyAsync(c->dw[wb] + BL.wo, c->hw[j] + BL.wo, (BL.total - BL.wo) * sizeof(half), hipMemcpyHostToDevice, c->wstream));
         KVPR_HIP(hipEventRecord(c->ev_wall[wb], c->wstream));
+        if (per_slot) {                                           // timing: when the whole layer had landed
+            LayerEvents& le = c->tev[(size_t)j * nb];
+            KVPR_HIP(hipEventRecord(le.at[LayerEvents::w_all], c->wstream));
+            le.has_w_all = true;
+        }
         return KVPR_OK;
     };
     if (int rc = load_weights(0)) return rc;
@@ -794,8 +812,9 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
             const int slot = j * nb + k;
             const half* hid_in = (j == 0) ? (const half*)x_in_dev + (size_t)k * bh : c->hid_all + (size_t)k * bh;
             half* hid_out = (j == L - 1) ? (half*)x_out_dev + (size_t)k * bh : c->hid_all + (size_t)k * bh;
-            // LayerNorm parameters arrive with the second part of the blob
-            KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_wall[wb], 0));
+            // the norm's parameters arrive with [Wk;Wv]: neither the norm nor the recomputation that follows it
+            // waits for Wq, Wo and the FFN matrices, which may still be on the link (Sec. 3.3 fine-grained MHA pipeline)
+            KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_wkv[wb], 0));
             if (int rc = pre_attention_norm(c, &w, hid_in)) return rc;
             if (int rc = enqueue_layer(c, slot, seq, ls[slot], &w, c->xn, c->attn_out, slot % c->nbuf,
                                        per_slot ? &c->tev[slot] : nullptr, false, &wf))

@@ -163,8 +163,6 @@ int launch_mt(const void* x, const void* w, const void* bias, void* y32, void* y
 
 }  // namespace
 
-size_t token_gemm_workspace_bytes(int, int, int) { return 0; }
-
 // flags bit 0: ReLU
 int launch_token_gemm_flags(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
                             int out_f32_cols, int64_t ld16, int flags, hipStream_t st) {
@@ -173,11 +171,6 @@ int launch_token_gemm_flags(const void* x, const void* w, const void* bias, void
     if (M <= 32) return launch_mt<2>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
     if (M <= 48) return launch_mt<3>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
     return launch_mt<4>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-}
-
-int launch_token_gemm(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
-                      int out_f32_cols, int64_t ld16, void*, hipStream_t st) {
-    return launch_token_gemm_flags(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, 0, st);
 }
 
 }  // namespace kvpr

@@ -8,7 +8,7 @@ using kvpr::fail;
 extern "C" int kvpr_recompute_gemm(const void* a, const void* w, const void* bias, void* cdev, int64_t M, int N, int K,
                                    int64_t ldc, void* stream) {
     if (M < 0 || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%lld N=%d K=%d out of range", (long long)M, N, K);
-    if (K % 64 || N % 8 || ldc < N || ldc % 4) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 4 == 0");
+    if (K % 64 || N % 8 || ldc < N || ldc % 8) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 8 == 0 (16-byte row pieces)");
     if (M == 0) return KVPR_OK;
     if (!a || !w || !cdev) return fail(KVPR_E_INVAL, "a / w / c is null");
     return kvpr::launch_gemm(a, w, bias, cdev, M, N, K, ldc, (hipStream_t)stream);
@@ -69,7 +69,7 @@ extern "C" int kvpr_recompute_gemm_rope(const void* a, const void* w, const void
                                         int64_t ldc, const void* table_dev, int n_pos, int rope_cols, int head_dim, int batch,
                                         int pos0, void* stream) {
     if (M < 0 || M >= ((int64_t)1 << 31) || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%lld N=%d K=%d out of range", (long long)M, N, K);
-    if (K % 64 || N % 8 || ldc < N || ldc % 4) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 4 == 0");
+    if (K % 64 || N % 8 || ldc < N || ldc % 8) return fail(KVPR_E_INVAL, "need K %% 64 == 0, N %% 8 == 0, ldc >= N, ldc %% 8 == 0 (16-byte row pieces)");
     if (head_dim != 64 && head_dim != 128) return fail(KVPR_E_INVAL, "head_dim must be 64 or 128");
     if (rope_cols < 0 || rope_cols > N || rope_cols % 128) return fail(KVPR_E_INVAL, "rope_cols must be a multiple of 128 in [0, N]");
     if (batch < 1 || pos0 < 0 || n_pos < 1) return fail(KVPR_E_RANGE, "batch=%d pos0=%d n_pos=%d out of range", batch, pos0, n_pos);

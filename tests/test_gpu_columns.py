@@ -91,6 +91,29 @@ def test_columns_match_oracle(k, n_layers, nb, b, s, h, H, ffn):
         st.close()
 
 
+def test_recompute_runs_while_the_rest_of_the_layer_is_on_the_link(k):
+    """Fine-grained MHA pipeline (Sec. 3.3, Table 2): [Wk;Wv] travel first, and the recomputation of the first batch of
+    a layer is released by them alone.  With 10 h^2 further weights (Wq, Wo, FFN: 84 MB here) behind them on the link,
+    the recompute GEMM must begin, by the events' own timestamps, before the layer's weights have all landed."""
+    n_layers, nb, b, s, h, H, ffn = 2, 1, 8, 256, 2048, 16, 8192
+    st = Columns(k, n_layers, nb, b, s, h, H, ffn, seed0=500)
+    try:
+        splits = [s, s]
+        for rep in range(2):                                   # the first pass also pays one-time kernel loading
+            print(f"fine-grained pipeline pass {rep}", flush=True)
+            _, tim = k.kvpr_decode_step_columns(st.ctx, s, n_layers * nb, dev(st.x_in), st.x_out, splits, timing=True)
+            torch.cuda.synchronize()
+        t0 = tim[0]
+        print("layer 0: recompute starts at %.3f ms, ends at %.3f ms, weights landed at %.3f ms" %
+              (t0.ms_recompute_start, t0.ms_recompute_start + t0.ms_recompute, t0.ms_weights_landed), flush=True)
+        assert all(t.weights_landed_valid for t in tim)
+        assert t0.ms_recompute > 0
+        assert t0.ms_recompute_start < t0.ms_weights_landed
+        assert rel_err(st.x_out.cpu().numpy(), st.oracle(splits)) <= 5e-3
+    finally:
+        st.close()
+
+
 def test_columns_debug_modes_timing_and_errors(k):
     st = Columns(k, 3, 2, 4, 48, 256, 2, 1024)
     try:
