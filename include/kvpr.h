@@ -22,7 +22,9 @@
  *     timing struct is requested or the text says "synchronises".
  *   - A context must be used from one host thread at a time.
  *   - The library also exports a few symbols whose names start with kvpr_debug_: hooks that tests and
- *     tuning sweeps use to force a kernel variant.  They are not part of this interface.
+ *     tuning sweeps use to force a kernel variant.  They are not part of this interface.  They set
+ *     process-wide variables without any synchronisation: call them from one thread, while no other
+ *     thread is inside the library.
  *   - dtype is IEEE float16 for all tensors; accumulation is float32.
  *
  * Layouts (token-major, row-major, innermost index contiguous)

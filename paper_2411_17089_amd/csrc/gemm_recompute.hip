@@ -5,18 +5,23 @@
 //
 // Design (MI355X):
 //  * One workgroup owns a BM x BN tile of C (256 x 256 by default, 8 waves as 4 x 2) and walks K in
-//    stages of 32.  A stage is (BM + BN) rows of 64 bytes in LDS; NSTAGE = 4 stages form a ring.
-//  * Stages are filled by direct global->LDS DMA (global_load_lds_dwordx4): no staging registers, no
-//    ds_write.  A wave-load covers 16 rows x 64 B; the 16-byte chunks of a row are XOR-swizzled by
-//    (row/4)%4 on the global-address side so that the ds_read_b128 of 16 consecutive rows touches 16
-//    different bank groups (measured: SQ_LDS_BANK_CONFLICT = 0).
-//  * The loop is software-pipelined by hand: the workgroup barrier sits between two MFMA groups, each
-//    group covers the LDS latency of the next operand fragments and the issue of the refill DMA, and
-//    the wait before the barrier is a counted vmcnt (the NSTAGE-2 younger stages stay in flight).
+//    stages of 64: one whole 128-byte line of every operand row.  A stage is two blocks in LDS (the A
+//    rows and the W rows, 32 KiB each); five blocks form a ring that fills the 160 KiB of LDS.
+//  * Blocks are filled by direct global->LDS DMA (global_load_lds_dwordx4): no staging registers, no
+//    ds_write.  An instruction covers 8 rows x 128 B.  What limits this kernel is that path: measured
+//    alone it delivers 40 B/clk/CU with 64-byte row pieces, 50 with 128-byte ones and 56 with 256-byte
+//    ones, against the 32 B/clk/CU that a 256 x 256 tile consumes at the full MFMA rate; with the DMA
+//    taken out of the loop the same schedule runs 25 % faster.  Whole lines per row is what moved it.
+//  * The 16-byte chunks of a row are XOR-swizzled by (row/2)%8 on the global-address side so that the
+//    ds_read_b128 of 16 consecutive rows touches 16 different bank groups.
+//  * The loop is software-pipelined by hand: per stage four groups of MFMAs, each covering the LDS
+//    latency of the next operand fragments; one workgroup barrier per stage, placed before the last
+//    group; the wait in front of it is a counted vmcnt (the youngest block stays in flight).
 //  * v_mfma_f32_32x32x16_f16 is issued "transposed" (W rows feed the instruction's row operand, X
 //    rows its column operand) so a lane owns 4 consecutive output columns per accumulator quad.
 //  * Epilogue: bias + conversion in registers, C tile staged through LDS, global stores of whole
-//    512-byte row pieces (the direct 8-byte stores of the first version cost ~15 % of the kernel).
+//    512-byte row pieces.  Stores straight from registers (8-byte pieces, or 16-byte pieces after a
+//    v_permlane32_swap) cost 10-15 % of the kernel: 32 rows x 32 bytes per instruction is a poor write.
 //  * Workgroup ids are remapped so that the workgroups an XCD runs concurrently (ids equal mod 8)
 //    form a compact block of tiles sharing A/W panels in that XCD's L2.  Across XCDs there are two
 //    mappings: each XCD takes a contiguous share of the tile rows (W is re-read by all XCDs and lives in
@@ -29,6 +34,7 @@
 //    column and its partner at distance HD/2 sit in the same lane, two or one accumulator tiles
 //    apart.  cos/sin come from a float2 table [position][HD/2] (L1/L2 hits: a tile spans few positions).
 #include "kvpr_internal.h"
+#include <mutex>
 #include <type_traits>
 
 namespace kvpr {
@@ -40,14 +46,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
-constexpr int BK = 32;          // halfs per stage
-constexpr int ROW_BYTES = 64;   // one LDS row of a stage
+constexpr int BK = 64;           // halfs per stage: one 128-byte line per row
+constexpr int ROW_BYTES = 128;   // one LDS row of a block
+constexpr int NBLK = 5;          // ring of half-stage blocks (A rows or W rows of one stage)
 
 // rotary epilogue: table[pos * HD/2 + i] = (cos, sin)(pos * theta_i); columns [0, cols) of C are rotated
 struct RopeArgs {
     const float2* table;
     int cols, batch, pos0;
-    int xcd_split_n;     // tile -> workgroup mapping (not a rotary parameter; rides in the same argument block)
 };
 
 template <int VM, int LGKM0>
@@ -56,28 +62,24 @@ __device__ __forceinline__ void wait_counts() {
     __builtin_amdgcn_s_waitcnt((VM & 15) | ((VM >> 4) << 14) | 0x0070 | (LGKM0 ? 0 : 0x0F00));
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M, int HD>
+template <int BM, int BN, int WM, int WN, int GROUP_M, int HD>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     const _Float16* __restrict__ A, const _Float16* __restrict__ W, const _Float16* __restrict__ bias,
     _Float16* __restrict__ C, int64_t M, int N, int K, int64_t ldc, int tiles_m, int tiles_n, int tiles_per_xcd,
-    RopeArgs rope) {
+    int xcd_split_n, RopeArgs rope) {
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int BLOCKS = (BM + BN) / 16;
-    constexpr int LOADS = BLOCKS / NW;
-    static_assert(BLOCKS % NW == 0, "tile/waves mismatch");
-    static_assert(NSTAGE >= 3 && NSTAGE <= 4, "ring depth");
-    constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+    constexpr int LA = BM / 8 / NW, LW = BN / 8 / NW;     // DMA instructions per wave per block (8 rows x 128 B each)
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
+    constexpr int BLK_BYTES = (BM > BN ? BM : BN) * ROW_BYTES;
     constexpr int NMFMA = TM * TN, NFRAG = TM + TN;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int pid = blockIdx.x;
     int tile_m, tile_n;
-    if (rope.xcd_split_n) {
-        // every XCD owns a band of tile columns and all XCDs walk the tile rows together: the A panels in use are
-        // shared by the eight XCDs (one HBM fetch, then memory-side cache hits) and W can stay in that cache
+    if (xcd_split_n) {
         const int xcd = pid & 7, i = pid >> 3;
         const int n_lo = xcd * tiles_n / 8, width = (xcd + 1) * tiles_n / 8 - n_lo;
         if (i >= width * tiles_m) return;
@@ -107,46 +109,45 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // wave-load i of this wave fills stage rows [16*blk, 16*blk+16) (A rows first, then W rows); lane L
-    // lands at row 16*blk + L/4, physical chunk L%4, and therefore fetches logical chunk (L%4)^((row/4)%4)
-    const _Float16* src[LOADS];
+    // DMA: instruction i of this wave fills block rows [8*(wave + NW*i), +8); lane L lands at row 8*blk + L/8,
+    // physical 16-byte chunk L%8, and therefore fetches logical chunk (L%8) ^ ((row/2)%8): with 128-byte rows the
+    // ds_read_b128 of 16 consecutive rows then touches 16 different bank groups.
+    const _Float16* srca[LA];
+    const _Float16* srcw[LW];
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int blk = wave + i * NW;
-        const int row = blk * 16 + (lane >> 2);
-        const int pc = lane & 3;
-        if (blk * 16 < BM) {
-            int64_t gr = m0 + row;
-            if (gr > M - 1) gr = M - 1;
-            src[i] = A + gr * K + ((pc ^ ((row >> 2) & 3)) << 3);
-        } else {
-            const int wr = row - BM;
-            int gr = n0 + wr;
-            if (gr > N - 1) gr = N - 1;
-            src[i] = W + (int64_t)gr * K + ((pc ^ ((wr >> 2) & 3)) << 3);
-        }
+    for (int i = 0; i < LA; ++i) {
+        const int row = (wave + NW * i) * 8 + (lane >> 3);
+        int64_t gr = m0 + row;
+        if (gr > M - 1) gr = M - 1;
+        srca[i] = A + gr * K + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
     }
-    auto issue_loads = [&](int kt) {
-        unsigned char* base = lds + (kt % NSTAGE) * STAGE_BYTES + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src[i] + kt * BK), (lds_ptr_t)(base + i * NW * 1024), 16, 0, 0);
+    for (int i = 0; i < LW; ++i) {
+        const int row = (wave + NW * i) * 8 + (lane >> 3);
+        int gr = n0 + row;
+        if (gr > N - 1) gr = N - 1;
+        srcw[i] = W + (int64_t)gr * K + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+    }
+    auto issue_a = [&](int kt, int slot) {
+        unsigned char* base = lds + slot * BLK_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LA; ++i)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(srca[i] + kt * BK), (lds_ptr_t)(base + i * NW * 1024), 16, 0, 0);
     };
+    auto issue_w = [&](int kt, int slot) {
+        unsigned char* base = lds + slot * BLK_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LW; ++i)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(srcw[i] + kt * BK), (lds_ptr_t)(base + i * NW * 1024), 16, 0, 0);
+    };
+    auto inc = [](int s, int d) { s += d; return s >= NBLK ? s - NBLK : s; };
 
+    // fragment addresses: row r of a block, k-step kk (16 halfs = two 16-byte chunks, lane half picks one).  The
+    // swizzle term (r/2)%8 depends only on lane%32 because every wave / tile offset is a multiple of 32 rows.
     const int frow = lane & 31, fhalf = lane >> 5;
-    int a_off[TM][2], w_off[TN][2];
+    int koff[4];
 #pragma unroll
-    for (int t = 0; t < TM; ++t) {
-        const int r = wm * WTM + t * 32 + frow;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) a_off[t][kk] = r * ROW_BYTES + (((kk * 2 + fhalf) ^ ((r >> 2) & 3)) << 4);
-    }
-#pragma unroll
-    for (int t = 0; t < TN; ++t) {
-        const int r = wn * WTN + t * 32 + frow;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) w_off[t][kk] = BM * ROW_BYTES + r * ROW_BYTES + (((kk * 2 + fhalf) ^ ((r >> 2) & 3)) << 4);
-    }
+    for (int kk = 0; kk < 4; ++kk) koff[kk] = frow * ROW_BYTES + (((kk * 2 + fhalf) ^ ((frow >> 1) & 7)) << 4);
 
     floatx16 acc[TN][TM];
 #pragma unroll
@@ -157,12 +158,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     half8 af0[TM], wf0[TN], af1[TM], wf1[TN];
-    auto load_frags = [&](int kt, int kk, half8* af, half8* wf) {
-        const unsigned char* st = lds + (kt % NSTAGE) * STAGE_BYTES;
+    auto load_frags = [&](int sa, int sw, int kk, half8* af, half8* wf) {
+        const unsigned char* pa = lds + sa * BLK_BYTES + wm * WTM * ROW_BYTES + koff[kk];
+        const unsigned char* pw = lds + sw * BLK_BYTES + wn * WTN * ROW_BYTES + koff[kk];
 #pragma unroll
-        for (int t = 0; t < TM; ++t) af[t] = *reinterpret_cast<const half8*>(st + a_off[t][kk]);
+        for (int t = 0; t < TM; ++t) af[t] = *reinterpret_cast<const half8*>(pa + t * 32 * ROW_BYTES);
 #pragma unroll
-        for (int t = 0; t < TN; ++t) wf[t] = *reinterpret_cast<const half8*>(st + w_off[t][kk]);
+        for (int t = 0; t < TN; ++t) wf[t] = *reinterpret_cast<const half8*>(pw + t * 32 * ROW_BYTES);
     };
     auto mfma_group = [&](const half8* af, const half8* wf) {
 #pragma unroll
@@ -171,51 +173,76 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
             for (int j = 0; j < TM; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], af[j], acc[i][j], 0, 0, 0);
     };
-    const int KT = K / BK;
-#pragma unroll
-    for (int d = 0; d < NSTAGE; ++d)
-        if (d < KT) issue_loads(d);
-    if (KT >= NSTAGE) wait_counts<(NSTAGE - 1) * LOADS, 0>();
-    else wait_counts<0, 0>();
-    __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, af0, wf0);
-
-    // one ring step: consumes stage kt, leaves the fragments of k-step 0 of stage kt+1 in (af0, wf0)
-    auto step = [&](int kt, auto refill) {
-        // phase A: fetch the fragments of k-step 1 of this stage while the MFMAs of k-step 0 run
-        load_frags(kt, 1, af1, wf1);
-        mfma_group(af0, wf0);
+    auto interleave = [&](auto id) {
+        constexpr int ID = decltype(id)::value;
 #pragma unroll
         for (int x = 0; x < NFRAG; ++x) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, ID);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, ID);
         __builtin_amdgcn_sched_barrier(0);
-        // this wave's reads of stage kt are complete (lgkmcnt 0) and stage kt+1 has landed: in the
-        // steady state the NSTAGE-2 stages issued after it may still be in flight
-        if (decltype(refill)::value) wait_counts<(NSTAGE - 2) * LOADS, 1>();
+    };
+    // Ring protocol.  Block 2*kt holds the A rows of stage kt, block 2*kt+1 its W rows; block j lives in slot j % 5.
+    // Stage kt issues block 2*kt+4 (A of stage kt+2) in its first k-step and block 2*kt+5 (W of stage kt+2) after its
+    // barrier, into the slots that stage kt-1's W rows and stage kt's A rows have left.
+    const int KT = K / BK;
+    issue_a(0, 0);
+    issue_w(0, 1);
+    if (KT > 1) {
+        issue_a(1, 2);
+        issue_w(1, 3);
+        wait_counts<LA + LW, 0>();
+    } else {
+        wait_counts<0, 0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 1, 0, af0, wf0);
+
+    // consumes the stage whose A rows sit in slot sa (W rows in sa + 1); on return (af0, wf0) hold k-step 0 of the next
+    auto stage = [&](int kt, int sa, auto more) {
+        constexpr bool MORE = decltype(more)::value;   // stage kt + 2 exists
+        const int sw = inc(sa, 1), sa2 = inc(sa, 2), sw2 = inc(sa, 3), sfree = inc(sa, 4);
+        if (MORE) issue_a(kt + 2, sfree);
+        load_frags(sa, sw, 1, af1, wf1);
+        mfma_group(af0, wf0);
+        interleave(std::integral_constant<int, 0>{});
+        load_frags(sa, sw, 2, af0, wf0);
+        mfma_group(af1, wf1);
+        interleave(std::integral_constant<int, 1>{});
+        load_frags(sa, sw, 3, af1, wf1);
+        mfma_group(af0, wf0);
+        interleave(std::integral_constant<int, 2>{});
+        // this wave's reads of the stage are complete and its share of the next stage has landed
+        if (MORE) wait_counts<LA, 1>();
         else wait_counts<0, 1>();
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        // phase B: refill the slot just freed, fetch k-step 0 of the next stage, run k-step 1 of this one
-        if (decltype(refill)::value) issue_loads(kt + NSTAGE);
-        load_frags(kt + 1, 0, af0, wf0);
+        if (MORE) issue_w(kt + 2, sa);
+        load_frags(sa2, sw2, 0, af0, wf0);
         mfma_group(af1, wf1);
-#pragma unroll
-        for (int x = 0; x < NFRAG; ++x) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 1);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave(std::integral_constant<int, 3>{});
     };
-    int kt = 0;
-    for (; kt < KT - NSTAGE; ++kt) step(kt, std::true_type{});
-    for (; kt < KT - 1; ++kt) step(kt, std::false_type{});
-    load_frags(kt, 1, af1, wf1);
-    mfma_group(af0, wf0);
-    mfma_group(af1, wf1);
+    int kt = 0, sa = 0;
+    for (; kt + 2 < KT; ++kt) {
+        stage(kt, sa, std::true_type{});
+        sa = inc(sa, 2);
+    }
+    if (kt + 1 < KT) {
+        stage(kt, sa, std::false_type{});
+        sa = inc(sa, 2);
+        ++kt;
+    }
+    {   // last stage: nothing follows
+        const int sw = inc(sa, 1);
+        load_frags(sa, sw, 1, af1, wf1);
+        mfma_group(af0, wf0);
+        load_frags(sa, sw, 2, af0, wf0);
+        mfma_group(af1, wf1);
+        load_frags(sa, sw, 3, af1, wf1);
+        mfma_group(af0, wf0);
+        mfma_group(af1, wf1);
+    }
 
     // ---- epilogue: bias + float16 conversion in registers, then through LDS so that every global
     //      store instruction writes whole 512-byte pieces of C rows (accumulator register r of tile
@@ -296,33 +323,34 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
     }
 }
 
-int g_gemm_xcd_split_n = -1;   // -1 = default choice
+int g_gemm_xcd_split_n = -1;   // -1 = default choice (debug hook; process-wide, set it only while no launch is in progress)
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int GROUP_M, int HD = 0>
+template <int BM, int BN, int WM, int WN, int GROUP_M, int HD = 0>
 int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
-                hipStream_t st, RopeArgs rope = RopeArgs{nullptr, 0, 1, 0, 0}) {
-    auto kern = gemm_bias_f16<BM, BN, WM, WN, NSTAGE, GROUP_M, HD>;
-    constexpr int stage_bytes = NSTAGE * (BM + BN) * ROW_BYTES, c_bytes = BM * (BN * 2 + 16);
-    constexpr int lds_bytes = stage_bytes > c_bytes ? stage_bytes : c_bytes;
-    static bool configured = false;   // per process and instantiation (one device is used)
-    if (!configured) {
-        KVPR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     lds_bytes));
-        configured = true;
-    }
+                hipStream_t st, RopeArgs rope = RopeArgs{nullptr, 0, 1, 0}) {
+    auto kern = gemm_bias_f16<BM, BN, WM, WN, GROUP_M, HD>;
+    constexpr int ring_bytes = NBLK * (BM > BN ? BM : BN) * ROW_BYTES, c_bytes = BM * (BN * 2 + 16);
+    constexpr int lds_bytes = ring_bytes > c_bytes ? ring_bytes : c_bytes;
+    // once per process and instantiation; call_once makes concurrent first launches from several threads safe
+    static std::once_flag configured;
+    static hipError_t configure_status = hipSuccess;
+    std::call_once(configured, [&] {
+        configure_status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    });
+    KVPR_HIP(configure_status);
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
     const int64_t total = (int64_t)tiles_m * tiles_n;
     // Which mapping: measured on MI355X, giving every XCD a band of W wins once W no longer sits comfortably in the
-    // memory-side cache next to the A panels in flight (N = 14336, K = 7168, 196 MiB: +12 %), and loses 1-2 % when W
+    // memory-side cache next to the A panels in flight (N = 14336, K = 7168, 196 MiB), and loses 1-2 % when W
     // is small (64 MiB at K = 4096); equal at 100 MiB.
     const bool big_w = (int64_t)N * K * 2 > ((int64_t)128 << 20);
-    rope.xcd_split_n = g_gemm_xcd_split_n >= 0 ? g_gemm_xcd_split_n : (big_w ? 1 : 0);
-    if (tiles_n < 8) rope.xcd_split_n = 0;
+    int xcd_split_n = g_gemm_xcd_split_n >= 0 ? g_gemm_xcd_split_n : (big_w ? 1 : 0);
+    if (tiles_n < 8) xcd_split_n = 0;
     const int max_width = (tiles_n + 7) / 8;
-    const int tiles_per_xcd = rope.xcd_split_n ? max_width * tiles_m : (int)((total + 7) / 8);
+    const int tiles_per_xcd = xcd_split_n ? max_width * tiles_m : (int)((total + 7) / 8);
     const unsigned grid = (unsigned)(tiles_per_xcd * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds_bytes, st, (const _Float16*)a, (const _Float16*)w,
-                       (const _Float16*)bias, (_Float16*)c, M, N, K, ldc, tiles_m, tiles_n, tiles_per_xcd, rope);
+                       (const _Float16*)bias, (_Float16*)c, M, N, K, ldc, tiles_m, tiles_n, tiles_per_xcd, xcd_split_n, rope);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }
@@ -335,10 +363,10 @@ int launch_gemm(const void* a, const void* w, const void* bias, void* c, int64_t
                 hipStream_t st) {
     if (M == 0) return KVPR_OK;
     switch (g_gemm_variant) {   // variants other than 0 exist for tests and tuning sweeps
-        case 1: return launch_tile<256, 256, 2, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
-        case 2: return launch_tile<256, 128, 2, 2, 3, 8>(a, w, bias, c, M, N, K, ldc, st);
-        case 3: return launch_tile<128, 128, 2, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
-        default: return launch_tile<256, 256, 4, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
+        case 1: return launch_tile<256, 256, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
+        case 2: return launch_tile<256, 128, 2, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
+        case 3: return launch_tile<128, 128, 2, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
+        default: return launch_tile<256, 256, 4, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
     }
 }
 
@@ -347,9 +375,9 @@ int launch_gemm(const void* a, const void* w, const void* bias, void* c, int64_t
 int launch_gemm_rope(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
                      const void* table, int rope_cols, int head_dim, int batch, int pos0, hipStream_t st) {
     if (M == 0) return KVPR_OK;
-    const RopeArgs r{(const float2*)table, rope_cols, batch, pos0, 0};
-    if (head_dim == 64) return launch_tile<256, 256, 4, 2, 4, 8, 64>(a, w, bias, c, M, N, K, ldc, st, r);
-    return launch_tile<256, 256, 4, 2, 4, 8, 128>(a, w, bias, c, M, N, K, ldc, st, r);
+    const RopeArgs r{(const float2*)table, rope_cols, batch, pos0};
+    if (head_dim == 64) return launch_tile<256, 256, 4, 2, 8, 64>(a, w, bias, c, M, N, K, ldc, st, r);
+    return launch_tile<256, 256, 4, 2, 8, 128>(a, w, bias, c, M, N, K, ldc, st, r);
 }
 
 }  // namespace kvpr
