@@ -1,15 +1,21 @@
 #!/usr/bin/env python3
 """Bench of KVPR's per-layer decode hot path on one MI355X.
 
-A "step" is one decode of one OPT-6.7B-shaped attention layer (hidden 4096, 32 heads x 128,
-fp16, batch 32, context 1024) through the whole path at the scheduler-chosen split l*:
-H2D of X[0:l*] and KV[l*:s] from the pinned host store, new-token q/k/v projection, recompute
-GEMM, decode attention over s+1 positions, output projection, store-back.  The layer's
-activations and cache start in pinned host memory (that is where the method keeps them; moving
-them is the method), weights and the decode token's input are resident in HBM.
+A "step" is one decode of one OPT-shaped attention layer through the whole path at the scheduler-chosen
+split l*: H2D of X[0:l*] and KV[l*:s] from the pinned host store, new-token q/k/v projection, recompute GEMM,
+decode attention over s+1 positions, output projection, store-back.  The layer's activations and cache start
+in pinned host memory (that is where the method keeps them; moving them is the method), weights and the
+decode token's input are resident in HBM.
 
-Prints ONE JSON line.  Paper context (A100 + PCIe 4.0, whole models, not comparable): up to
-35.8 % lower decode latency and 46.2 % higher throughput than its baselines.
+With no --model the run covers every configuration the metric is quoted on, in one process, and prints ONE
+JSON line: the headline fields are those of the largest layer shape (OPT-30B shape, hidden 7168, batch 32,
+context 1024); `configs` holds the OPT-6.7B shape (at l* and at l in {0, s/4, s/2, 3s/4, s}), the OPT-13B
+shape, the OPT-30B context sweep at batch 16 (s in {512, 1024, 2048, 4096}), the 40-layer OPT-13B-shaped
+stack generating 32 tokens greedily, and the column-by-column schedule with offloaded weights.  --steps /
+--warmup apply to every per-layer timing.  With --model the run is that one layer shape.
+
+Paper context (A100 + PCIe 4.0, whole models, not comparable): up to 35.8 % lower decode latency and 46.2 %
+higher throughput than its baselines.
 """
 from __future__ import annotations
 
@@ -150,7 +156,9 @@ def run_stack(args):
         "pinned_store_GiB": L * (s + gen + args.warmup + 2) * (x_bpp + kv_bpp) / 2 ** 30, "setup_s": setup_s,
     }
     k.kvpr_destroy(ctx)
-    print(json.dumps(result))
+    del keep, ws, w_lm, emb, logits
+    torch.cuda.empty_cache()
+    return result
 
 
 def run_columns(args):
@@ -227,7 +235,9 @@ def run_columns(args):
         "pinned_GiB": (S * (s + 2 * (gen + args.warmup) + 2) * (x_bpp + kv_bpp) + L * blob_bytes) / 2 ** 30, "setup_s": setup_s,
     }
     k.kvpr_destroy(ctx)
-    print(json.dumps(out))
+    del dev_w, wdev
+    torch.cuda.empty_cache()
+    return out
 
 
 def run_kernels(args):
@@ -277,12 +287,300 @@ def run_kernels(args):
     print(json.dumps(out))
 
 
+def profile_figures(model, b, s):
+    """Figures that only a profiler run can give (rocprofv3 counter runs of `bench.py --kernels`, committed under
+    profiles/): HBM-side bytes per recomputed position and the fraction of cycles the MFMA unit was busy."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    return json.load(open(path)).get(f"recompute_gemm/{model}/b{b}/s{s}")
+
+
+def run_layer(args, model, b, s, split_arg=-1, sweep=(), attention=True, extension=False, cpu=False):
+    """One attention layer of `model` shape at batch b, context s: profile, plan, calibrate, warm up, time
+    args.steps decodes.  Returns the figures of the case as a dict."""
+    import torch
+    import kvpr_inputs
+    import paper_2411_17089_amd as k
+    h, H, d = kvpr_inputs.SHAPES[model]
+    cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
+
+    layer = kvpr_inputs.make_layer(0, b, s, h, H)
+    f16 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    llama = model.startswith("llama")
+    arch = k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT
+    wqkv = f16(np.concatenate([layer["Wq"].T, layer["Wk"].T, layer["Wv"].T], 0))
+    bqkv = f16(np.concatenate([layer["bq"], layer["bk"], layer["bv"]]))
+    wo, bo, x_new = f16(layer["Wo"].T), f16(layer["bo"]), f16(layer["x_new"])
+    w = k.make_weights(wqkv=wqkv, wo=wo) if llama else k.make_weights(wqkv=wqkv, bqkv=bqkv, wo=wo, bo=bo)
+    out = torch.empty((b, h), dtype=torch.float16, device="cuda")
+
+    # bytes per cached position (whole batch) as they cross the link, flops per recomputed position (Eq. 6, Eq. 8)
+    qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
+    f_pp = 4 * b * h * h
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, dtype=k.KVPR_F16 | qflags, arch=arch)
+    k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
+    k.kvpr_store_prefill_kv(ctx, 0, s, w)          # stand-in for prefill: cache = X.[Wk|Wv]+b, computed on the GPU
+
+    prof0 = k.kvpr_profile(ctx, b, s)
+    k.kvpr_set_profile(ctx, prof0, cm, args.granularity)
+    k.kvpr_set_chunks(ctx, args.chunks)
+    # Refine the two constants in place: a few untimed decodes at the planned split with the run-time adaptation on.
+    # The GEMM inside the real pipeline (fresh activations, cache copy in flight, GPU coming out of an idle stretch)
+    # runs below its isolated rate on the wider shapes; the plan should use what the pipeline delivers.
+    prof = prof0
+    if args.calibrate > 0 and split_arg < 0:
+        k.kvpr_set_adaptive(ctx, 0.5)
+        for _ in range(args.calibrate):
+            k.kvpr_layer_decode(ctx, 0, s, -1, w, x_new, out)
+            torch.cuda.synchronize()
+        prof = k.kvpr_get_profile(ctx)
+        k.kvpr_set_adaptive(ctx, 0.0)
+    pchunks = args.chunks if cm == k.KVPR_COST_EQ10 else 1
+    # The split comes from the calibrated constants.  Every "bound" below is a cost model evaluated with the start-up
+    # profile's constants (isolated copy rate, GEMM under a concurrent copy), so no ratio is measured against itself:
+    #   builder's bound: the cost form in use with l restricted to multiples of the granularity and the GEMM charged
+    #                    in whole rounds of one tile per compute unit;
+    #   plain Eq. 10:    the paper's form as printed, every integer l, divisible GEMM work.
+    l_star, _ = k.kvpr_plan_split_linear(prof, cm, pchunks, s, x_bpp, kv_bpp, f_pp, args.granularity)
+    l_uncal, _ = k.kvpr_plan_split_linear(prof0, cm, pchunks, s, x_bpp, kv_bpp, f_pp, args.granularity)
+    plain = k.kvpr_profile_t.from_buffer_copy(prof0)
+    plain.gemm_round_flops = 0
+    plain.h2d_latency_s = plain.gemm_latency_s = 0.0
+    l_plain, t_plain = k.kvpr_plan_split_linear(plain, k.KVPR_COST_EQ10, 1, s, x_bpp, kv_bpp, f_pp, 1)
+    l_eq10, t_eq10 = k.kvpr_plan_split_linear(prof0, k.KVPR_COST_EQ10, 1, s, x_bpp, kv_bpp, f_pp, args.granularity)
+
+    def timed_at(split, steps):
+        for _ in range(args.warmup):
+            k.kvpr_layer_decode(ctx, 0, s, split, w, x_new, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            k.kvpr_layer_decode_timed(ctx, 0, s, split, w, x_new, out, i)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall * 1e3 / steps, [k.kvpr_timing_read(ctx, i) for i in range(steps)]
+
+    split = l_star if split_arg < 0 else split_arg
+    t_bound_split = k.kvpr_cost_linear(prof0, cm, pchunks, split, s, x_bpp, kv_bpp, f_pp)
+    t_plain_split = k.kvpr_cost_linear(plain, k.KVPR_COST_EQ10, 1, split, s, x_bpp, kv_bpp, f_pp)
+    ms_step, tim = timed_at(split, args.steps)
+
+    mean = lambda name: float(np.mean([getattr(t, name) for t in tim]))
+    ms_gemm, ms_attn = mean("ms_recompute"), mean("ms_attn")
+    ms_act, ms_kv = mean("ms_act_copy"), mean("ms_kv_copy")
+    gemm_flops = 4.0 * b * split * h * h
+    attn_bytes = 2.0 * b * (s + 1) * h * 2
+    # ms_attn sums the two attention phases; with a packed cache the transferred rows are read in packed form
+    attn_phase_bytes = float(2 * b * (split + 1) * h * 2 + kv_bpp * (s - split)) if qflags & k.KVPR_KV_INT4 else attn_bytes
+    two_phase = bool(qflags & k.KVPR_KV_INT4 or split >= 128)
+    attn_kernel = "attention_partial_ranged x2 (+combine)" if two_phase else "attention_partial (+combine)"
+    h2d_bytes = float(x_bpp * split + kv_bpp * (s - split))
+    gemm_tflops = gemm_flops / (ms_gemm * 1e-3) / 1e12 if split > 0 else 0.0
+    attn_gbps = attn_phase_bytes / (ms_attn * 1e-3) / 1e9
+    h2d_gbps = h2d_bytes / ((ms_act + ms_kv) * 1e-3) / 1e9
+
+    res = {
+        "workload": f"{model}-shaped attention layer, hidden {h}, {H} heads x {d}, batch {b}, context {s}, "
+                    f"decode 1 token at split l={split}",
+        "model": model, "batch": b, "context": s, "split": split, "l_star": l_star,
+        "l_star_from_startup_profile_alone": l_uncal,
+        "ms_per_layer": ms_step, "tokens_per_s": b / (ms_step * 1e-3),
+        "ms_assemble": mean("ms_assemble"), "ms_total_events": mean("ms_total"),
+        # per-step spread (event time first enqueue -> end of the step): the link of these boxes has occasional slow stretches
+        "ms_total_events_min_median_max": [float(np.min([t.ms_total for t in tim])), float(np.median([t.ms_total for t in tim])),
+                                           float(np.max([t.ms_total for t in tim]))],
+        "bounds": {
+            "which": "builder = cost form '%s', l a multiple of %d, GEMM charged in whole 256-tile rounds; plain = Eq. 10 as "
+                     "printed (every integer l, divisible work); both with the start-up profile's constants" % (args.cost_model, args.granularity),
+            "builder_bound_ms_at_split": t_bound_split * 1e3,
+            "builder_eq10_bound_ms_at_its_optimum": t_eq10 * 1e3, "builder_eq10_l_star": l_eq10,
+            "plain_eq10_bound_ms_at_split": t_plain_split * 1e3,
+            "plain_eq10_bound_ms_at_its_optimum": t_plain * 1e3, "plain_eq10_l_star": l_plain,
+            "assemble_over_builder_bound": mean("ms_assemble") / (t_bound_split * 1e3),
+            "assemble_over_plain_eq10_at_split": mean("ms_assemble") / (t_plain_split * 1e3),
+            "assemble_over_plain_eq10_optimum": mean("ms_assemble") / (t_plain * 1e3),
+            "step_over_builder_bound": ms_step / (t_bound_split * 1e3),
+            "step_over_plain_eq10_optimum": ms_step / (t_plain * 1e3),
+        },
+        "breakdown_ms": {"act_copy": ms_act, "kv_copy": ms_kv, "recompute": ms_gemm, "proj": mean("ms_proj"),
+                         "attn": ms_attn, "out": mean("ms_out"), "store": mean("ms_store"), "attn_early": mean("ms_attn_early")},
+        "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12,
+                    "before_calibration": {"v_com_GBps": prof0.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof0.gemm_flops_per_s / 1e12},
+                    "calibration_decodes": args.calibrate if split_arg < 0 else 0,
+                    "v_gpu_alone_TFLOPs": prof.gemm_alone_flops_per_s / 1e12, "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
+                    "d2h_GBps": prof.d2h_bytes_per_s / 1e9, "attn_GBps": prof.attn_bytes_per_s / 1e9},
+        "gemm": {"TFLOPs": gemm_tflops, "frac_of_mfma_peak": gemm_tflops / PEAK_MFMA_F16_TFLOPS, "avg_ms": ms_gemm,
+                 "flops_per_launch": gemm_flops},
+        "h2d": {"achieved_GBps": h2d_gbps, "measured_pinned_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
+                "frac": h2d_gbps / (prof.h2d_peak_bytes_per_s / 1e9), "bytes_per_step": h2d_bytes},
+        "attention_in_layer_event_pairs": {"kernels": attn_kernel, "ms": ms_attn, "ms_before_cache_fence": mean("ms_attn_early"),
+                                           "bytes": attn_phase_bytes, "GBps": attn_gbps,
+                                           "note": "event pairs around single 20-90 us launches carry ~10 us of gap each"},
+    }
+
+    if attention:
+        # the attention exactly as the layer runs it at this split (two ranged launches + combine when l >= 128, one
+        # launch otherwise) and the single-launch kernel, each 20 times back to back between one pair of events
+        kv_res = torch.randn((s + 1, b, 2 * h), dtype=torch.float16, device="cuda")
+        q_res = torch.randn((b, h), dtype=torch.float32, device="cuda")
+        z_res = torch.empty((b, h), dtype=torch.float16, device="cuda")
+        ws_res = torch.empty(k.kvpr_attention_workspace_bytes(b, h, H, s + 1), dtype=torch.uint8, device="cuda")
+        def b2b(fn):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / 20
+        ms_single = b2b(lambda: k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H))
+        ms_layer_form = (b2b(lambda: k.kvpr_decode_attention_mixed(q_res, kv_res, None, z_res, ws_res, s + 1, split, b, h, H))
+                         if two_phase and not qflags else ms_single)
+        del kv_res
+        res["attention"] = {
+            "as_in_layer": {"kernels": attn_kernel if not qflags else "attention_partial (+combine)", "avg_ms": ms_layer_form,
+                            "GBps": attn_bytes / (ms_layer_form * 1e-3) / 1e9,
+                            "frac_of_hbm_peak": attn_bytes / (ms_layer_form * 1e-3) / 1e9 / PEAK_HBM_GBPS},
+            "single_launch": {"kernels": "attention_partial (+combine)", "avg_ms": ms_single,
+                              "GBps": attn_bytes / (ms_single * 1e-3) / 1e9,
+                              "frac_of_hbm_peak": attn_bytes / (ms_single * 1e-3) / 1e9 / PEAK_HBM_GBPS},
+            "bytes_per_launch": attn_bytes,
+        }
+
+    if sweep:
+        res["split_sweep"] = []
+        for l in sweep:
+            ms_l, tim_l = timed_at(l, args.steps)
+            t_b = k.kvpr_cost_linear(prof0, cm, pchunks, l, s, x_bpp, kv_bpp, f_pp)
+            t_p = k.kvpr_cost_linear(plain, k.KVPR_COST_EQ10, 1, l, s, x_bpp, kv_bpp, f_pp)
+            asm = float(np.mean([t.ms_assemble for t in tim_l]))
+            res["split_sweep"].append({"split": l, "ms_per_layer": ms_l, "ms_assemble": asm,
+                                       "assemble_over_builder_bound": asm / (t_b * 1e3), "assemble_over_plain_eq10": asm / (t_p * 1e3)})
+        k.kvpr_layer_decode(ctx, 0, s, split, w, x_new, out)      # leave `out` at the headline split for the oracle check
+        torch.cuda.synchronize()
+
+    if extension and args.extension_chunks > 1 and args.chunks == 1 and cm == k.KVPR_COST_EQ10 and split_arg < 0:
+        # same layer, same number of steps, X[0:l] copied in parts with each part's GEMM started as it lands
+        c = args.extension_chunks
+        k.kvpr_set_chunks(ctx, c)
+        l_c, _ = k.kvpr_plan_split_linear(prof, k.KVPR_COST_EQ10, c, s, x_bpp, kv_bpp, f_pp, args.granularity)
+        t_c = k.kvpr_cost_linear(prof0, k.KVPR_COST_EQ10, c, l_c, s, x_bpp, kv_bpp, f_pp)
+        for _ in range(args.warmup):
+            k.kvpr_layer_decode(ctx, 0, s, l_c, w, x_new, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            k.kvpr_layer_decode(ctx, 0, s, l_c, w, x_new, out)
+        torch.cuda.synchronize()
+        ms_c = (time.perf_counter() - t0) * 1e3 / args.steps
+        k.kvpr_set_chunks(ctx, 1)
+        res["extension_chunked_copy"] = {
+            "chunks": c, "l_star": l_c, "ms_per_layer": ms_c, "tokens_per_s": b / (ms_c * 1e-3),
+            "chunked_model_bound_ms": t_c * 1e3, "step_over_chunked_bound": ms_c / (t_c * 1e3),
+            "step_over_plain_eq10_optimum": ms_c / (t_plain * 1e3), "speedup_over_paper_schedule": ms_step / ms_c,
+            "note": "not the paper's schedule: X[0:l] travels in parts and each part is recomputed as it lands; "
+                    "same outputs bit for bit"}
+
+    if cpu:
+        n_seq = min(args.cpu_seqs, b)
+        o_ref, dt, cores = cpu_baseline(layer, n_seq, llama)
+        got = out.float().cpu().numpy()[:n_seq]
+        res["cpu_baseline"] = {
+            "value": n_seq / dt, "unit": "tokens/s per layer", "cores": cores, "kind": "oracle",
+            "sample": f"{model} shape, batch {b}, context {s}: first {n_seq} of the {b} sequences of the layer, one decode step: numpy "
+                      f"float64 recompute of all {s} K/V rows (Eq. 1) + attention + output projection; {dt:.2f} s",
+            ("max_rel_err_gpu_vs_oracle_on_sample" if not qflags else "max_rel_err_gpu_over_4bit_store_vs_exact_oracle_on_sample"):
+                float(np.max(np.abs(got - o_ref)) / np.max(np.abs(o_ref))),
+        }
+    k.kvpr_destroy(ctx)
+    del wqkv, wo, layer
+    torch.cuda.empty_cache()
+    return res
+
+
+def headline(args, r):
+    """The one-line record of the driver's contract, from the figures of one layer case."""
+    pf = profile_figures(r["model"], r["batch"], r["context"])
+    traffic = None
+    roof = {"kernel": "gemm_bias_f16 (recompute GEMM%s)" % (", rotary epilogue" if r["model"].startswith("llama") else ""),
+            "bound": "mfma", "achieved": r["gemm"]["TFLOPs"], "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+            "frac": r["gemm"]["frac_of_mfma_peak"], "traffic": None, "flops_per_launch": r["gemm"]["flops_per_launch"],
+            "avg_ms": r["gemm"]["avg_ms"],
+            "measured": "HIP events around the launch inside each timed layer decode, mean over the timed steps"}
+    if pf:
+        # not measurable inside this process: counters of a separate rocprofv3 run of `bench.py --kernels` at this shape,
+        # per recomputed position (the kernel's traffic is linear in the number of row tiles), times this run's split
+        traffic = (pf["fetch_bytes_per_position"] + pf["write_bytes_per_position"]) * r["split"]
+        roof["traffic"] = traffic
+        roof["traffic_source"] = pf.get("source", "profiles/traffic.json")
+        roof["traffic_detail"] = {"fetch_bytes": pf["fetch_bytes_per_position"] * r["split"],
+                                  "write_bytes": pf["write_bytes_per_position"] * r["split"],
+                                  "algorithmic_read_bytes": 2.0 * r["batch"] * r["split"] * pf["hidden"] + 4.0 * pf["hidden"] ** 2,
+                                  "algorithmic_write_bytes": 4.0 * r["batch"] * r["split"] * pf["hidden"]}
+        if "mfma_busy_frac" in pf:
+            roof["mfma_busy_frac"] = pf["mfma_busy_frac"]
+            roof["mfma_busy_source"] = pf.get("mfma_busy_source", roof["traffic_source"])
+    out = {
+        "metric": "decode_layer_tokens_per_s_at_optimal_split",
+        "value": r["tokens_per_s"],
+        "unit": "tokens/s per layer (batch / per-layer decode latency)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_layer"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic (seeded N(0,1) activations, N(0,0.02) weights; cache = GPU prefill of the same X)",
+        "config": {"workload": r["workload"], "cost_model": args.cost_model, "granularity": args.granularity,
+                   "l_star": r["l_star"], "chunks": args.chunks, "store_int4": args.store_int4},
+        "ms_per_layer": r["ms_per_layer"], "ms_assemble": r["ms_assemble"], "ms_total_events": r["ms_total_events"],
+        "ms_total_events_min_median_max": r["ms_total_events_min_median_max"],
+        "bounds": r["bounds"],
+        "latency_over_bound": r["bounds"]["assemble_over_plain_eq10_at_split"],
+        "breakdown_ms": r["breakdown_ms"], "profile": r["profile"],
+        "roofline": roof,
+        "h2d": r["h2d"],
+    }
+    if "attention" in r:
+        a = r["attention"]["as_in_layer"]
+        out["roofline_attention"] = {"kernel": a["kernels"] + ", float16 cache, as the layer launches it at this split, 20 times back to back",
+                                     "bound": "hbm", "achieved": a["GBps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                     "frac": a["frac_of_hbm_peak"], "bytes_per_launch": r["attention"]["bytes_per_launch"],
+                                     "avg_ms": a["avg_ms"], "single_launch": r["attention"]["single_launch"],
+                                     "in_layer_event_pairs": r["attention_in_layer_event_pairs"]}
+    for key in ("extension_chunked_copy", "split_sweep", "cpu_baseline"):
+        if key in r:
+            out[key] = r[key]
+    return out
+
+
+def compact(r):
+    """A case as an entry of the `configs` array."""
+    e = {"workload": r["workload"], "l_star": r["l_star"], "l_star_from_startup_profile_alone": r["l_star_from_startup_profile_alone"],
+         "ms_per_layer": r["ms_per_layer"], "tokens_per_s": r["tokens_per_s"],
+         "gemm_TFLOPs": r["gemm"]["TFLOPs"], "gemm_frac_of_mfma_peak": r["gemm"]["frac_of_mfma_peak"],
+         "h2d_GBps": r["h2d"]["achieved_GBps"], "h2d_frac_of_pinned_peak": r["h2d"]["frac"],
+         "assemble_over_builder_bound": r["bounds"]["assemble_over_builder_bound"],
+         "assemble_over_plain_eq10_at_split": r["bounds"]["assemble_over_plain_eq10_at_split"],
+         "assemble_over_plain_eq10_optimum": r["bounds"]["assemble_over_plain_eq10_optimum"],
+         "plain_eq10_l_star": r["bounds"]["plain_eq10_l_star"], "ms_total_events_min_median_max": r["ms_total_events_min_median_max"],
+         "profile": {"v_com_GBps": r["profile"]["v_com_GBps"], "v_gpu_TFLOPs": r["profile"]["v_gpu_TFLOPs"],
+                     "before_calibration": r["profile"]["before_calibration"]}}
+    if "attention" in r:
+        e["attention_frac_of_hbm_peak_as_in_layer"] = r["attention"]["as_in_layer"]["frac_of_hbm_peak"]
+        e["attention_frac_of_hbm_peak_single_launch"] = r["attention"]["single_launch"]["frac_of_hbm_peak"]
+    for key in ("split_sweep", "extension_chunked_copy"):
+        if key in r:
+            e[key] = r[key]
+    return e
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--model", default="opt-6.7b", help="opt-6.7b | opt-13b | opt-30b | llama2-7b | llama2-13b | tiny")
+    ap.add_argument("--model", default=None,
+                    help="opt-6.7b | opt-13b | opt-30b | llama2-7b | llama2-13b | tiny: run this one layer shape; default = every configuration")
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--seq", type=int, default=1024)
     ap.add_argument("--split", type=int, default=-1, help="-1 = scheduler's l*")
@@ -309,197 +607,73 @@ def main():
                     help="untimed decodes that refine the profiled v_com / v_gpu inside the real pipeline before planning (0 = plan from kvpr_profile alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
+    ap.add_argument("--skip", default="", help="(default run) comma list of parts to leave out: sweep, stack, columns")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
-    import kvpr_inputs
-    import paper_2411_17089_amd as k
+    import paper_2411_17089_amd as k  # noqa: F401  (fails loudly when libkvpr.so is missing)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    say = lambda msg: print("bench: " + msg, file=sys.stderr, flush=True)
     if args.stack:
-        return run_stack(args)
+        args.model = args.model or "opt-13b"
+        return print(json.dumps(run_stack(args)))
     if args.kernels:
+        args.model = args.model or "opt-6.7b"
         return run_kernels(args)
     if args.columns:
-        return run_columns(args)
-    h, H, d = kvpr_inputs.SHAPES[args.model]
-    b, s = args.batch, args.seq
-    cm = {"eq10": k.KVPR_COST_EQ10, "ns": k.KVPR_COST_NS, "row": k.KVPR_COST_ROW, "pipe": k.KVPR_COST_PIPE}[args.cost_model]
+        args.model = args.model or "opt-13b"
+        return print(json.dumps(run_columns(args)))
+    if args.model is not None:
+        r = run_layer(args, args.model, args.batch, args.seq, args.split, attention=True, extension=True,
+                      cpu=not args.no_cpu_baseline)
+        return print(json.dumps(headline(args, r)))
 
-    layer = kvpr_inputs.make_layer(0, b, s, h, H)
-    f16 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    llama = args.model.startswith("llama")
-    arch = k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT
-    wqkv = f16(np.concatenate([layer["Wq"].T, layer["Wk"].T, layer["Wv"].T], 0))
-    bqkv = f16(np.concatenate([layer["bq"], layer["bk"], layer["bv"]]))
-    wo, bo, x_new = f16(layer["Wo"].T), f16(layer["bo"]), f16(layer["x_new"])
-    w = k.make_weights(wqkv=wqkv, wo=wo) if llama else k.make_weights(wqkv=wqkv, bqkv=bqkv, wo=wo, bo=bo)
-    out = torch.empty((b, h), dtype=torch.float16, device="cuda")
-
-    # bytes per cached position (whole batch) as they cross the link, flops per recomputed position (Eq. 6, Eq. 8)
-    qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
-    f_pp = 4 * b * h * h
-    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2, dtype=k.KVPR_F16 | qflags, arch=arch)
-    k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
-    k.kvpr_store_prefill_kv(ctx, 0, s, w)          # stand-in for prefill: cache = X.[Wk|Wv]+b, computed on the GPU
-
-    prof0 = k.kvpr_profile(ctx, b, s)
-    k.kvpr_set_profile(ctx, prof0, cm, args.granularity)
-    k.kvpr_set_chunks(ctx, args.chunks)
-    # Refine the two constants in place: a few untimed decodes at the planned split with the run-time adaptation on.
-    # The GEMM inside the real pipeline (fresh activations, cache copy in flight, GPU coming out of an idle stretch)
-    # runs up to 15 % below its isolated rate on the wider shapes; the plan should use what the pipeline delivers.
-    prof = prof0
-    if args.calibrate > 0 and args.split < 0:
-        k.kvpr_set_adaptive(ctx, 0.5)
-        for _ in range(args.calibrate):
-            k.kvpr_layer_decode(ctx, 0, s, -1, w, x_new, out)
-            torch.cuda.synchronize()
-        prof = k.kvpr_get_profile(ctx)
-        k.kvpr_set_adaptive(ctx, 0.0)
-    pchunks = args.chunks if cm == k.KVPR_COST_EQ10 else 1
-    # the split comes from the calibrated constants; every "bound" below is the cost model with the start-up profile's
-    # constants (isolated copy rate, GEMM under a concurrent copy), so that the ratios are not measured against themselves
-    l_star, t_bound = k.kvpr_plan_split_linear(prof, cm, pchunks, s, x_bpp, kv_bpp, f_pp, args.granularity)
-    split = l_star if args.split < 0 else args.split
-    t_bound_split = k.kvpr_cost_linear(prof0, cm, pchunks, split, s, x_bpp, kv_bpp, f_pp)
-    l_eq10, t_eq10 = k.kvpr_plan_split_linear(prof0, k.KVPR_COST_EQ10, 1, s, x_bpp, kv_bpp, f_pp, args.granularity)
-
-    for _ in range(args.warmup):
-        k.kvpr_layer_decode(ctx, 0, s, split, w, x_new, out)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        k.kvpr_layer_decode_timed(ctx, 0, s, split, w, x_new, out, i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    tim = [k.kvpr_timing_read(ctx, i) for i in range(args.steps)]
-    ms_step = wall * 1e3 / args.steps
-
-    mean = lambda name: float(np.mean([getattr(t, name) for t in tim]))
-    ms_gemm, ms_attn = mean("ms_recompute"), mean("ms_attn")
-    ms_act, ms_kv = mean("ms_act_copy"), mean("ms_kv_copy")
-    gemm_flops = 4.0 * b * split * h * h
-    attn_bytes = 2.0 * b * (s + 1) * h * 2
-    # ms_attn sums the two attention phases; with a packed cache the transferred rows are read in packed form
-    attn_phase_bytes = float(2 * b * (split + 1) * h * 2 + kv_bpp * (s - split)) if qflags & k.KVPR_KV_INT4 else attn_bytes
-    attn_kernel = ("attention_partial_ranged x2 (+combine)" if (qflags & k.KVPR_KV_INT4 or split >= 128)
-                   else "attention_partial (+combine)")
-    h2d_bytes = float(x_bpp * split + kv_bpp * (s - split))
-    gemm_tflops = gemm_flops / (ms_gemm * 1e-3) / 1e12 if split > 0 else 0.0
-    attn_gbps = attn_phase_bytes / (ms_attn * 1e-3) / 1e9
-    h2d_gbps = h2d_bytes / ((ms_act + ms_kv) * 1e-3) / 1e9
-
-    # the attention kernel again, 20 launches back to back between one pair of events on the same stream: the
-    # per-layer event pair above also holds the two event-to-kernel gaps (~10 us of a ~90 us kernel)
-    kv_res = torch.randn((s + 1, b, 2 * h), dtype=torch.float16, device="cuda")
-    q_res = torch.randn((b, h), dtype=torch.float32, device="cuda")
-    z_res = torch.empty((b, h), dtype=torch.float16, device="cuda")
-    ws_res = torch.empty(k.kvpr_attention_workspace_bytes(b, h, H, s + 1), dtype=torch.uint8, device="cuda")
-    for _ in range(3):
-        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(20):
-        k.kvpr_decode_attention(q_res, kv_res, z_res, ws_res, s + 1, b, h, H)
-    e1.record()
-    e1.synchronize()
-    ms_attn_b2b = e0.elapsed_time(e1) / 20
-    del kv_res
-    attn_gbps_b2b = attn_bytes / (ms_attn_b2b * 1e-3) / 1e9
-
-    # HBM-side bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a
-    # known-size copy); only valid for the shape and split they were taken at
-    traffic, traffic_detail = None, None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        traffic_detail = json.load(open(tpath)).get(f"recompute_gemm/{args.model}/b{b}/s{s}")
-        if traffic_detail and traffic_detail.get("split") == split:
-            traffic = traffic_detail["total_bytes"]
-        else:
-            traffic_detail = None
-
-    result = {
-        "metric": "decode_layer_tokens_per_s_at_optimal_split",
-        "value": b / (ms_step * 1e-3),
-        "unit": "tokens/s per layer (batch / per-layer decode latency)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
-        "data": "synthetic (seeded N(0,1) activations, N(0,0.02) weights; cache = GPU prefill of the same X)",
-        "config": {"workload": f"{args.model}-shaped attention layer, hidden {h}, {H} heads x {d}, batch {b}, context {s}, "
-                               f"decode 1 token at split l={split}",
-                   "cost_model": args.cost_model, "granularity": args.granularity, "l_star": l_star, "chunks": args.chunks,
-                   "store_int4": args.store_int4},
-        "ms_per_layer": ms_step,
-        "ms_assemble": mean("ms_assemble"), "ms_total_events": mean("ms_total"),
-        # per-step spread (event time first enqueue -> end of the step): the link of these boxes has occasional slow stretches
-        "ms_total_events_min_median_max": [float(np.min([t.ms_total for t in tim])), float(np.median([t.ms_total for t in tim])),
-                                           float(np.max([t.ms_total for t in tim]))],
-        "cost_model_bound_ms": t_bound_split * 1e3,
-        "eq10_bound_ms_at_its_own_optimum": t_eq10 * 1e3, "eq10_l_star": l_eq10,
-        "step_over_eq10_bound": ms_step / (t_eq10 * 1e3),
-        "latency_over_bound": mean("ms_assemble") / (t_bound_split * 1e3),
-        "step_over_bound": ms_step / (t_bound_split * 1e3),
-        "breakdown_ms": {"act_copy": ms_act, "kv_copy": ms_kv, "recompute": ms_gemm, "proj": mean("ms_proj"),
-                         "attn": ms_attn, "out": mean("ms_out"), "store": mean("ms_store"), "attn_early": mean("ms_attn_early")},
-        "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12,
-                    "before_calibration": {"v_com_GBps": prof0.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof0.gemm_flops_per_s / 1e12},
-                    "calibration_decodes": args.calibrate if args.split < 0 else 0,
-                    "v_gpu_alone_TFLOPs": prof.gemm_alone_flops_per_s / 1e12, "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9, "d2h_GBps": prof.d2h_bytes_per_s / 1e9,
-                    "attn_GBps": prof.attn_bytes_per_s / 1e9},
-        "roofline": {"kernel": "gemm_bias_f16 (recompute GEMM%s)" % (", rotary epilogue" if llama else ""), "bound": "mfma", "achieved": gemm_tflops,
-                     "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_MFMA_F16_TFLOPS,
-                     "traffic": traffic, "traffic_detail": traffic_detail, "flops_per_launch": gemm_flops, "avg_ms": ms_gemm},
-        # the attention kernel by itself: one pass over all s+1 float16 rows, 20 launches between one pair of events
-        # (the in-layer figures below are event pairs around single ~30-90 us launches and carry ~10 us of gap each)
-        "roofline_attention": {"kernel": "attention_partial (+combine), float16 cache, back to back", "bound": "hbm",
-                               "achieved": attn_gbps_b2b, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                               "frac": attn_gbps_b2b / PEAK_HBM_GBPS, "bytes_per_launch": attn_bytes, "avg_ms": ms_attn_b2b,
-                               "in_layer": {"kernels": attn_kernel, "ms": ms_attn, "ms_before_cache_fence": mean("ms_attn_early"),
-                                            "bytes": attn_phase_bytes, "GBps": attn_gbps}},
-        "h2d": {"achieved_GBps": h2d_gbps, "measured_pinned_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
-                "frac": h2d_gbps / (prof.h2d_peak_bytes_per_s / 1e9), "bytes_per_step": h2d_bytes},
-    }
-
-    if args.extension_chunks > 1 and args.chunks == 1 and cm == k.KVPR_COST_EQ10 and args.split < 0:
-        # same layer, same number of steps, X[0:l] copied in parts with each part's GEMM started as it lands
-        c = args.extension_chunks
-        k.kvpr_set_chunks(ctx, c)
-        l_c, _ = k.kvpr_plan_split_linear(prof, k.KVPR_COST_EQ10, c, s, x_bpp, kv_bpp, f_pp, args.granularity)
-        t_c = k.kvpr_cost_linear(prof0, k.KVPR_COST_EQ10, c, l_c, s, x_bpp, kv_bpp, f_pp)
-        for _ in range(args.warmup):
-            k.kvpr_layer_decode(ctx, 0, s, l_c, w, x_new, out)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            k.kvpr_layer_decode(ctx, 0, s, l_c, w, x_new, out)
-        torch.cuda.synchronize()
-        ms_c = (time.perf_counter() - t0) * 1e3 / args.steps
-        k.kvpr_set_chunks(ctx, 1)
-        result["extension_chunked_copy"] = {
-            "chunks": c, "l_star": l_c, "ms_per_layer": ms_c, "tokens_per_s": b / (ms_c * 1e-3),
-            "chunked_model_bound_ms": t_c * 1e3, "step_over_chunked_bound": ms_c / (t_c * 1e3),
-            "step_over_eq10_bound": ms_c / (t_eq10 * 1e3), "speedup_over_paper_schedule": ms_step / ms_c,
-            "note": "not the paper's schedule: X[0:l] travels in parts and each part is recomputed as it lands; "
-                    "same outputs bit for bit"}
-
-    if not args.no_cpu_baseline:
-        n_seq = min(args.cpu_seqs, b)
-        o_ref, dt, cores = cpu_baseline(layer, n_seq, llama)
-        got = out.float().cpu().numpy()[:n_seq]
-        result["cpu_baseline"] = {
-            "value": n_seq / dt, "unit": "tokens/s per layer", "cores": cores, "kind": "oracle",
-            "sample": f"first {n_seq} of the {b} sequences of the same layer, one decode step: numpy float64 recompute of "
-                      f"all {s} K/V rows (Eq. 1) + attention + output projection; {dt:.2f} s",
-            ("max_rel_err_gpu_vs_oracle_on_sample" if not qflags else "max_rel_err_gpu_over_4bit_store_vs_exact_oracle_on_sample"):
-                float(np.max(np.abs(got - o_ref)) / np.max(np.abs(o_ref))),
-        }
-    k.kvpr_destroy(ctx)
+    # ---- default: every configuration the metric is quoted on, one JSON line ----
+    skip = set(filter(None, args.skip.split(",")))
+    t_start = time.perf_counter()
+    configs = []
+    say("OPT-6.7B shape, batch 32, context 1024 (l* and the split sweep, CPU oracle beside it)")
+    c2 = run_layer(args, "opt-6.7b", 32, 1024, sweep=() if "sweep" in skip else (0, 256, 512, 768, 1024), extension=True,
+                   cpu=not args.no_cpu_baseline)
+    say("OPT-13B shape, batch 32, context 1024")
+    c3 = run_layer(args, "opt-13b", 32, 1024)
+    say("OPT-30B shape, batch 32, context 1024 (headline)")
+    c4 = run_layer(args, "opt-30b", 32, 1024, extension=True)
+    configs += [compact(c2), compact(c3)]
+    if "sweep" not in skip:
+        for s in (512, 1024, 2048, 4096):
+            say(f"OPT-30B shape, batch 16, context {s}")
+            configs.append(compact(run_layer(args, "opt-30b", 16, s)))
+    result = headline(args, c4)
+    if "cpu_baseline" in c2:
+        result["cpu_baseline"] = c2["cpu_baseline"]
+        result["cpu_baseline"]["note"] = ("timed on the OPT-6.7B-shaped layer (first entry of configs), not on the headline shape: the "
+                                          "float64 oracle needs (7168/4096)^2 = 3.1 times as long per sequence there")
+    if "stack" not in skip:
+        say("OPT-13B-shaped stack, 40 layers, batch 32, prompt 1024, 32 greedy tokens")
+        sa = argparse.Namespace(**vars(args))
+        sa.model, sa.batch, sa.seq, sa.layers, sa.gen, sa.warmup = "opt-13b", 32, 1024, 40, 32, 2
+        st = run_stack(sa)
+        configs.append({"workload": st["config"]["workload"], "tokens_per_s": st["value"], "ms_per_token": st["ms_per_step"],
+                        "ms_per_layer": st["ms_per_layer"], "splits_first_last": st["config"]["splits_first_last"],
+                        "h2d_GBps_sustained": st["h2d_GBps_sustained"], "h2d_frac_of_peak": st["h2d_frac_of_peak"],
+                        "breakdown_ms_per_layer": st["breakdown_ms_per_layer"], "host_enqueue_ms_per_token": st["host_enqueue_ms_per_token"],
+                        "pinned_store_GiB": st["pinned_store_GiB"], "profile": st["profile"], "cost_model": st["config"]["cost_model"]})
+    if "columns" not in skip:
+        say("column-by-column schedule, OPT-13B shape, 8 layers x 4 GPU batches of 32, weights offloaded")
+        ca = argparse.Namespace(**vars(args))
+        ca.model, ca.batch, ca.seq, ca.layers, ca.gpu_batches, ca.gen, ca.warmup = "opt-13b", 32, 1024, 8, 4, 8, 2
+        co = run_columns(ca)
+        configs.append({"workload": co["config"]["workload"], "tokens_per_s": co["value"], "kvpr": co["kvpr"],
+                        "no_recompute": co["no_recompute"], "speedup_over_no_recompute": co["speedup_over_no_recompute"]})
+    result["configs"] = configs
+    result["bench_wall_s"] = time.perf_counter() - t_start
     print(json.dumps(result))
 
 
