@@ -240,6 +240,111 @@ def run_columns(args):
     return out
 
 
+def run_power_probe(args):
+    """Evidence for what bounds the recompute GEMM on real data: shader clock and socket power (amd-smi, sampled twice a
+    second from a side thread) while (a) the recompute GEMM of the OPT-6.7B shape and (b) a register-only loop of the
+    same MFMA run for a few seconds each, on N(0,1) / N(0,0.02) operands, on a constant and on zeros."""
+    import subprocess
+    import threading
+    import ctypes as C
+    import torch
+    import kvpr_inputs
+    import paper_2411_17089_amd as k
+    h, H, d = kvpr_inputs.SHAPES[args.model]
+    b = args.batch
+    split = args.split if args.split >= 0 else 832
+    M = split * b
+    A = torch.empty((M, h), device="cuda", dtype=torch.float16)
+    W = torch.empty((2 * h, h), device="cuda", dtype=torch.float16)
+    Cc = torch.empty((M, 2 * h), device="cuda", dtype=torch.float16)
+    sink = torch.empty((256 * 512,), device="cuda", dtype=torch.float32)
+    k.lib.kvpr_debug_mfma_loop.restype = C.c_int
+    k.lib.kvpr_debug_mfma_loop.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def find(obj, want):
+        """first numeric 'value' under a key whose name contains `want` in amd-smi's JSON"""
+        if isinstance(obj, dict):
+            for key, v in obj.items():
+                if want in key.lower():
+                    if isinstance(v, dict) and "value" in v and isinstance(v["value"], (int, float)):
+                        return float(v["value"])
+                    if isinstance(v, dict) and "clk" in v:
+                        r = find({"clk_": v["clk"]}, "clk_")
+                        if r is not None:
+                            return r
+                    if isinstance(v, (int, float)):
+                        return float(v)
+                r = find(v, want)
+                if r is not None:
+                    return r
+        elif isinstance(obj, list):
+            for v in obj:
+                r = find(v, want)
+                if r is not None:
+                    return r
+        return None
+
+    samples, stop, raw = [], threading.Event(), []
+    def sampler():
+        while not stop.is_set():
+            try:
+                txt = subprocess.run(["amd-smi", "metric", "-g", "0", "--clock", "--power", "--json"], capture_output=True,
+                                     text=True, timeout=10).stdout
+                j = json.loads(txt)
+                if not raw:
+                    raw.append(txt[:1500])
+                samples.append((time.perf_counter(), find(j, "gfx_0"), find(j, "socket_power")))
+            except Exception as e:   # amd-smi missing or not permitted: the rates are still reported
+                if not raw:
+                    raw.append("amd-smi failed: %r" % (e,))
+            stop.wait(0.5)
+
+    def sustained(fn, work, seconds):
+        fn()
+        torch.cuda.synchronize()
+        n, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
+            n += 20
+        dt = time.perf_counter() - t0
+        mine = [s for s in samples if s[0] >= t0 + 1.0 and s[0] <= t0 + dt]    # skip the first second (ramp)
+        clk = [s[1] for s in mine if s[1] is not None]
+        pw = [s[2] for s in mine if s[2] is not None]
+        return {"TFLOPs": work * n / dt / 1e12, "seconds": dt, "launches": n, "samples": len(mine),
+                "shader_clock_MHz_min_mean_max": [min(clk), sum(clk) / len(clk), max(clk)] if clk else None,
+                "socket_power_W_min_mean_max": [min(pw), sum(pw) / len(pw), max(pw)] if pw else None}
+
+    th = threading.Thread(target=sampler, daemon=True)
+    th.start()
+    out = {"shape": {"M": M, "N": 2 * h, "K": h}, "modes": {}}
+    loop_iters = 4000
+    for mode in ("normal", "constant", "zeros"):
+        if mode == "normal":
+            A.normal_()
+            W.normal_()
+            W.mul_(0.02)
+        elif mode == "constant":
+            A.fill_(0.5)
+            W.fill_(0.015625)
+        else:
+            A.zero_()
+            W.zero_()
+        torch.cuda.synchronize()
+        time.sleep(1.0)
+        g = sustained(lambda: k.kvpr_recompute_gemm(A, W, None, Cc, M, 2 * h, h, 2 * h), 4.0 * M * h * h, args.probe_seconds)
+        time.sleep(1.0)
+        r = sustained(lambda: k.lib.kvpr_debug_mfma_loop(A.data_ptr(), W.data_ptr(), A.numel(), W.numel(), sink.data_ptr(), loop_iters, stream),
+                      256.0 * 8 * loop_iters * 16 * 2 * 32 * 32 * 16, args.probe_seconds)
+        out["modes"][mode] = {"recompute_gemm": g, "register_only_mfma_loop": r}
+    stop.set()
+    th.join(timeout=15)
+    out["amd_smi_first_sample"] = raw[0] if raw else None
+    print(json.dumps(out))
+
+
 def run_kernels(args):
     """Standalone launches of the path's kernels at the bench shape, for rocprofv3 counter runs:
     a plain device copy of known size (reference for scaling FETCH_SIZE / WRITE_SIZE), the recompute
@@ -325,6 +430,7 @@ def run_layer(args, model, b, s, split_arg=-1, sweep=(), attention=True, extensi
     prof0 = k.kvpr_profile(ctx, b, s)
     k.kvpr_set_profile(ctx, prof0, cm, args.granularity)
     k.kvpr_set_chunks(ctx, args.chunks)
+    k.kvpr_set_keep_warm(ctx, args.keep_warm)
     # Refine the two constants in place: a few untimed decodes at the planned split with the run-time adaptation on.
     # The GEMM inside the real pipeline (fresh activations, cache copy in flight, GPU coming out of an idle stretch)
     # runs below its isolated rate on the wider shapes; the plan should use what the pipeline delivers.
@@ -418,6 +524,17 @@ def run_layer(args, model, b, s, split_arg=-1, sweep=(), attention=True, extensi
                                            "bytes": attn_phase_bytes, "GBps": attn_gbps,
                                            "note": "event pairs around single 20-90 us launches carry ~10 us of gap each"},
     }
+
+    if args.keep_warm > 0 and split > 0:
+        # the same split without the clock keep-alive: the GEMM then starts on a GPU that idled through the activation copy
+        k.kvpr_set_keep_warm(ctx, 0.0)
+        ms_cold, tim_cold = timed_at(split, args.steps)
+        k.kvpr_set_keep_warm(ctx, args.keep_warm)
+        ms_gemm_cold = float(np.mean([t.ms_recompute for t in tim_cold]))
+        res["without_keep_warm"] = {"ms_per_layer": ms_cold, "gemm_avg_ms": ms_gemm_cold,
+                                    "gemm_TFLOPs": gemm_flops / (ms_gemm_cold * 1e-3) / 1e12,
+                                    "ms_assemble": float(np.mean([t.ms_assemble for t in tim_cold]))}
+        res["keep_warm_fraction"] = args.keep_warm
 
     if attention:
         # the attention exactly as the layer runs it at this split (two ranged launches + combine when l >= 128, one
@@ -547,7 +664,7 @@ def headline(args, r):
                                      "frac": a["frac_of_hbm_peak"], "bytes_per_launch": r["attention"]["bytes_per_launch"],
                                      "avg_ms": a["avg_ms"], "single_launch": r["attention"]["single_launch"],
                                      "in_layer_event_pairs": r["attention_in_layer_event_pairs"]}
-    for key in ("extension_chunked_copy", "split_sweep", "cpu_baseline"):
+    for key in ("extension_chunked_copy", "split_sweep", "cpu_baseline", "without_keep_warm", "keep_warm_fraction"):
         if key in r:
             out[key] = r[key]
     return out
@@ -568,7 +685,7 @@ def compact(r):
     if "attention" in r:
         e["attention_frac_of_hbm_peak_as_in_layer"] = r["attention"]["as_in_layer"]["frac_of_hbm_peak"]
         e["attention_frac_of_hbm_peak_single_launch"] = r["attention"]["single_launch"]["frac_of_hbm_peak"]
-    for key in ("split_sweep", "extension_chunked_copy"):
+    for key in ("split_sweep", "extension_chunked_copy", "without_keep_warm"):
         if key in r:
             e[key] = r[key]
     return e
@@ -590,6 +707,9 @@ def main():
                     help="throughput mode: column-by-column schedule with the weights offloaded too (use with --layers, --gpu-batches)")
     ap.add_argument("--gpu-batches", type=int, default=4)
     ap.add_argument("--kernels", action="store_true", help="launch each kernel of the path standalone (for rocprofv3 --pmc runs)")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="clock / power evidence: the recompute GEMM and a register-only MFMA loop on normal, constant and zero operands under amd-smi sampling")
+    ap.add_argument("--probe-seconds", type=float, default=6.0)
     ap.add_argument("--layers", type=int, default=40)
     ap.add_argument("--gen", type=int, default=32)
     ap.add_argument("--no-greedy", action="store_true", help="(stack mode, diagnostics) skip the LM head / argmax / embedding step")
@@ -605,6 +725,9 @@ def main():
                     help="(stack / columns modes) extension: keep adapting v_com / v_gpu while decoding with this moving-average weight")
     ap.add_argument("--calibrate", type=int, default=6,
                     help="untimed decodes that refine the profiled v_com / v_gpu inside the real pipeline before planning (0 = plan from kvpr_profile alone)")
+    ap.add_argument("--keep-warm", type=float, default=0.85,
+                    help="extension: fraction of the predicted activation-copy time during which the otherwise idle GPU runs a "
+                         "register-only MFMA loop, so that the recompute GEMM does not start with the clocks down (0 = off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
     ap.add_argument("--skip", default="", help="(default run) comma list of parts to leave out: sweep, stack, columns")
@@ -626,6 +749,9 @@ def main():
     if args.kernels:
         args.model = args.model or "opt-6.7b"
         return run_kernels(args)
+    if args.power_probe:
+        args.model = args.model or "opt-6.7b"
+        return run_power_probe(args)
     if args.columns:
         args.model = args.model or "opt-13b"
         return print(json.dumps(run_columns(args)))

@@ -246,6 +246,18 @@ int kvpr_adapt_update(kvpr_profile_t* prof, double alpha, int64_t link_bytes, do
 int kvpr_set_adaptive(kvpr_ctx* ctx, double alpha);
 int kvpr_get_profile(kvpr_ctx* ctx, kvpr_profile_t* out);
 
+/* Extension (not in the paper): clock keep-alive for the single-layer latency path.  In the paper's schedule the GPU
+ * has nothing to do while X[0:l] is on the link (the first term of Eq. 10), and a GPU that has idled for a few
+ * milliseconds starts the recompute GEMM with its clocks down (measured: 10-15 % slower at hidden >= 5120).  With
+ * fraction in (0, 0.95], kvpr_layer_decode[_timed] on a context that has a profile puts a register-only MFMA loop
+ * on the compute stream, between the token projection and the wait for the activations, that runs for
+ * fraction * (bytes of the first activation chunk) / h2d_bytes_per_s of wall time (its waves watch the constant-rate
+ * wall clock; an iteration count bounds it as well).  It reads 192 bytes of wqkv per lane and writes nothing; results
+ * are unchanged.  If the link turns out faster than the profile says, the GEMM starts late by at most the
+ * difference.  0 (the default) turns it off.  kvpr_decode_step and the column schedule never use it: there the GPU is
+ * busy with the neighbouring layers. */
+int kvpr_set_keep_warm(kvpr_ctx* ctx, double fraction);
+
 /* One decode step of one attention layer (Sec. 3.2 row-by-row pipeline with partial
  * recomputation; Eq. 1, 2, 3, 5, 7).  `seq` = cached positions s already in the host
  * store; split in [0, seq], or -1 to use the plan from kvpr_set_profile.

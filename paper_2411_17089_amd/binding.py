@@ -85,6 +85,7 @@ _SIGS = {
     "kvpr_adapt_update": (_i, [C.POINTER(kvpr_profile_t), C.c_double, _i64, C.c_double, _i64, C.c_double]),
     "kvpr_set_adaptive": (_i, [_vp, C.c_double]),
     "kvpr_get_profile": (_i, [_vp, C.POINTER(kvpr_profile_t)]),
+    "kvpr_set_keep_warm": (_i, [_vp, C.c_double]),
     "kvpr_layer_decode": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, C.POINTER(kvpr_layer_timing)]),
     "kvpr_layer_decode_timed": (_i, [_vp, _i, _i, _i, C.POINTER(kvpr_layer_weights), _vp, _vp, _i]),
     "kvpr_timing_read": (_i, [_vp, _i, C.POINTER(kvpr_layer_timing)]),
@@ -345,6 +346,10 @@ def kvpr_adapt_update(prof, alpha, link_bytes, link_seconds, gemm_flops, gemm_se
 
 def kvpr_set_adaptive(ctx, alpha):
     _check(lib.kvpr_set_adaptive(ctx, alpha))
+
+
+def kvpr_set_keep_warm(ctx, fraction):
+    _check(lib.kvpr_set_keep_warm(ctx, fraction))
 
 
 def kvpr_get_profile(ctx) -> kvpr_profile_t:

@@ -72,6 +72,10 @@ struct kvpr_ctx {
     LayerEvents probe[kProbes]{};
     bool probe_made = false, probe_pending[kProbes] = {};
     int probe_next = 0;
+    // clock keep-alive: fraction of the predicted activation-copy time that the compute stream spends in a register-only
+    // MFMA loop before it waits for the activations (0 = off)
+    double keep_warm = 0.0;
+    double wall_clock_hz = 0.0;
     int cost_model = KVPR_COST_EQ10, granularity = 1;
     int debug = 0;
 

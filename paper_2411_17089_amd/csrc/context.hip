@@ -196,6 +196,14 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     // ---- recompute rows [0, l) as soon as their activations have landed (Eq. 7) ----
     auto recompute = [&]() -> int {
         if (wf) KVPR_HIP(hipStreamWaitEvent(c->compute, wf->kv_ready, 0));
+        // single-layer latency path: the GPU would sit idle while X[0:l] is on the link and come out of that with its
+        // clocks down; keep it busy for most of the predicted copy time instead (kvpr_set_keep_warm)
+        if (fence_copy_to_start && !wf && c->keep_warm > 0.0 && c->have_prof && l > 0) {
+            const double t_first = (double)bound[1] * (double)xsb / c->prof.h2d_bytes_per_s;
+            if (t_first * c->keep_warm > 200e-6)
+                if (int rc = kvpr::launch_keep_warm(w->wqkv, (size_t)3 * h * h, t_first * c->keep_warm, c->wall_clock_hz, c->q32, c->compute))
+                    return rc;
+        }
         if (nchunk <= 1) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_x[buf], 0));
         if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::r0], c->compute));
         if (l > 0) {
@@ -465,6 +473,11 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     c->qx = (d->dtype & KVPR_X_INT4) != 0;
     c->qkv = (d->dtype & KVPR_KV_INT4) != 0;
     c->compute = (hipStream_t)compute_stream;
+    {
+        int dev = 0, khz = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+            c->wall_clock_hz = (double)khz * 1e3;
+    }
     const int slots = c->slots();
     c->nbuf = slots > 1 ? 2 : 1;
     const size_t x_bytes = (size_t)d->max_seq * c->x_row_halfs() * sizeof(half);
@@ -594,6 +607,14 @@ extern "C" int kvpr_set_adaptive(kvpr_ctx* c, double alpha) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
     if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(KVPR_E_RANGE, "alpha %g outside [0, 1]", alpha);
     c->adapt_alpha = alpha;
+    return KVPR_OK;
+}
+
+extern "C" int kvpr_set_keep_warm(kvpr_ctx* c, double fraction) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (!(fraction >= 0.0 && fraction <= 0.95)) return fail(KVPR_E_RANGE, "fraction %g outside [0, 0.95]", fraction);
+    if (fraction > 0.0 && !(c->wall_clock_hz > 0.0)) return fail(KVPR_E_STATE, "the device reports no wall clock rate");
+    c->keep_warm = fraction;
     return KVPR_OK;
 }
 

@@ -167,3 +167,103 @@ extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out
     *out = p;
     return KVPR_OK;
 }
+
+// ---- MFMA ceiling probe (debug hook, used by `bench.py --power-probe`) ----
+// A register-only loop of the recompute GEMM's MFMA (v_mfma_f32_32x32x16_f16, a 4 x 2 tile of accumulators per wave,
+// two k-steps of fragments) on operand fragments read once from a_dev / w_dev: no LDS, no memory traffic in the
+// loop.  Its rate on given data is what the chip's power limit leaves to any fp16 GEMM on that data.
+namespace {
+
+typedef _Float16 probe_half8 __attribute__((ext_vector_type(8)));
+typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(512) void mfma_loop_kernel(const _Float16* __restrict__ xa, const _Float16* __restrict__ xw,
+                                                         size_t n_a, size_t n_w, float* __restrict__ out, int iters) {
+    probe_half8 w[2][4], a[2][2];
+    const size_t t = (size_t)blockIdx.x * 512 + threadIdx.x;
+    for (int s = 0; s < 2; ++s) {
+        for (int i = 0; i < 4; ++i) w[s][i] = *reinterpret_cast<const probe_half8*>(xw + ((((t * 8 + s * 4 + i) * 8) % (n_w - 7)) & ~(size_t)7));
+        for (int j = 0; j < 2; ++j) a[s][j] = *reinterpret_cast<const probe_half8*>(xa + ((((t * 4 + s * 2 + j) * 8) % (n_a - 7)) & ~(size_t)7));
+    }
+    probe_floatx16 c[4][2];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j)
+            for (int r = 0; r < 16; ++r) c[i][j][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w[s][i], a[s][j], c[i][j], 0, 0, 0);
+    }
+    float sum = 0.f;
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j)
+            for (int r = 0; r < 16; ++r) sum += c[i][j][r];
+    out[t] = sum;
+}
+
+}  // namespace
+
+// a_dev / w_dev: float16 arrays of n_a / n_w elements (>= 8 each); out_dev: float32 [256 * 512]; flops = 256 * 8 * iters * 16 * 32768
+extern "C" int kvpr_debug_mfma_loop(const void* a_dev, const void* w_dev, int64_t n_a, int64_t n_w, void* out_dev, int iters, void* stream) {
+    if (!a_dev || !w_dev || !out_dev || n_a < 8 || n_w < 8 || iters < 1) return fail(KVPR_E_INVAL, "bad mfma loop arguments");
+    hipLaunchKernelGGL(mfma_loop_kernel, dim3(256), dim3(512), 0, (hipStream_t)stream, (const _Float16*)a_dev, (const _Float16*)w_dev,
+                       (size_t)n_a, (size_t)n_w, (float*)out_dev, iters);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+// ---- clock keep-alive (kvpr_set_keep_warm) ----
+// The same register-only MFMA loop, bounded by wall time: every wave leaves once `budget_ticks` of the constant-rate
+// wall clock have passed since it started, and after max_iters iterations at the latest.
+namespace {
+
+__global__ __launch_bounds__(512) void keep_warm_kernel(const _Float16* __restrict__ xw, size_t n_w, long long budget_ticks,
+                                                         int max_iters, float* __restrict__ sink) {
+    probe_half8 w[2][4], a[2][2];
+    const size_t t = (size_t)blockIdx.x * 512 + threadIdx.x;
+    for (int s = 0; s < 2; ++s) {
+        for (int i = 0; i < 4; ++i) w[s][i] = *reinterpret_cast<const probe_half8*>(xw + ((((t * 8 + s * 4 + i) * 8) % (n_w - 7)) & ~(size_t)7));
+        for (int j = 0; j < 2; ++j) a[s][j] = *reinterpret_cast<const probe_half8*>(xw + ((((t * 4 + s * 2 + j) * 8 + 4096) % (n_w - 7)) & ~(size_t)7));
+    }
+    probe_floatx16 c[4][2];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j)
+            for (int r = 0; r < 16; ++r) c[i][j][r] = 0.f;
+    const long long t0 = wall_clock64();
+    for (int it = 0; it < max_iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w[s][i], a[s][j], c[i][j], 0, 0, 0);
+        if ((it & 3) == 3 && wall_clock64() - t0 >= budget_ticks) break;
+    }
+    float sum = 0.f;
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j)
+            for (int r = 0; r < 16; ++r) sum += c[i][j][r];
+    if (sum == 12345.678f) sink[t & 255] = sum;     // keeps the loop alive; never true for these operands in practice
+}
+
+}  // namespace
+
+namespace kvpr {
+
+// w: any resident float16 array of n_w >= 8192 elements (a weight matrix); seconds of wall time to stay busy
+int launch_keep_warm(const void* w, size_t n_w, double seconds, double wall_clock_hz, void* sink, hipStream_t st) {
+    if (!w || n_w < 8192 || !(seconds > 0.0) || !(wall_clock_hz > 0.0)) return KVPR_OK;
+    const long long ticks = (long long)(seconds * wall_clock_hz);
+    // an iteration is 16 MFMAs per wave, two waves per SIMD: at least 1024 cycles, i.e. >= 0.4 us at any clock the chip runs;
+    // the iteration bound is a backstop of a few times the requested time
+    long long max_iters = (long long)(seconds / 0.4e-6) * 4 + 64;
+    if (max_iters > 2000000) max_iters = 2000000;
+    hipLaunchKernelGGL(keep_warm_kernel, dim3(256), dim3(512), 0, st, (const _Float16*)w, n_w, ticks, (int)max_iters, (float*)sink);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+}  // namespace kvpr

@@ -302,3 +302,42 @@ def test_adaptive_profile_tracks_the_measured_rates(k):
         assert e.value.code == k.KVPR_E_RANGE
     finally:
         rig.close()
+
+
+def test_keep_warm_changes_timing_but_not_results(k):
+    """The clock keep-alive puts a wall-time-bounded MFMA loop in front of the recompute GEMM: outputs are bit for bit
+    those without it, the GEMM starts no earlier than the requested busy time, and the loop ends by itself."""
+    rig = Rig(k, 21, 8, 512, 1024, 8)
+    try:
+        l = 384
+        base, _ = rig.decode(l)
+        assert rel_err(base, ko.layer_decode(rig.layer, l, rig.stored)["o"]) <= TIGHT
+        # a profile that claims a slow link (10 GB/s): X[0:384] = 6 MiB then "takes" 0.63 ms, of which 0.9 are kept busy
+        prof = k.make_profile(10e9, 1e15)
+        k.kvpr_set_profile(rig.ctx, prof, k.KVPR_COST_EQ10, 1)
+        # one-time costs (kernel loading, first touch) put multi-millisecond outliers into the first decodes of a process:
+        # every figure is the smallest of a few repeats
+        start_off = min(rig.decode(l, timing=True)[1].ms_recompute_start for _ in range(4))
+        k.kvpr_set_keep_warm(rig.ctx, 0.9)
+        starts = []
+        for rep in range(4):
+            print(f"keep-warm decode {rep}", flush=True)
+            got, t_on = rig.decode(l, timing=True)
+            assert np.array_equal(got, base)
+            starts.append(t_on.ms_recompute_start)
+        want_ms = 0.9 * l * 8 * 1024 * 2 / 10e9 * 1e3
+        print(f"recompute could start at {start_off:.3f} ms without, {min(starts):.3f} ms with (all: {starts}; "
+              f"requested busy time {want_ms:.3f} ms)", flush=True)
+        assert min(starts) >= want_ms                            # never earlier than asked
+        assert min(starts) <= want_ms + 0.5                      # the loop is bounded by wall time: it ended about when asked
+        k.kvpr_set_keep_warm(rig.ctx, 0.0)
+        back = []
+        for rep in range(3):
+            got, t_back = rig.decode(l, timing=True)
+            assert np.array_equal(got, base)
+            back.append(t_back.ms_recompute_start)
+        assert min(back) < want_ms
+        with pytest.raises(k.KvprError):
+            k.kvpr_set_keep_warm(rig.ctx, 1.5)
+    finally:
+        rig.close()
