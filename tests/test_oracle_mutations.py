@@ -286,3 +286,75 @@ def test_llama_unmutated_passes():
 @pytest.mark.parametrize("name,replace", LLAMA_MUTATIONS, ids=[m[0] for m in LLAMA_MUTATIONS])
 def test_llama_pins_catch(name, replace):
     assert not llama_pins_hold(_load(LLAMA, replace)), name
+
+
+# ---- greedy sampling step ----
+def greedy_pins_hold(ko) -> bool:
+    try:
+        hidden = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]])
+        W_lm = np.array([[1.0, 5.0, 5.0, 0.0], [2.0, 0.0, 7.0, 7.0]])
+        emb = np.array([[10.0, 11.0], [20.0, 21.0], [30.0, 31.0], [40.0, 41.0]])
+        tokens, logits, x_next = ko.greedy_next(hidden, W_lm, emb)
+        return bool(np.array_equal(logits, [[1, 5, 5, 0], [2, 0, 7, 7], [3, 5, 12, 7]]) and tokens.tolist() == [1, 2, 2]
+                    and np.array_equal(x_next, [[20, 21], [30, 31], [30, 31]]))
+    except Exception:
+        return False
+
+
+ORACLE = os.path.join(ROOT, "oracle", "kvpr_oracle.py")
+GREEDY_MUTATIONS = [
+    ("last maximum on ties", ("    tokens = np.argmax(logits, axis=-1)", "    tokens = logits.shape[-1] - 1 - np.argmax(logits[..., ::-1], axis=-1)")),
+    ("embedding row by batch index", ("_f64(emb)[tokens])", "_f64(emb)[: len(tokens)])")),
+    ("argmin", ("    tokens = np.argmax(logits, axis=-1)", "    tokens = np.argmin(logits, axis=-1)")),
+]
+
+
+def test_greedy_unmutated_passes():
+    assert greedy_pins_hold(_load(ORACLE))
+
+
+@pytest.mark.parametrize("name,replace", GREEDY_MUTATIONS, ids=[m[0] for m in GREEDY_MUTATIONS])
+def test_greedy_pins_catch(name, replace):
+    assert not greedy_pins_hold(_load(ORACLE, replace)), name
+
+
+# ---- wiring of the LLaMA-shaped decoder layer and stack, against the Hugging Face layer ----
+def llama_stack_pins_hold(lo) -> bool:
+    try:
+        import test_oracle_llama_hf as hf
+        cfg, layers = hf._hf_layers(2, 7)
+        b, s = 2, 9
+        hidden = torch.randn(b, s + 1, hf.H_DIM, dtype=torch.float64, generator=torch.Generator().manual_seed(8))
+        h1, h2 = hf._run_hf(cfg, layers, hidden)
+        with torch.no_grad():
+            x1 = layers[0].input_layernorm(hidden).numpy()
+            x2 = layers[1].input_layernorm(h1).numpy()
+        Ls = [hf._as_oracle_layer(layers[0], np.ascontiguousarray(np.swapaxes(x1[:, :s], 0, 1))),
+              hf._as_oracle_layer(layers[1], np.ascontiguousarray(np.swapaxes(x2[:, :s], 0, 1)))]
+        one, _ = lo.decoder_stack_decode(Ls[:1], hidden[:, s].numpy(), [4], None, "none", "none")
+        two, _ = lo.decoder_stack_decode(Ls, hidden[:, s].numpy(), [4, 9], None, "none", "none")
+        return hf._close(one, h1[:, s].numpy()) and hf._close(two, h2[:, s].numpy())
+    except Exception:
+        return False
+
+
+LLAMA_STACK_MUTATIONS = [
+    ("attention residual dropped", ('        x = rnd(x + rnd(r["o"]))', '        x = rnd(rnd(r["o"]))')),
+    ("FFN residual dropped", ('        x = rnd(x + rnd(project(f1, L["Wd"])))', '        x = rnd(rnd(project(f1, L["Wd"])))')),
+    ("attention input not normalised", ('        xn = rnd(rms_norm(x, L["ln1_g"]))', "        xn = rnd(x)")),
+    ("norm gains exchanged", ('        xn2 = rnd(rms_norm(x, L["ln2_g"]))', '        xn2 = rnd(rms_norm(x, L["ln1_g"]))')),
+    ("second norm taken before the attention residual", ('        x = rnd(x + rnd(r["o"]))\n        xn2 = rnd(rms_norm(x, L["ln2_g"]))',
+                                                         '        xn2 = rnd(rms_norm(x, L["ln2_g"]))\n        x = rnd(x + rnd(r["o"]))')),
+    ("post-norm: the norm applied to the sum", ('        x = rnd(x + rnd(r["o"]))', '        x = rnd(rms_norm(x + rnd(r["o"]), L["ln2_g"]))')),
+    ("every layer fed the stack input", ('        xn = rnd(rms_norm(x, L["ln1_g"]))', '        xn = rnd(rms_norm(_f64(x_in), L["ln1_g"]))')),
+    ("silu on the up branch", ("        f1 = rnd(silu(g) * u)", "        f1 = rnd(g * silu(u))")),
+]
+
+
+def test_llama_stack_unmutated_passes():
+    assert llama_stack_pins_hold(_load(LLAMA))
+
+
+@pytest.mark.parametrize("name,replace", LLAMA_STACK_MUTATIONS, ids=[m[0] for m in LLAMA_STACK_MUTATIONS])
+def test_llama_stack_pins_catch(name, replace):
+    assert not llama_stack_pins_hold(_load(LLAMA, replace)), name

@@ -62,3 +62,23 @@ def test_activation_rounding_mode_is_close():
     c, _ = ko.decoder_stack_decode([L, L], x, [2, 3], kv_round="fp16", act_round="fp16")
     assert np.max(np.abs(a - c)) <= 5e-3 * np.max(np.abs(a))
     assert not np.array_equal(a, c)
+
+
+def test_greedy_next_hand_values():
+    """Greedy sampling step (row argmax of hidden . W_lm, lowest index on ties, embedding row of the token): a hand case
+    with ties in two rows and a vocabulary wider than the hidden size, so that W_lm's orientation [h, vocab] is fixed."""
+    hidden = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]])
+    W_lm = np.array([[1.0, 5.0, 5.0, 0.0],
+                     [2.0, 0.0, 7.0, 7.0]])                         # [h = 2, vocab = 4]
+    emb = np.array([[10.0, 11.0], [20.0, 21.0], [30.0, 31.0], [40.0, 41.0]])
+    tokens, logits, x_next = ko.greedy_next(hidden, W_lm, emb)
+    assert np.array_equal(logits, [[1, 5, 5, 0], [2, 0, 7, 7], [3, 5, 12, 7]])
+    assert tokens.tolist() == [1, 2, 2]                             # rows 0 and 1 tie: the lower index wins
+    assert np.array_equal(x_next, [[20, 21], [30, 31], [30, 31]])
+    assert ko.greedy_next(hidden, W_lm)[2] is None
+    with pytest.raises(ValueError):
+        ko.greedy_next(hidden, W_lm.T)                              # [vocab, h] does not multiply a [b, h] hidden state
+    # float16 inputs are taken at their exact values: a logit gap of one float16 ulp decides the token
+    h16 = np.array([[1.0, 1.0]], dtype=np.float16)
+    w16 = np.array([[1.0, 1.0], [1.0, np.float16(1.0) + np.float16(2.0 ** -10)]], dtype=np.float16)
+    assert ko.greedy_next(h16, w16)[0].tolist() == [1]
