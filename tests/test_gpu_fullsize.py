@@ -173,6 +173,54 @@ def test_full_size_stack_two_layers_sampled_sequences(k):
         k.kvpr_destroy(ctx)
 
 
+def test_full_size_column_schedule_sampled_sequences(k):
+    """Column-by-column schedule with offloaded weights (Algorithm 1) at the paper's throughput shape: two OPT-13B-shaped
+    decoder layers (600 MiB of weights each in pinned memory) x two GPU batches of 32 sequences, context 1024.  Every GPU
+    batch is an independent set of sequences, so the oracle runs the two-layer stack for one sequence of each batch."""
+    (h, H, d), b, s, n_layers, nb = kvpr_inputs.SHAPES["opt-13b"], 32, 1024, 2, 2
+    ffn = 4 * h
+    ctx = k.kvpr_create_offload(n_layers, h, H, d, ffn, b, s + 2, nb)
+    try:
+        params, X, keep = [], {}, []
+        for j in range(n_layers):
+            P = kvpr_inputs.make_layer(950 + j, b, 1, h, H)               # weights of layer j
+            P.update(kvpr_inputs.make_ffn(950 + j, h, ffn))
+            params.append(P)
+            host = {
+                "wqkv": np.ascontiguousarray(np.concatenate([P["Wq"].T, P["Wk"].T, P["Wv"].T], 0)),
+                "bqkv": np.concatenate([P["bq"], P["bk"], P["bv"]]), "wo": np.ascontiguousarray(P["Wo"].T), "bo": P["bo"],
+                "w1": np.ascontiguousarray(P["W1"].T), "b1": P["b1"], "w2": np.ascontiguousarray(P["W2"].T), "b2": P["b2"],
+                "ln1_g": P["ln1_g"], "ln1_b": P["ln1_b"], "ln2_g": P["ln2_g"], "ln2_b": P["ln2_b"]}
+            host = {n: np.ascontiguousarray(a, dtype=np.float16) for n, a in host.items()}
+            keep.append(host)
+            k.kvpr_weights_write(ctx, j, k.make_weights(**host))
+            dv = {n: torch.from_numpy(a).cuda() for n, a in host.items()}  # device copy, for the prefill helper only
+            wdev = k.make_weights(**dv)
+            for q in range(nb):
+                X[j, q] = kvpr_inputs._draw(np.random.default_rng([950, j, q]), (s, b, h), 1.0)
+                k.kvpr_store_write(ctx, j * nb + q, 0, s, X[j, q], None)
+                k.kvpr_store_prefill_kv(ctx, j * nb + q, s, wdev)
+            del dv, wdev
+            torch.cuda.empty_cache()
+        x_in = kvpr_inputs._draw(np.random.default_rng(949), (nb, b, h), 1.0)
+        x_out = torch.empty((nb, b, h), dtype=torch.float16, device="cuda")
+        splits = [832, 0, 1024, 576]                                       # slot = layer * nb + batch
+        print("full-size column schedule", flush=True)
+        got_splits, tim = k.kvpr_decode_step_columns(ctx, s, n_layers * nb, torch.from_numpy(x_in).cuda(), x_out, splits, timing=True)
+        torch.cuda.synchronize()
+        assert got_splits == splits
+        got = x_out.cpu().numpy()
+        assert np.isfinite(got).all()
+        for q, n in ((0, 7), (1, 29)):
+            sub = [dict(params[j], X=np.ascontiguousarray(X[j, q][:, n:n + 1])) for j in range(n_layers)]
+            ref, _ = ko.decoder_stack_decode(sub, x_in[q, n:n + 1], [splits[j * nb + q] for j in range(n_layers)])
+            assert rel_err(got[q, n:n + 1], ref) <= 5e-3, (q, n)
+        # the first batch of layer 0 recomputes 832 positions: its GEMM is released by [Wk;Wv] (100 MiB), not by the 600 MiB blob
+        assert tim[0].weights_landed_valid and tim[0].ms_recompute_start < tim[0].ms_weights_landed
+    finally:
+        k.kvpr_destroy(ctx)
+
+
 def test_full_size_longest_context_sampled_sequences(k):
     """The longest context of the sweep: OPT-30B-shaped layer (hidden 7168, 56 heads), batch 16, context 4096
     (1.75 GiB of cache in the host store); whole sequences against the oracle at three splits."""
