@@ -145,14 +145,37 @@ int launch_t(const void* x, const void* w, const void* bias, void* y32, void* y1
     return KVPR_OK;
 }
 
-// tiles per workgroup: about one workgroup per CU (256), bounded by the LDS reduction buffer
-// (TPW * MT <= 8 keeps it at 64 KiB) and by the accumulator registers
+// Tiles per workgroup.  A launch runs in rounds of one workgroup per compute unit, and a round costs about its tiles
+// per workgroup plus a fixed part of one and a half tiles (first-load latency, x fragments, the reduction): the choice
+// minimises rounds x (tiles + 1.5) (ties: the wider workgroup), bounded by the LDS reduction buffer (TPW * MT <= 8 keeps it
+// at 64 KiB) and by the accumulator registers.  The model orders all 32 measured (shape, tiles per workgroup) pairs of
+// hidden 4096 / 7168, batch 32 correctly; e.g. q|k|v at hidden 7168 (1344 tiles): 3 per workgroup 85 us, 2: 95 us, 4: 110 us.
+int compute_units() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
+        else n = 256;
+    }
+    return n;
+}
+
 template <int MT>
 int launch_mt(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
               int out_f32_cols, int64_t ld16, int relu, hipStream_t st) {
     const int tiles = (N + 15) / 16;
-    int tpw = g_token_tpw > 0 ? g_token_tpw : (tiles + 255) / 256;
     const int cap = 8 / MT;
+    int tpw = g_token_tpw;
+    if (tpw <= 0) {
+        const int cus = compute_units();
+        long best = -1;
+        for (int t : {1, 2, 3, 4, 8}) {
+            if (t > cap) break;
+            const int grid = (tiles + t - 1) / t;
+            const long cost = (long)((grid + cus - 1) / cus) * (2 * t + 3);
+            if (best < 0 || cost <= best) { best = cost; tpw = t; }
+        }
+    }
     if (tpw > cap) tpw = cap;
     if (tpw >= 8) return launch_t<MT, (8 / MT >= 8 ? 8 : 1)>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
     if (tpw >= 4) return launch_t<MT, (8 / MT >= 4 ? 4 : 1)>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
