@@ -21,9 +21,10 @@
 // positions (plus, optionally, one extra position) from either the float16 buffer or the packed staging
 // buffer [position][batch][9h/8 bytes] and always leaves a partial (m, l, acc) in the workspace.  The
 // runtime launches it over the recomputed rows [0, l) and the new row as soon as they exist, and over the
-// packed rows [l, s) once they have landed: those are dequantised in registers (4 bytes of codes per lane
-// and half, value = float16(code * scale + mn) exactly as the standalone codec), so they are never
-// expanded in HBM.  One combine kernel merges all partials.
+// packed rows [l, s) once they have landed (attention_partial_packed: 16 bytes of K codes and 16 of V codes per
+// lane, dequantised in registers to float16(code * scale + mn) exactly as the standalone codec), so they are never
+// expanded in HBM.  One combine kernel merges all partials, or, when both phases run one workgroup per sequence
+// and column group, the second phase merges the first one's partial itself.
 #include "kvpr_internal.h"
 #include <math.h>
 #include <mutex>
@@ -32,6 +33,7 @@ namespace kvpr {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int COLS_PER_GROUP = 64 * 8;   // columns one wave covers
 
@@ -206,14 +208,13 @@ __device__ __forceinline__ bool merge_waves(float (*sm)[10][64], int wave, int l
     return true;
 }
 
-// Positions pos0 .. pos0 + n_pos - 1, then extra_pos if it is >= 0.  PACKED = false: rows of kv16 [*, batch, 2h]
-// float16.  PACKED = true: rows of kvq [*, batch, 9h/8] (h bytes of codes: K then V, then h/32 + h/32 (scale, mn)
-// float16 pairs, one per 64 columns).  Always writes partial slot split_base + blockIdx.z.
-template <int D, int UNROLL, int ATT_WAVES, bool PACKED>
+// Positions pos0 .. pos0 + n_pos - 1, then extra_pos if it is >= 0, rows of kv16 [*, batch, 2h] float16.  Writes partial
+// slot split_base + blockIdx.z, or (fuse_slot >= 0) merges the partial in that slot and writes z.
+template <int D, int UNROLL, int ATT_WAVES>
 __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_ranged(
-    const float* __restrict__ q, const _Float16* __restrict__ kv16, const uint8_t* __restrict__ kvq,
+    const float* __restrict__ q, const _Float16* __restrict__ kv16,
     float* __restrict__ ws_acc, float* __restrict__ ws_ml, int pos0, int n_pos, int extra_pos, int batch, int h,
-    int chunk, int split_base, float scale_log2) {
+    int chunk, int split_base, float scale_log2, int fuse_slot, _Float16* __restrict__ z) {
     const int cg = blockIdx.x, n = blockIdx.y, sp = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = cg * COLS_PER_GROUP + lane * 8;
@@ -231,43 +232,13 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_ranged(
     const int j1 = min(n_total, j0 + chunk);
     auto position = [&](int j) { return j < n_pos ? pos0 + j : extra_pos; };
 
-    // float16 source
     const int64_t row_stride = (int64_t)batch * 2 * h;
     const _Float16* kbase = kv16 + (int64_t)n * 2 * h + ccol;
-    // packed source: byte offsets inside a packed row of this sequence
-    const int64_t qrow_stride = (int64_t)batch * (h + h / 8);
-    const uint8_t* qbase = kvq + (int64_t)n * (h + h / 8);
-    const int k_code = ccol / 2, v_code = (h + ccol) / 2;
-    const int k_meta = h + (ccol / 64) * 4, v_meta = h + ((h + ccol) / 64) * 4;
-
     float m_run = -INFINITY, l_run = 0.f;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int j = j0 + wave * UNROLL; j < j1; j += ATT_WAVES * UNROLL) {
         float kf[UNROLL][8], vf[UNROLL][8];
-        if (PACKED) {
-            uint32_t kc[UNROLL], vc[UNROLL], km[UNROLL], vm[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint8_t* row = qbase + (int64_t)position(min(j + u, j1 - 1)) * qrow_stride;
-                kc[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + k_code));
-                vc[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + v_code));
-                km[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + k_meta));
-                vm[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + v_meta));
-            }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                union { uint32_t w; _Float16 hh[2]; } a, b;
-                a.w = km[u];
-                b.w = vm[u];
-                const float ks = (float)a.hh[0], kmn = (float)a.hh[1], vs = (float)b.hh[0], vmn = (float)b.hh[1];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    // the value the codec defines: float16(code * scale + mn)
-                    kf[u][e] = (float)(_Float16)((float)((kc[u] >> (4 * e)) & 15u) * ks + kmn);
-                    vf[u][e] = (float)(_Float16)((float)((vc[u] >> (4 * e)) & 15u) * vs + vmn);
-                }
-            }
-        } else {
+        {
             half8 kh[UNROLL], vh[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -309,6 +280,23 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_ranged(
     }
     __shared__ float sm[ATT_WAVES][10][64];
     if (!merge_waves<ATT_WAVES>(sm, wave, lane, m_run, l_run, acc) || !active) return;
+    if (fuse_slot >= 0) {
+        // this launch has one workgroup per (sequence, column group) and so has the earlier one whose partial sits in
+        // slot fuse_slot: merge the two here and write z, instead of a combine launch
+        const float* a = ws_acc + ((int64_t)fuse_slot * batch + n) * h + col;
+        const float2 ml = *reinterpret_cast<const float2*>(ws_ml + (((int64_t)fuse_slot * batch + n) * (h / 8) + col / 8) * 2);
+        const float4 a0 = *reinterpret_cast<const float4*>(a), a1 = *reinterpret_cast<const float4*>(a + 4);
+        const float m_tot = fmaxf(m_run, ml.x);
+        const float w_mine = (m_run == -INFINITY) ? 0.f : exp2f(m_run - m_tot);
+        const float w_prev = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m_tot);
+        const float inv = 1.f / (l_run * w_mine + ml.y * w_prev);
+        const float prev[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        half8 out;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = (_Float16)((acc[e] * w_mine + prev[e] * w_prev) * inv);
+        *reinterpret_cast<half8*>(z + (int64_t)n * h + col) = out;
+        return;
+    }
     const int slot = split_base + sp;
     float* a = ws_acc + ((int64_t)slot * batch + n) * h + col;
     *reinterpret_cast<float4*>(a) = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -317,13 +305,146 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_ranged(
     *reinterpret_cast<float2*>(ml) = make_float2(m_run, l_run);
 }
 
+// The value the 4-bit codec defines for one element: float16(code * scale + mn), code = nibble e of the code words
+__device__ __forceinline__ float dequant_nibble(uint32_t word, int e, float scale, float mn) {
+    return (float)(_Float16)((float)((word >> (4 * e)) & 15u) * scale + mn);
+}
+
+// Packed rows of kvq [*, batch, 9h/8] (h bytes of codes: K then V, then h/32 + h/32 (scale, mn) float16 pairs, one per
+// 64 columns), positions pos0 .. pos0 + n_pos - 1.  A lane owns 32 consecutive columns of one head: its K codes and its
+// V codes are 16 bytes each, so every wave load is one contiguous KiB of codes (2048 columns), dequantised in registers.
+// The first version read 4 bytes of codes per lane (256-byte segments) and reached 1.8 TB/s.
+template <int D, int ATT_WAVES>
+__global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_packed(
+    const float* __restrict__ q, const uint8_t* __restrict__ kvq, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
+    int pos0, int n_pos, int batch, int h, int chunk, int split_base, float scale_log2, int fuse_slot,
+    _Float16* __restrict__ z) {
+    constexpr int PU = 4;                                   // positions in flight per wave
+    const int cg = blockIdx.x, n = blockIdx.y, sp = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = cg * 2048 + lane * 32;
+    const bool active = col < h;
+    const int ccol = active ? col : 0;
+    float qf[32];
+#pragma unroll
+    for (int e = 0; e < 32; e += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(q + (int64_t)n * h + ccol + e);
+        qf[e] = v.x * scale_log2; qf[e + 1] = v.y * scale_log2; qf[e + 2] = v.z * scale_log2; qf[e + 3] = v.w * scale_log2;
+    }
+    const int j0 = sp * chunk;
+    const int j1 = min(n_pos, j0 + chunk);
+    const int64_t qrow_stride = (int64_t)batch * (h + h / 8);
+    const uint8_t* qbase = kvq + (int64_t)n * (h + h / 8);
+    const int k_code = ccol / 2, v_code = (h + ccol) / 2;
+    const int k_meta = h + (ccol / 64) * 4, v_meta = h + ((h + ccol) / 64) * 4;
+
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) acc[e] = 0.f;
+    for (int j = j0 + wave * PU; j < j1; j += ATT_WAVES * PU) {
+        uint4v kc[PU], vc[PU];
+        uint32_t km[PU], vm[PU];
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const uint8_t* row = qbase + (int64_t)(pos0 + min(j + u, j1 - 1)) * qrow_stride;   // tail slots re-read the last row, masked below
+            kc[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(row + k_code));
+            vc[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(row + v_code));
+            km[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + k_meta));
+            vm[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + v_meta));
+        }
+        float sc[PU];
+        float m_new = m_run;
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            union { uint32_t w; _Float16 hh[2]; } a;
+            a.w = km[u];
+            const float ks = (float)a.hh[0], kmn = (float)a.hh[1];
+            const uint32_t kw[4] = {kc[u][0], kc[u][1], kc[u][2], kc[u][3]};
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) d = fmaf(dequant_nibble(kw[e >> 3], e & 7, ks, kmn), qf[e], d);
+            // sum over the D/32 consecutive lanes of the head
+            d = dpp_xchg_add<0xB1>(d);
+            if (D == 128) d = dpp_xchg_add<0x4E>(d);
+            sc[u] = (j + u < j1) ? d : -INFINITY;
+            m_new = fmaxf(m_new, sc[u]);
+        }
+        const float rescale = exp2f(m_run - m_new);
+        l_run *= rescale;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) acc[e] *= rescale;
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            union { uint32_t w; _Float16 hh[2]; } b;
+            b.w = vm[u];
+            const float vs = (float)b.hh[0], vmn = (float)b.hh[1];
+            const uint32_t vw[4] = {vc[u][0], vc[u][1], vc[u][2], vc[u][3]};
+            const float p = exp2f(sc[u] - m_new);
+            l_run += p;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) acc[e] = fmaf(p, dequant_nibble(vw[e >> 3], e & 7, vs, vmn), acc[e]);
+        }
+        m_run = m_new;
+    }
+    // ---- merge the waves (wave 0 always has at least one position)
+    __shared__ float sm[ATT_WAVES][34][64];
+    sm[wave][0][lane] = m_run;
+    sm[wave][1][lane] = l_run;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) sm[wave][2 + e][lane] = acc[e];
+    __syncthreads();
+    if (wave != 0 || !active) return;
+    float m_tot = m_run;
+#pragma unroll
+    for (int w = 1; w < ATT_WAVES; ++w) m_tot = fmaxf(m_tot, sm[w][0][lane]);
+    float l_tot = 0.f;
+    float o[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) o[e] = 0.f;
+#pragma unroll
+    for (int w = 0; w < ATT_WAVES; ++w) {
+        const float mw = sm[w][0][lane];
+        const float wt = (mw == -INFINITY) ? 0.f : exp2f(mw - m_tot);
+        l_tot += sm[w][1][lane] * wt;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) o[e] += sm[w][2 + e][lane] * wt;
+    }
+    if (fuse_slot >= 0) {
+        // one workgroup per (sequence, column group) here and in the earlier float16 phase: merge its partial, write z
+        const float* a = ws_acc + ((int64_t)fuse_slot * batch + n) * h + col;
+        const float2 ml = *reinterpret_cast<const float2*>(ws_ml + (((int64_t)fuse_slot * batch + n) * (h / 8) + col / 8) * 2);
+        const float m_all = fmaxf(m_tot, ml.x);
+        const float w_mine = (m_tot == -INFINITY) ? 0.f : exp2f(m_tot - m_all);
+        const float w_prev = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m_all);
+        const float inv = 1.f / (l_tot * w_mine + ml.y * w_prev);
+#pragma unroll
+        for (int e = 0; e < 32; e += 8) {
+            const float4 a0 = *reinterpret_cast<const float4*>(a + e), a1 = *reinterpret_cast<const float4*>(a + e + 4);
+            const float prev[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            half8 out;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) out[t] = (_Float16)((o[e + t] * w_mine + prev[t] * w_prev) * inv);
+            *reinterpret_cast<half8*>(z + (int64_t)n * h + col + e) = out;
+        }
+        return;
+    }
+    const int slot = split_base + sp;
+    float* a = ws_acc + ((int64_t)slot * batch + n) * h + col;
+#pragma unroll
+    for (int e = 0; e < 32; e += 4) *reinterpret_cast<float4*>(a + e) = make_float4(o[e], o[e + 1], o[e + 2], o[e + 3]);
+    float* ml = ws_ml + (((int64_t)slot * batch + n) * (h / 8) + col / 8) * 2;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) *reinterpret_cast<float2*>(ml + 2 * g) = make_float2(m_tot, l_tot);   // one (m, l) per 8 columns
+}
+
 int g_attn_target_blocks = 256;   // one workgroup per CU: the fewest position splits that fill the chip
 int g_attn_cfg = 1;       // (unroll, waves per workgroup) choice, see launch_attention
 int g_attn_force_splits = 0;
 
 struct SplitPlan { int chunk, splits; };
-SplitPlan plan_splits(int batch, int hidden, int S) {
-    const int groups = (hidden + COLS_PER_GROUP - 1) / COLS_PER_GROUP;
+SplitPlan plan_splits(int batch, int hidden, int S, int cols_per_group = COLS_PER_GROUP) {
+    const int groups = (hidden + cols_per_group - 1) / cols_per_group;
     int64_t base = (int64_t)groups * batch;
     int want = g_attn_force_splits > 0 ? g_attn_force_splits : (int)((g_attn_target_blocks + base - 1) / base);
     const int max_splits = (S + 63) / 64;              // keep at least 64 positions per workgroup
@@ -401,11 +522,13 @@ int launch_attention(const void* q, const void* kv, void* z, void* ws, int S, in
 namespace {
 
 struct MixedPlan { SplitPlan a, b; int total; };
-MixedPlan plan_mixed(int batch, int hidden, int S, int split) {
+constexpr int PACKED_COLS_PER_GROUP = 64 * 32;   // columns one wave of the packed-row kernel covers
+
+MixedPlan plan_mixed(int batch, int hidden, int S, int split, bool packed) {
     MixedPlan p;
     p.a = plan_splits(batch, hidden, split + 1);                    // rows [0, split) and the new row
-    const int nb = S - 1 - split;                                   // packed rows
-    p.b = nb > 0 ? plan_splits(batch, hidden, nb) : SplitPlan{0, 0};
+    const int nb = S - 1 - split;                                   // transferred rows
+    p.b = nb > 0 ? plan_splits(batch, hidden, nb, packed ? PACKED_COLS_PER_GROUP : COLS_PER_GROUP) : SplitPlan{0, 0};
     auto cap = [](SplitPlan& sp, int n) {                           // 256 + 256 partial slots fit the workspace bound
         if (sp.splits > 256) { sp.chunk = (n + 255) / 256; sp.splits = (n + sp.chunk - 1) / sp.chunk; }
     };
@@ -415,20 +538,35 @@ MixedPlan plan_mixed(int batch, int hidden, int S, int split) {
     return p;
 }
 
-template <bool PACKED>
-int launch_ranged(const void* q, const void* kv16, const void* kvq, float* ws_acc, float* ws_ml, int pos0, int n_pos,
-                  int extra_pos, int batch, int hidden, int d, SplitPlan sp, int split_base, hipStream_t st) {
+int launch_ranged(const void* q, const void* kv16, float* ws_acc, float* ws_ml, int pos0, int n_pos,
+                  int extra_pos, int batch, int hidden, int d, SplitPlan sp, int split_base, hipStream_t st,
+                  int fuse_slot = -1, void* z = nullptr) {
     const int groups = (hidden + COLS_PER_GROUP - 1) / COLS_PER_GROUP;
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)d));
     dim3 grid(groups, batch, sp.splits);
     if (d == 128)
-        hipLaunchKernelGGL((attention_partial_ranged<128, 8, 4, PACKED>), grid, dim3(256), 0, st, (const float*)q,
-                           (const _Float16*)kv16, (const uint8_t*)kvq, ws_acc, ws_ml, pos0, n_pos, extra_pos, batch, hidden,
-                           sp.chunk, split_base, scale_log2);
+        hipLaunchKernelGGL((attention_partial_ranged<128, 8, 4>), grid, dim3(256), 0, st, (const float*)q,
+                           (const _Float16*)kv16, ws_acc, ws_ml, pos0, n_pos, extra_pos, batch, hidden,
+                           sp.chunk, split_base, scale_log2, fuse_slot, (_Float16*)z);
     else
-        hipLaunchKernelGGL((attention_partial_ranged<64, 8, 4, PACKED>), grid, dim3(256), 0, st, (const float*)q,
-                           (const _Float16*)kv16, (const uint8_t*)kvq, ws_acc, ws_ml, pos0, n_pos, extra_pos, batch, hidden,
-                           sp.chunk, split_base, scale_log2);
+        hipLaunchKernelGGL((attention_partial_ranged<64, 8, 4>), grid, dim3(256), 0, st, (const float*)q,
+                           (const _Float16*)kv16, ws_acc, ws_ml, pos0, n_pos, extra_pos, batch, hidden,
+                           sp.chunk, split_base, scale_log2, fuse_slot, (_Float16*)z);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+int launch_packed(const void* q, const void* kvq, float* ws_acc, float* ws_ml, int pos0, int n_pos, int batch, int hidden,
+                  int d, SplitPlan sp, int split_base, hipStream_t st, int fuse_slot, void* z) {
+    const int groups = (hidden + PACKED_COLS_PER_GROUP - 1) / PACKED_COLS_PER_GROUP;
+    const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)d));
+    dim3 grid(groups, batch, sp.splits);
+    if (d == 128)
+        hipLaunchKernelGGL((attention_partial_packed<128, 4>), grid, dim3(256), 0, st, (const float*)q, (const uint8_t*)kvq,
+                           ws_acc, ws_ml, pos0, n_pos, batch, hidden, sp.chunk, split_base, scale_log2, fuse_slot, (_Float16*)z);
+    else
+        hipLaunchKernelGGL((attention_partial_packed<64, 4>), grid, dim3(256), 0, st, (const float*)q, (const uint8_t*)kvq,
+                           ws_acc, ws_ml, pos0, n_pos, batch, hidden, sp.chunk, split_base, scale_log2, fuse_slot, (_Float16*)z);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }
@@ -441,17 +579,20 @@ int launch_ranged(const void* q, const void* kv16, const void* kvq, float* ws_ac
 int launch_attention_mixed(const void* q, const void* kv16, const void* kvq, void* z, void* ws, int S, int split, int batch,
                            int hidden, int n_heads, int phase, hipStream_t st) {
     const int d = hidden / n_heads;
-    const MixedPlan p = plan_mixed(batch, hidden, S, split);
+    const MixedPlan p = plan_mixed(batch, hidden, S, split, kvq != nullptr);
     float* ws_acc = (float*)ws;
     float* ws_ml = ws_acc + (int64_t)p.total * batch * hidden;
     if (phase == 0)
-        return launch_ranged<false>(q, kv16, kvq, ws_acc, ws_ml, 0, split, S - 1, batch, hidden, d, p.a, 0, st);
+        return launch_ranged(q, kv16, ws_acc, ws_ml, 0, split, S - 1, batch, hidden, d, p.a, 0, st);
+    // one workgroup per (sequence, column group) in both phases: the second phase merges the first one's partial itself
+    const bool fuse = p.a.splits == 1 && p.b.splits == 1;
     if (p.b.splits > 0)
-        if (int rc = kvq ? launch_ranged<true>(q, kv16, kvq, ws_acc, ws_ml, split, S - 1 - split, -1, batch, hidden, d, p.b,
-                                               p.a.splits, st)
-                         : launch_ranged<false>(q, kv16, kvq, ws_acc, ws_ml, split, S - 1 - split, -1, batch, hidden, d, p.b,
-                                                p.a.splits, st))
+        if (int rc = kvq ? launch_packed(q, kvq, ws_acc, ws_ml, split, S - 1 - split, batch, hidden, d, p.b, p.a.splits, st,
+                                         fuse ? 0 : -1, z)
+                         : launch_ranged(q, kv16, ws_acc, ws_ml, split, S - 1 - split, -1, batch, hidden, d, p.b, p.a.splits, st,
+                                         fuse ? 0 : -1, z))
             return rc;
+    if (fuse) return KVPR_OK;
     const int64_t threads = (int64_t)batch * (hidden / 8);
     hipLaunchKernelGGL(attention_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ws_acc, ws_ml,
                        (_Float16*)z, batch, hidden, p.total);
