@@ -198,6 +198,17 @@ int kvpr_store_prefill_kv(kvpr_ctx* ctx, int layer, int seq, const kvpr_layer_we
  * M = batch*seq (median of 5 after warm-up; the GEMM once alone and once under a concurrent copy).  Synchronises.  batch*seq must not exceed
  * the context's batch*max_seq. */
 int kvpr_profile(kvpr_ctx* ctx, int batch, int seq, kvpr_profile_t* out);
+/* Refinement of v_gpu (Sec. 3.1, Eq. 9) for a context that decodes one layer at a time (kvpr_layer_decode) with
+ * the GPU idle between steps: rehearses the copy / GEMM sequence of one step at the split that *prof plans with
+ * Eq. 10 (activation-sized pinned copy first, under the clock keep-alive if kvpr_set_keep_warm was given; then the
+ * recompute GEMM over batch*l rows of random operands while the rest of a cache-sized copy lands), four times with
+ * a full synchronisation in between, and replaces prof->gemm_flops_per_s by (flops as the cost model charges them)
+ * / (median GEMM time of the last three); re-plans once and repeats if the split moved.  No other field changes.
+ * A GPU that works in such bursts clocks the GEMM differently from the back-to-back launches kvpr_profile times.
+ * prof must hold positive h2d_bytes_per_s and gemm_flops_per_s.  Reads the first layer's host cache as copy source
+ * (contents irrelevant), overwrites device staging buffers, allocates and frees its own scratch, synchronises.
+ * KVPR_E_RANGE if batch or seq exceed the context's. */
+int kvpr_profile_step(kvpr_ctx* ctx, int batch, int seq, kvpr_profile_t* prof);
 
 /* Scheduler (Sec. 3.2, Eq. 6-11).  Pure host arithmetic, no context.  Evaluates the
  * cost for every l in {0, g, 2g, ...} U {seq} (g = granularity >= 1) in ascending order

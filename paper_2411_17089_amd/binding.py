@@ -75,6 +75,7 @@ _SIGS = {
     "kvpr_store_ptrs": (_i, [_vp, _i, C.POINTER(_vp), C.POINTER(_vp)]),
     "kvpr_store_prefill_kv": (_i, [_vp, _i, _i, C.POINTER(kvpr_layer_weights)]),
     "kvpr_profile": (_i, [_vp, _i, _i, C.POINTER(kvpr_profile_t)]),
+    "kvpr_profile_step": (_i, [_vp, _i, _i, C.POINTER(kvpr_profile_t)]),
     "kvpr_plan_split": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "kvpr_cost": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_double)]),
     "kvpr_set_chunks": (_i, [_vp, _i]),
@@ -178,6 +179,13 @@ def kvpr_store_prefill_kv(ctx, layer, seq, weights):
 def kvpr_profile(ctx, batch, seq) -> kvpr_profile_t:
     p = kvpr_profile_t()
     _check(lib.kvpr_profile(ctx, batch, seq, C.byref(p)))
+    return p
+
+
+def kvpr_profile_step(ctx, batch, seq, prof) -> kvpr_profile_t:
+    """Returns a copy of prof with gemm_flops_per_s as one single-layer decode step runs the GEMM."""
+    p = kvpr_profile_t.from_buffer_copy(prof)
+    _check(lib.kvpr_profile_step(ctx, batch, seq, C.byref(p)))
     return p
 
 

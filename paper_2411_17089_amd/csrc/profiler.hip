@@ -168,6 +168,95 @@ extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out
     return KVPR_OK;
 }
 
+// v_gpu as one decode step of one layer runs the GEMM (Eq. 9, Eq. 10): the step is rehearsed at the split the
+// profile plans.  X-sized copy first (the GPU idles, or runs the clock keep-alive if the context has one), then
+// the GEMM over batch*l rows while the rest of a cache-sized copy lands; full synchronisation between rehearsals,
+// as between steps.  A GPU that works in such bursts runs the GEMM at other clocks than in the back-to-back
+// launches kvpr_profile times, in both directions: lower out of a long idle stretch, higher while the board's
+// power average is low.
+extern "C" int kvpr_profile_step(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* prof) {
+    if (!c || !prof) return fail(KVPR_E_INVAL, "ctx / prof is null");
+    if (batch < 1 || seq < 1) return fail(KVPR_E_RANGE, "batch and seq must be >= 1");
+    if (batch > c->d.batch || seq > c->d.max_seq - 1)
+        return fail(KVPR_E_RANGE, "batch %d / seq %d exceed the context's %d / %d", batch, seq, c->d.batch, c->d.max_seq - 1);
+    if (!(prof->h2d_bytes_per_s > 0.0) || !(prof->gemm_flops_per_s > 0.0))
+        return fail(KVPR_E_INVAL, "prof needs positive h2d_bytes_per_s and gemm_flops_per_s (run kvpr_profile first)");
+    const int h = c->d.hidden;
+    // bytes and flops per position at this batch (the context's own per-position sizes are for its full batch)
+    const int64_t x_bpp = (int64_t)c->x_store_bytes() / c->d.batch * batch;
+    const int64_t kv_bpp = (int64_t)c->kv_store_bytes() / c->d.batch * batch;
+    const int64_t f_pp = 4 * (int64_t)batch * h * h;
+    const size_t kv_bytes = (size_t)seq * kv_bpp;
+
+    half* wtmp = nullptr;
+    void* dtmp = nullptr;
+    hipEvent_t go = nullptr, ev_x = nullptr, e0 = nullptr, e1 = nullptr;
+    int rc = KVPR_OK;
+    KVPR_HIP(hipDeviceSynchronize());
+    if (hipMalloc((void**)&wtmp, (size_t)2 * h * h * sizeof(half)) != hipSuccess) rc = fail(KVPR_E_NOMEM, "profiler weight buffer");
+    if (!rc && hipMalloc(&dtmp, kv_bytes) != hipSuccess) rc = fail(KVPR_E_NOMEM, "profiler copy target");
+    if (!rc && (hipEventCreate(&go) != hipSuccess || hipEventCreate(&ev_x) != hipSuccess || hipEventCreate(&e0) != hipSuccess ||
+                hipEventCreate(&e1) != hipSuccess))
+        rc = fail(KVPR_E_HIP, "profiler events");
+    if (!rc) rc = kvpr::launch_fill_random(wtmp, (size_t)2 * h * h, 0.035f, 1u, c->compute);
+    if (!rc) rc = kvpr::launch_fill_random(c->dx[0], (size_t)batch * seq * h, 1.7f, 2u, c->compute);
+
+    kvpr_profile_t p = *prof;
+    int32_t l_prev = -1;
+    for (int pass = 0; pass < 2 && !rc; ++pass) {
+        int32_t l = 0;
+        rc = kvpr_plan_split_linear(&p, KVPR_COST_EQ10, 1, seq, x_bpp, kv_bpp, f_pp, 64, &l, nullptr);
+        if (rc) break;
+        if (l < 64) l = seq >= 128 ? seq * 3 / 4 / 64 * 64 : seq;      // a plan without recomputation: rehearse a typical split
+        if (l == l_prev) break;
+        l_prev = l;
+        const size_t x_bytes = (size_t)l * x_bpp, rest_bytes = (size_t)(seq - l) * kv_bpp;
+        const int64_t rows = (int64_t)batch * l;
+        const double t_act = (double)x_bytes / p.h2d_bytes_per_s;
+        float ms[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < 4 && !rc; ++r) {
+            auto run = [&]() -> int {
+                KVPR_HIP(hipEventRecord(go, c->compute));
+                KVPR_HIP(hipStreamWaitEvent(c->copy, go, 0));
+                KVPR_HIP(hipMemcpyAsync(dtmp, c->hkv[0], x_bytes, hipMemcpyHostToDevice, c->copy));
+                KVPR_HIP(hipEventRecord(ev_x, c->copy));
+                if (rest_bytes)
+                    KVPR_HIP(hipMemcpyAsync((char*)dtmp + x_bytes, c->hkv[0] + x_bytes, rest_bytes, hipMemcpyHostToDevice, c->copy));
+                if (c->keep_warm > 0.0 && t_act * c->keep_warm > 200e-6)
+                    if (int q = kvpr::launch_keep_warm(wtmp, (size_t)2 * h * h, t_act * c->keep_warm, c->wall_clock_hz, c->q32, c->compute))
+                        return q;
+                KVPR_HIP(hipStreamWaitEvent(c->compute, ev_x, 0));
+                KVPR_HIP(hipEventRecord(e0, c->compute));
+                if (int q = c->llama ? kvpr::launch_gemm_rope(c->dx[0], wtmp, nullptr, c->dkv[0], rows, 2 * h, h, 2 * (int64_t)h, c->rope_tab,
+                                                              h, c->d.head_dim, batch, 0, c->compute)
+                                     : kvpr::launch_gemm(c->dx[0], wtmp, nullptr, c->dkv[0], rows, 2 * h, h, 2 * (int64_t)h, c->compute))
+                    return q;
+                KVPR_HIP(hipEventRecord(e1, c->compute));
+                KVPR_HIP(hipStreamSynchronize(c->compute));
+                KVPR_HIP(hipStreamSynchronize(c->copy));
+                KVPR_HIP(hipEventElapsedTime(&ms[r], e0, e1));
+                return KVPR_OK;
+            };
+            rc = run();
+        }
+        if (rc) break;
+        std::sort(ms + 1, ms + 4);                                       // the first rehearsal is the warm-up
+        int64_t flops = f_pp * l;                                        // charged as the cost model charges it
+        if (const int64_t q = p.gemm_round_flops; q > 0) flops = (flops + q - 1) / q * q;
+        if (ms[2] > 0.f) p.gemm_flops_per_s = (double)flops / ((double)ms[2] * 1e-3);
+    }
+    (void)hipDeviceSynchronize();
+    if (go) (void)hipEventDestroy(go);
+    if (ev_x) (void)hipEventDestroy(ev_x);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (dtmp) (void)hipFree(dtmp);
+    if (wtmp) (void)hipFree(wtmp);
+    if (rc) return rc;
+    prof->gemm_flops_per_s = p.gemm_flops_per_s;
+    return KVPR_OK;
+}
+
 // ---- MFMA ceiling probe (debug hook, used by `bench.py --power-probe`) ----
 // A register-only loop of the recompute GEMM's MFMA (v_mfma_f32_32x32x16_f16, a 4 x 2 tile of accumulators per wave,
 // two k-steps of fragments) on operand fragments read once from a_dev / w_dev: no LDS, no memory traffic in the

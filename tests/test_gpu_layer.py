@@ -264,6 +264,35 @@ def test_profile_reports_sane_rates(k):
             k.kvpr_destroy(ctx)
 
 
+def test_profile_step_refines_only_the_gemm_rate(k):
+    """The step rehearsal replaces v_gpu by a sane figure, leaves every other field alone, works with and without the
+    clock keep-alive, on both architectures and on a packed store, and refuses what it cannot measure."""
+    import ctypes
+    for arch, flags in ((k.KVPR_ARCH_OPT, 0), (k.KVPR_ARCH_LLAMA, 0), (k.KVPR_ARCH_OPT, k.KVPR_KV_INT4 | k.KVPR_X_INT4)):
+        ctx = k.kvpr_create(1, 1024, 8, 128, 0, 16, 1026, dtype=k.KVPR_F16 | flags, arch=arch)
+        try:
+            p = k.kvpr_profile(ctx, 16, 1024)
+            for frac in (0.0, 0.85):
+                k.kvpr_set_keep_warm(ctx, frac)
+                q = k.kvpr_profile_step(ctx, 16, 1024, p)
+                assert 0.3 * p.gemm_flops_per_s < q.gemm_flops_per_s < 2.6e15
+                a, b_ = bytearray(bytes(p)), bytearray(bytes(q))
+                off = type(p).gemm_flops_per_s.offset
+                a[off:off + 8] = b_[off:off + 8] = bytes(8)
+                assert a == b_
+            q = k.kvpr_profile_step(ctx, 3, 40, p)                   # below one granule: rehearsed at l = seq
+            assert 1e11 < q.gemm_flops_per_s < 2.6e15
+            for bad in ((17, 64), (16, 1026), (0, 64), (16, 0)):
+                with pytest.raises(k.KvprError) as e:
+                    k.kvpr_profile_step(ctx, bad[0], bad[1], p)
+                assert e.value.code == k.KVPR_E_RANGE
+            with pytest.raises(k.KvprError) as e:
+                k.kvpr_profile_step(ctx, 16, 1024, k.make_profile(0.0, 1e12))
+            assert e.value.code == k.KVPR_E_INVAL
+        finally:
+            k.kvpr_destroy(ctx)
+
+
 def test_adaptive_profile_tracks_the_measured_rates(k):
     """Start from a profile whose link rate is 3x too high: untimed decodes record probes, the planner folds them in
     and the estimate converges to what the copies actually achieve; results stay correct throughout."""
