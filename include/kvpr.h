@@ -289,7 +289,11 @@ int kvpr_timing_read(kvpr_ctx* ctx, int slot, kvpr_layer_timing* timing);
  * attention block, residual, LayerNorm, ReLU FFN (Eq. 4), residual), with the next
  * layer's transfers prefetched into the other device buffer while this layer computes
  * (Sec. 4 "Implementation": double buffering across decoder layers).
- * x_in_dev / x_out_dev [batch, hidden] hidden states; splits_in [n_layers] or null (= plan). */
+ * x_in_dev / x_out_dev [batch, hidden] hidden states; splits_in [n_layers] or null (= plan).
+ * Asynchronous, with bounded run-ahead: at most two steps of a context are in flight; a further call (this one or
+ * kvpr_decode_step_columns) first blocks the calling thread until the step before the previous one has finished on
+ * the GPU.  Deeper queues gain nothing and made steps slower (the runtime stalls the caller by itself, later and
+ * for longer). */
 int kvpr_decode_step(kvpr_ctx* ctx, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
                      void* x_out_dev, const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_layer);
 

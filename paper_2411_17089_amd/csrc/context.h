@@ -63,6 +63,10 @@ struct kvpr_ctx {
     bool free_recorded[2] = {false, false};
     hipEvent_t ev_buf_store[2]{};        // per device buffer: "the last store-back that read a row of this buffer is done"
     bool buf_store_recorded[2] = {false, false};
+    // whole-stack steps in flight: a step's end is recorded on the compute stream, and a new step first waits (on the
+    // host) for the end of the step before the previous one
+    hipEvent_t ev_step[2]{};
+    uint64_t steps_enqueued = 0;
     std::vector<LayerEvents> tev;        // lazily created timing events, one set per layer slot
     kvpr_profile_t prof{};
     bool have_prof = false;

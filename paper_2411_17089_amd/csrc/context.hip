@@ -364,6 +364,7 @@ void destroy_impl(kvpr_ctx* c) {
     if (c->store) (void)hipStreamSynchronize(c->store);
     (void)hipStreamSynchronize(c->compute);
     for (hipEvent_t e : c->ev_slot_store) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->ev_step) if (e) (void)hipEventDestroy(e);
     for (auto p : c->hx) if (p) (void)hipHostFree(p);
     for (auto p : c->hkv) if (p) (void)hipHostFree(p);
     for (int i = 0; i < 2; ++i) {
@@ -522,6 +523,9 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     if ((e = hipEventCreateWithFlags(&c->ev_proj, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
     if ((e = hipEventCreateWithFlags(&c->ev_store, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
     if ((e = hipEventCreateWithFlags(&c->ev_begin, hipEventDisableTiming)) != hipSuccess) return bail(KVPR_E_HIP, "event", e);
+    for (int i = 0; i < 2; ++i)
+        if ((e = hipEventCreateWithFlags(&c->ev_step[i], hipEventDisableTiming | hipEventBlockingSync)) != hipSuccess)
+            return bail(KVPR_E_HIP, "event", e);
     const size_t bh = (size_t)d->batch * d->hidden;
     if ((e = hipMalloc((void**)&c->q32, bh * sizeof(float))) != hipSuccess) return bail(KVPR_E_NOMEM, "q buffer", e);
     if ((e = hipMalloc((void**)&c->z16, bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "z buffer", e);
@@ -706,6 +710,23 @@ int residual_and_ffn(kvpr_ctx* c, const kvpr_layer_weights* w, const half* hid_i
 
 }  // namespace
 
+namespace {
+
+// Bound on the run-ahead of a caller that enqueues token after token without synchronising: at most two whole-stack
+// steps are in flight.  With more (a 40-layer step is ~2000 stream operations) the runtime itself stalls the host for
+// a second at a time and steps in a deep queue ran up to twice as long (measured: 290 -> 330-590 ms per token).
+int step_begin(kvpr_ctx* c) {
+    if (c->steps_enqueued >= 2) KVPR_HIP(hipEventSynchronize(c->ev_step[c->steps_enqueued & 1]));
+    return KVPR_OK;
+}
+int step_end(kvpr_ctx* c) {
+    KVPR_HIP(hipEventRecord(c->ev_step[c->steps_enqueued & 1], c->compute));
+    ++c->steps_enqueued;
+    return KVPR_OK;
+}
+
+}  // namespace
+
 extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* layers, const void* x_in_dev,
                                 void* x_out_dev, const int32_t* splits_in, int32_t* splits_out,
                                 kvpr_layer_timing* per_layer) {
@@ -722,6 +743,7 @@ extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* 
     }
     if (per_layer)
         if (int rc = ensure_timing_events(c, L)) return rc;
+    if (int rc = step_begin(c)) return rc;
     const size_t bh = (size_t)b * h;
     const half* hid_in = (const half*)x_in_dev;
     for (int i = 0; i < L; ++i) {
@@ -734,6 +756,7 @@ extern "C" int kvpr_decode_step(kvpr_ctx* c, int seq, const kvpr_layer_weights* 
         if (int rc = residual_and_ffn(c, w, hid_in, hid_out)) return rc;
         hid_in = hid_out;
     }
+    if (int rc = step_end(c)) return rc;
     if (splits_out) std::copy(ls.begin(), ls.end(), splits_out);
     if (per_layer) {
         KVPR_HIP(hipStreamSynchronize(c->compute));
@@ -802,6 +825,7 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
     }
     if (per_slot)
         if (int rc = ensure_timing_events(c, S)) return rc;
+    if (int rc = step_begin(c)) return rc;
     const BlobLayout BL(h, f, c->llama);
     const size_t bh = (size_t)b * h;
     const size_t kv_part = (BL.wo - BL.wkv) * sizeof(half);       // [Wk;Wv] rows, the q|k|v bias, the first norm's parameters
@@ -845,6 +869,7 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
         KVPR_HIP(hipEventRecord(c->ev_wfree[wb], c->compute));
         c->wfree_recorded[wb] = true;
     }
+    if (int rc = step_end(c)) return rc;
     if (splits_out) std::copy(ls.begin(), ls.end(), splits_out);
     if (per_slot) {
         KVPR_HIP(hipStreamSynchronize(c->compute));

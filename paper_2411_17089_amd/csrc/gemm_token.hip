@@ -7,11 +7,13 @@
 //   - a workgroup owns TPW tiles of 16 output features and all M rows of x; TPW is chosen so that the
 //     grid is about one workgroup per CU.  Its 8 waves split K in interleaved slabs of 128 columns,
 //     so the workgroup as a whole walks contiguous memory;
-//   - lanes read W straight from global memory into MFMA operand registers with non-temporal
-//     16-byte loads (each weight is used once).  In the instruction's own operand layout (lane = row
-//     r, k-chunk c) one load instruction covers 16 rows x one whole 64-byte segment, so every fetched
-//     segment is fully used (a lane-contiguous k permutation was 4x worse: each instruction then
-//     touched 64 segments for 16 bytes each);
+//   - lanes read W straight from global memory into MFMA operand registers with 16-byte loads.  In
+//     the instruction's own operand layout (lane = row r, k-chunk c) one load instruction covers 16
+//     rows x one whole 64-byte segment, so every fetched segment is fully used (a lane-contiguous k
+//     permutation was 4x worse: each instruction then touched 64 segments for 16 bytes each).  The
+//     loads are ordinary ones although each weight is used once: two consecutive instructions share
+//     every 128-byte line, and with non-temporal loads the second one often missed again (measured
+//     3-5 % slower at K = 4096, 13-15 % at K = 7168);
 //   - x is tiny (M*K halfs) and comes from L2; one x fragment is reused for the TPW weight tiles, so
 //     the L2->CU traffic for x stays below the HBM traffic for W (with one tile per workgroup it was
 //     twice the weight bytes and capped the kernel at 2.2 TB/s);
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(TG_WAVES * 64) void token_gemm(const _Float16* __re
         for (int p = 0; p < TPW; ++p)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                wf[p][j] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(wp[p] + k0 + j * 32));
+                wf[p][j] = *reinterpret_cast<const half8*>(wp[p] + k0 + j * 32);
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
