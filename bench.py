@@ -86,7 +86,8 @@ def run_stack(args):
     rnd = lambda shape, sc: (torch.randn(shape, device="cuda", dtype=torch.float32) * sc).half()
     t0 = time.perf_counter()
     qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
-    ctx = k.kvpr_create(L, h, H, d, ffn, b, s + gen + args.warmup + 2, dtype=k.KVPR_F16 | qflags,
+    also_pipe = cm == k.KVPR_COST_EQ10 and args.extension_chunks > 0
+    ctx = k.kvpr_create(L, h, H, d, ffn, b, s + (2 if also_pipe else 1) * (gen + args.warmup) + 3, dtype=k.KVPR_F16 | qflags,
                         arch=k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT)
     keep, ws = [], []
     for i in range(L):
@@ -153,8 +154,28 @@ def run_stack(args):
         "profile_at_end": {"v_com_GBps": k.kvpr_get_profile(ctx).h2d_bytes_per_s / 1e9,
                            "v_gpu_TFLOPs": k.kvpr_get_profile(ctx).gemm_flops_per_s / 1e12},
         "breakdown_ms_per_layer": breakdown, "host_enqueue_ms_per_token": host_s * 1e3 / gen,
-        "pinned_store_GiB": L * (s + gen + args.warmup + 2) * (x_bpp + kv_bpp) / 2 ** 30, "setup_s": setup_s,
+        "pinned_store_GiB": L * (s + (2 if also_pipe else 1) * (gen + args.warmup) + 3) * (x_bpp + kv_bpp) / 2 ** 30, "setup_s": setup_s,
     }
+    if also_pipe:
+        # extension, not the paper's objective: the steady-state cost form (a prefetching pipeline pays max(link, GPU) per
+        # layer, so it recomputes until the GPU is as busy as the link); same context, the generation simply goes on
+        seq += 1
+        k.kvpr_set_profile(ctx, prof, k.KVPR_COST_PIPE, args.granularity)
+        for _ in range(args.warmup):
+            one_token(seq, x)
+            seq += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pipe_splits = []
+        for _ in range(gen):
+            pipe_splits.append(one_token(seq, x)[0])
+            seq += 1
+        torch.cuda.synchronize()
+        wall_p = time.perf_counter() - t0
+        result["extension_steady_state_cost_form"] = {
+            "tokens_per_s": b * gen / wall_p, "ms_per_layer": wall_p * 1e3 / gen / L, "splits_first_last": [pipe_splits[0], pipe_splits[-1]],
+            "context_first_last": [seq - gen, seq - 1],
+            "note": "KVPR_COST_PIPE = max(link time, recompute + rest of the layer's GPU work); not in the paper"}
     k.kvpr_destroy(ctx)
     del keep, ws, w_lm, emb, logits
     torch.cuda.empty_cache()
@@ -800,6 +821,8 @@ def main():
                         "h2d_GBps_sustained": st["h2d_GBps_sustained"], "h2d_frac_of_peak": st["h2d_frac_of_peak"],
                         "breakdown_ms_per_layer": st["breakdown_ms_per_layer"], "host_enqueue_ms_per_token": st["host_enqueue_ms_per_token"],
                         "pinned_store_GiB": st["pinned_store_GiB"], "profile": st["profile"], "cost_model": st["config"]["cost_model"]})
+        if "extension_steady_state_cost_form" in st:
+            configs[-1]["extension_steady_state_cost_form"] = st["extension_steady_state_cost_form"]
     if "columns" not in skip:
         say("column-by-column schedule, OPT-13B shape, 8 layers x 4 GPU batches of 32, weights offloaded")
         ca = argparse.Namespace(**vars(args))

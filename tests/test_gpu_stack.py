@@ -119,6 +119,31 @@ def test_decode_step_two_tokens(k):
         st.close()
 
 
+def test_six_steps_enqueued_without_waiting_equal_six_waited_for(k):
+    """A caller that never synchronises between tokens (the library lets at most two steps of a context be in flight and
+    blocks the caller for the rest) gets bit for bit what a caller that waits after every step gets."""
+    n_layers, b, s, h, H, ffn = 3, 4, 40, 256, 2, 1024
+    rng = np.random.default_rng(3)
+    xs = [dev(kvpr_inputs._draw(rng, (b, h), 1.0)) for _ in range(6)]
+    splits = [[int(v) for v in rng.integers(0, s + t + 1, n_layers)] for t in range(6)]
+    outs = {}
+    for mode in ("waited", "free"):
+        st = Stack(k, n_layers, b, s, h, H, ffn, max_seq=s + 8)
+        try:
+            res = [torch.empty((b, h), dtype=torch.float16, device="cuda") for _ in range(6)]
+            for t in range(6):
+                k.kvpr_decode_step(st.ctx, s + t, st.w, xs[t], res[t], splits[t])
+                if mode == "waited":
+                    torch.cuda.synchronize()
+            torch.cuda.synchronize()
+            outs[mode] = [r.cpu().numpy() for r in res]
+        finally:
+            st.close()
+    for t in range(6):
+        assert np.isfinite(outs["free"][t].astype(np.float32)).all()
+        assert np.array_equal(outs["free"][t], outs["waited"][t]), t
+
+
 def test_decode_step_needs_ffn(k):
     ctx = k.kvpr_create(2, 256, 2, 128, 0, 2, 8)
     try:
