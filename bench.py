@@ -454,17 +454,34 @@ def run_layer(args, model, b, s, split_arg=-1, sweep=(), attention=True, extensi
     prof0 = k.kvpr_profile_step(ctx, b, s, prof_sustained)
     k.kvpr_set_profile(ctx, prof0, cm, args.granularity)
     k.kvpr_set_chunks(ctx, args.chunks)
-    # Refine the two constants in place: a few untimed decodes at the planned split with the run-time adaptation on.
-    # The GEMM inside the real pipeline (fresh activations, cache copy in flight, GPU coming out of an idle stretch)
-    # runs below its isolated rate on the wider shapes; the plan should use what the pipeline delivers.
+    # Refine the two constants: a few untimed decodes at the planned split, each timed by its own events and waited
+    # for; the link rate and the GEMM rate (flops as the cost model charges them) are the medians over these decodes.
+    # Medians, not the library's moving average (kvpr_set_adaptive): the first decodes on a fresh store find its pages
+    # still in the CPU's caches and single copies run at 30-45 GB/s, which a six-sample moving average does not forget.
     prof = prof0
+    trace = []
     if args.calibrate > 0 and split_arg < 0:
-        k.kvpr_set_adaptive(ctx, 0.5)
-        for _ in range(args.calibrate):
-            k.kvpr_layer_decode(ctx, 0, s, -1, w, x_new, out)
+        l_cal, _ = k.kvpr_plan_split_linear(prof0, cm, args.chunks if cm == k.KVPR_COST_EQ10 else 1, s, x_bpp, kv_bpp, f_pp, args.granularity)
+        for _ in range(2):
+            k.kvpr_layer_decode(ctx, 0, s, l_cal, w, x_new, out)
             torch.cuda.synchronize()
-        prof = k.kvpr_get_profile(ctx)
-        k.kvpr_set_adaptive(ctx, 0.0)
+        for i in range(args.calibrate):
+            k.kvpr_layer_decode_timed(ctx, 0, s, l_cal, w, x_new, out, i)
+            torch.cuda.synchronize()
+            t = k.kvpr_timing_read(ctx, i)
+            trace.append([t.ms_act_copy + t.ms_kv_copy, t.ms_recompute])
+        prof = k.kvpr_profile_t.from_buffer_copy(prof0)
+        link_ms = float(np.median([t[0] for t in trace]))
+        gemm_ms = float(np.median([t[1] for t in trace]))
+        if link_ms > 0:
+            prof.h2d_bytes_per_s = (x_bpp * l_cal + kv_bpp * (s - l_cal)) / (link_ms * 1e-3)
+        if l_cal > 0 and gemm_ms > 0 and args.chunks == 1:
+            flops = f_pp * l_cal
+            if prof0.gemm_round_flops > 0:
+                flops = -(-flops // prof0.gemm_round_flops) * prof0.gemm_round_flops
+            prof.gemm_flops_per_s = flops / (gemm_ms * 1e-3)
+        k.kvpr_set_profile(ctx, prof, cm, args.granularity)
+        trace = [[round(a, 3), round(g, 3)] for a, g in trace]
     pchunks = args.chunks if cm == k.KVPR_COST_EQ10 else 1
     # The split comes from the calibrated constants.  Every "bound" below is a cost model evaluated with the start-up
     # profile's constants (isolated copy rate, GEMM under a concurrent copy), so no ratio is measured against itself:
@@ -539,6 +556,7 @@ def run_layer(args, model, b, s, split_arg=-1, sweep=(), attention=True, extensi
                     "before_calibration": {"v_com_GBps": prof0.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof0.gemm_flops_per_s / 1e12,
                                            "v_gpu_back_to_back_under_copy_TFLOPs": prof_sustained.gemm_flops_per_s / 1e12},
                     "calibration_decodes": args.calibrate if split_arg < 0 else 0,
+                    "calibration_split": l_cal if trace else None, "calibration_link_ms_gemm_ms": trace,
                     "v_gpu_alone_TFLOPs": prof.gemm_alone_flops_per_s / 1e12, "h2d_peak_GBps": prof.h2d_peak_bytes_per_s / 1e9,
                     "d2h_GBps": prof.d2h_bytes_per_s / 1e9, "attn_GBps": prof.attn_bytes_per_s / 1e9},
         # means over the timed steps (what rocprofv3's average shows) and, beside them, medians: a step that a host
@@ -711,7 +729,8 @@ def compact(r):
          "assemble_over_plain_eq10_optimum": r["bounds"]["assemble_over_plain_eq10_optimum"],
          "plain_eq10_l_star": r["bounds"]["plain_eq10_l_star"], "ms_total_events_min_median_max": r["ms_total_events_min_median_max"],
          "profile": {"v_com_GBps": r["profile"]["v_com_GBps"], "v_gpu_TFLOPs": r["profile"]["v_gpu_TFLOPs"],
-                     "before_calibration": r["profile"]["before_calibration"]}}
+                     "before_calibration": r["profile"]["before_calibration"],
+                     "calibration_link_ms_gemm_ms": r["profile"]["calibration_link_ms_gemm_ms"]}}
     if "attention" in r:
         e["attention_frac_of_hbm_peak_as_in_layer"] = r["attention"]["as_in_layer"]["frac_of_hbm_peak"]
         e["attention_frac_of_hbm_peak_single_launch"] = r["attention"]["single_launch"]["frac_of_hbm_peak"]
@@ -754,7 +773,7 @@ def main():
     ap.add_argument("--adaptive", type=float, default=0.0,
                     help="(stack / columns modes) extension: keep adapting v_com / v_gpu while decoding with this moving-average weight")
     ap.add_argument("--calibrate", type=int, default=6,
-                    help="untimed decodes that refine the profiled v_com / v_gpu inside the real pipeline before planning (0 = plan from kvpr_profile alone)")
+                    help="untimed decodes whose median link and GEMM rates replace the profiled v_com / v_gpu before planning (0 = plan from the profiler alone)")
     ap.add_argument("--keep-warm", type=float, default=0.85,
                     help="extension: fraction of the predicted activation-copy time during which the otherwise idle GPU runs a "
                          "register-only MFMA loop, so that the recompute GEMM does not start with the clocks down (0 = off)")
