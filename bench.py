@@ -744,7 +744,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed decodes before the timed ones; the first two to three dozen decodes of a fresh context are disturbed "
+                         "(single copies and kernels several times slower, host calls of 10-30 ms).  Default 25; 2 tokens in --stack / --columns mode")
     ap.add_argument("--model", default=None,
                     help="opt-6.7b | opt-13b | opt-30b | llama2-7b | llama2-13b | tiny: run this one layer shape; default = every configuration")
     ap.add_argument("--batch", type=int, default=32)
@@ -781,6 +783,8 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=32)
     ap.add_argument("--skip", default="", help="(default run) comma list of parts to leave out: sweep, stack, columns")
     args = ap.parse_args()
+    if args.warmup is None:
+        args.warmup = 2 if (args.stack or args.columns) else 25
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
