@@ -325,6 +325,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
 
 int g_gemm_xcd_split_n = -1;   // -1 = default choice (debug hook; process-wide, set it only while no launch is in progress)
 
+// Which mapping of workgroups to tiles: measured on MI355X, giving every XCD a band of W wins once W no longer sits
+// comfortably in the memory-side cache next to the A panels in flight (N = 14336, K = 7168, 196 MiB), and loses 1-2 %
+// when W is small (64 MiB at K = 4096); equal at 100 MiB.
+bool band_mapping(int N, int K) {
+    if ((N + 255) / 256 < 8) return false;
+    if (g_gemm_xcd_split_n >= 0) return g_gemm_xcd_split_n != 0;
+    return (int64_t)N * K * 2 > ((int64_t)128 << 20);
+}
+
 template <int BM, int BN, int WM, int WN, int GROUP_M, int HD = 0>
 int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t M, int N, int K, int64_t ldc,
                 hipStream_t st, RopeArgs rope = RopeArgs{nullptr, 0, 1, 0}) {
@@ -340,12 +349,7 @@ int launch_tile(const void* a, const void* w, const void* bias, void* c, int64_t
     KVPR_HIP(configure_status);
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
     const int64_t total = (int64_t)tiles_m * tiles_n;
-    // Which mapping: measured on MI355X, giving every XCD a band of W wins once W no longer sits comfortably in the
-    // memory-side cache next to the A panels in flight (N = 14336, K = 7168, 196 MiB), and loses 1-2 % when W
-    // is small (64 MiB at K = 4096); equal at 100 MiB.
-    const bool big_w = (int64_t)N * K * 2 > ((int64_t)128 << 20);
-    int xcd_split_n = g_gemm_xcd_split_n >= 0 ? g_gemm_xcd_split_n : (big_w ? 1 : 0);
-    if (tiles_n < 8) xcd_split_n = 0;
+    const int xcd_split_n = band_mapping(N, K) ? 1 : 0;
     const int max_width = (tiles_n + 7) / 8;
     const int tiles_per_xcd = xcd_split_n ? max_width * tiles_m : (int)((total + 7) / 8);
     const unsigned grid = (unsigned)(tiles_per_xcd * 8);
@@ -366,7 +370,11 @@ int launch_gemm(const void* a, const void* w, const void* bias, void* c, int64_t
         case 1: return launch_tile<256, 256, 2, 4, 8>(a, w, bias, c, M, N, K, ldc, st);
         case 2: return launch_tile<256, 128, 2, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
         case 3: return launch_tile<128, 128, 2, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
-        default: return launch_tile<256, 256, 4, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
+        default:
+            // raster groups of 4 tile rows inside an XCD's band of W (7 tile columns at N = 14336: a 4 x 7 block is
+            // what 32 compute units cover), 8 with the row mapping: 1.5 % at M = 24576, N = 14336, K = 7168
+            return band_mapping(N, K) ? launch_tile<256, 256, 4, 2, 4>(a, w, bias, c, M, N, K, ldc, st)
+                                      : launch_tile<256, 256, 4, 2, 8>(a, w, bias, c, M, N, K, ldc, st);
     }
 }
 
