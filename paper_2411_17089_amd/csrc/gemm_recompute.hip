@@ -325,13 +325,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bias_f16(
 
 int g_gemm_xcd_split_n = -1;   // -1 = default choice (debug hook; process-wide, set it only while no launch is in progress)
 
-// Which mapping of workgroups to tiles: measured on MI355X, giving every XCD a band of W wins once W no longer sits
-// comfortably in the memory-side cache next to the A panels in flight (N = 14336, K = 7168, 196 MiB), and loses 1-2 %
-// when W is small (64 MiB at K = 4096); equal at 100 MiB.
+// Which mapping of workgroups to tiles: measured on MI355X at M = 24576-26624, giving every XCD a band of W wins once
+// W no longer sits comfortably in the memory-side cache next to the A panels in flight (+3.7 % at N = 10240, K = 5120,
+// 100 MiB; more at N = 14336, K = 7168, 196 MiB), and loses 1-2 % when W is small (64 MiB at K = 4096).
 bool band_mapping(int N, int K) {
     if ((N + 255) / 256 < 8) return false;
     if (g_gemm_xcd_split_n >= 0) return g_gemm_xcd_split_n != 0;
-    return (int64_t)N * K * 2 > ((int64_t)128 << 20);
+    return (int64_t)N * K * 2 > ((int64_t)80 << 20);
 }
 
 template <int BM, int BN, int WM, int WN, int GROUP_M, int HD = 0>
@@ -385,7 +385,8 @@ int launch_gemm_rope(const void* a, const void* w, const void* bias, void* c, in
     if (M == 0) return KVPR_OK;
     const RopeArgs r{(const float2*)table, rope_cols, batch, pos0};
     if (head_dim == 64) return launch_tile<256, 256, 4, 2, 8, 64>(a, w, bias, c, M, N, K, ldc, st, r);
-    return launch_tile<256, 256, 4, 2, 8, 128>(a, w, bias, c, M, N, K, ldc, st, r);
+    return band_mapping(N, K) ? launch_tile<256, 256, 4, 2, 4, 128>(a, w, bias, c, M, N, K, ldc, st, r)
+                              : launch_tile<256, 256, 4, 2, 8, 128>(a, w, bias, c, M, N, K, ldc, st, r);
 }
 
 }  // namespace kvpr
