@@ -665,6 +665,44 @@ def run_layer(args, model, b, s, split_arg=-1, sweep=(), attention=True, extensi
     return res
 
 
+def mfma_ceiling(seconds=1.5):
+    """What this box's power management lets the fp16 MFMA unit sustain on this kind of data: a register-only loop of the
+    GEMM's instruction (no LDS, no global traffic after the first loads) on N(0,1) x N(0,0.02) operands, in launches of
+    about the GEMM's length, back to back for `seconds` after a second of ramp."""
+    import ctypes as C
+    import torch
+    import paper_2411_17089_amd as k
+    k.lib.kvpr_debug_mfma_loop.restype = C.c_int
+    k.lib.kvpr_debug_mfma_loop.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]
+    g = torch.Generator(device="cuda").manual_seed(0)
+    a = torch.randn((1 << 22,), device="cuda", dtype=torch.float32, generator=g).half()
+    w = (torch.randn((1 << 22,), device="cuda", dtype=torch.float32, generator=g) * 0.02).half()
+    sink = torch.empty((256 * 512,), device="cuda", dtype=torch.float32)
+    stream = torch.cuda.current_stream().cuda_stream
+    iters = 6000
+    flops = 256 * 8 * iters * 16 * 32768.0
+    def launch():
+        rc = k.lib.kvpr_debug_mfma_loop(a.data_ptr(), w.data_ptr(), a.numel(), w.numel(), sink.data_ptr(), iters, stream)
+        if rc != 0:
+            raise RuntimeError("kvpr_debug_mfma_loop failed: %d" % rc)
+    t_end = time.perf_counter() + 1.0
+    while time.perf_counter() < t_end:
+        for _ in range(10):
+            launch()
+        torch.cuda.synchronize()
+    n, t0 = 0, time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            launch()
+        torch.cuda.synchronize()
+        n += 10
+    dt = time.perf_counter() - t0
+    return {"TFLOPs": flops * n / dt / 1e12, "frac_of_mfma_peak": flops * n / dt / 1e12 / PEAK_MFMA_F16_TFLOPS, "launches": n, "seconds": dt,
+            "what": "register-only loop of v_mfma_f32_32x32x16_f16 on N(0,1) x N(0,0.02) operands, 256 workgroups of 8 waves, "
+                    "back-to-back launches of about 4 ms: the rate the board's power management grants the MFMA unit "
+                    "with no data movement at all"}
+
+
 def headline(args, r):
     """The one-line record of the driver's contract, from the figures of one layer case."""
     pf = profile_figures(r["model"], r["batch"], r["context"])
@@ -781,7 +819,7 @@ def main():
                          "register-only MFMA loop, so that the recompute GEMM does not start with the clocks down (0 = off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
-    ap.add_argument("--skip", default="", help="(default run) comma list of parts to leave out: sweep, stack, columns")
+    ap.add_argument("--skip", default="", help="comma list of parts to leave out: ceiling; in the default run also sweep, stack, columns")
     args = ap.parse_args()
     if args.warmup is None:
         args.warmup = 2 if (args.stack or args.columns) else 25
@@ -811,7 +849,12 @@ def main():
     if args.model is not None:
         r = run_layer(args, args.model, args.batch, args.seq, args.split, attention=True, extension=True,
                       cpu=not args.no_cpu_baseline)
-        return print(json.dumps(headline(args, r)))
+        result = headline(args, r)
+        if "ceiling" not in args.skip.split(","):
+            ceil = mfma_ceiling()
+            result["roofline"]["power_limited_mfma_ceiling"] = ceil
+            result["roofline"]["achieved_over_power_limited_ceiling"] = result["roofline"]["achieved"] / ceil["TFLOPs"]
+        return print(json.dumps(result))
 
     # ---- default: every configuration the metric is quoted on, one JSON line ----
     skip = set(filter(None, args.skip.split(",")))
@@ -830,6 +873,11 @@ def main():
             say(f"OPT-30B shape, batch 16, context {s}")
             configs.append(compact(run_layer(args, "opt-30b", 16, s)))
     result = headline(args, c4)
+    if "ceiling" not in skip:
+        say("register-only MFMA loop (what the power limit grants on this data)")
+        ceil = mfma_ceiling()
+        result["roofline"]["power_limited_mfma_ceiling"] = ceil
+        result["roofline"]["achieved_over_power_limited_ceiling"] = result["roofline"]["achieved"] / ceil["TFLOPs"]
     if "cpu_baseline" in c2:
         result["cpu_baseline"] = c2["cpu_baseline"]
         result["cpu_baseline"]["note"] = ("timed on the OPT-6.7B-shaped layer (first entry of configs), not on the headline shape: the "
