@@ -497,8 +497,11 @@ def run_layer(args, model, b, s, split_arg=-1, sweep=(), attention=True, extensi
     l_eq10, t_eq10 = k.kvpr_plan_split_linear(prof0, k.KVPR_COST_EQ10, 1, s, x_bpp, kv_bpp, f_pp, args.granularity)
 
     def timed_at(split, steps):
-        for _ in range(args.warmup):
-            k.kvpr_layer_decode(ctx, 0, s, split, w, x_new, out)
+        # warm-up through the same entry point, timing slots and queue depth as the timed decodes: the runtime grows its
+        # pools (completion signals, timing events) the first time that many operations are in flight at once, and
+        # while it does, running copies and kernels take up to twice as long
+        for i in range(args.warmup):
+            k.kvpr_layer_decode_timed(ctx, 0, s, split, w, x_new, out, i % steps)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
@@ -784,7 +787,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=None,
                     help="untimed decodes before the timed ones; the first two to three dozen decodes of a fresh context are disturbed "
-                         "(single copies and kernels several times slower, host calls of 10-30 ms).  Default 25; 2 tokens in --stack / --columns mode")
+                         "(single copies and kernels several times slower, host calls of 10-30 ms).  Default max(25, steps); 2 tokens in --stack / --columns mode")
     ap.add_argument("--model", default=None,
                     help="opt-6.7b | opt-13b | opt-30b | llama2-7b | llama2-13b | tiny: run this one layer shape; default = every configuration")
     ap.add_argument("--batch", type=int, default=32)
@@ -822,7 +825,7 @@ def main():
     ap.add_argument("--skip", default="", help="comma list of parts to leave out: ceiling; in the default run also sweep, stack, columns")
     args = ap.parse_args()
     if args.warmup is None:
-        args.warmup = 2 if (args.stack or args.columns) else 25
+        args.warmup = 2 if (args.stack or args.columns) else max(25, args.steps)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)

@@ -205,8 +205,8 @@ int kvpr_profile(kvpr_ctx* ctx, int batch, int seq, kvpr_profile_t* out);
  * a full synchronisation in between, and replaces prof->gemm_flops_per_s by (flops as the cost model charges them)
  * / (median GEMM time of the last three); re-plans once and repeats if the split moved.  No other field changes.
  * A GPU that works in such bursts clocks the GEMM differently from the back-to-back launches kvpr_profile times.
- * prof must hold positive h2d_bytes_per_s and gemm_flops_per_s.  Reads the first layer's host cache as copy source
- * (contents irrelevant), overwrites device staging buffers, allocates and frees its own scratch, synchronises.
+ * prof must hold positive h2d_bytes_per_s and gemm_flops_per_s.  Reads the first layer's host activations and cache as
+ * copy sources (contents irrelevant), overwrites device staging buffers, allocates and frees its own scratch, synchronises.
  * KVPR_E_RANGE if batch or seq exceed the context's. */
 int kvpr_profile_step(kvpr_ctx* ctx, int batch, int seq, kvpr_profile_t* prof);
 

@@ -186,7 +186,8 @@ extern "C" int kvpr_profile_step(kvpr_ctx* c, int batch, int seq, kvpr_profile_t
     const int64_t x_bpp = (int64_t)c->x_store_bytes() / c->d.batch * batch;
     const int64_t kv_bpp = (int64_t)c->kv_store_bytes() / c->d.batch * batch;
     const int64_t f_pp = 4 * (int64_t)batch * h * h;
-    const size_t kv_bytes = (size_t)seq * kv_bpp;
+    // copy target: any split's X part and cache part side by side (X rows can be the larger ones when only the cache is packed)
+    const size_t kv_bytes = (size_t)seq * (size_t)std::max(x_bpp, kv_bpp);
 
     half* wtmp = nullptr;
     void* dtmp = nullptr;
@@ -218,10 +219,10 @@ extern "C" int kvpr_profile_step(kvpr_ctx* c, int batch, int seq, kvpr_profile_t
             auto run = [&]() -> int {
                 KVPR_HIP(hipEventRecord(go, c->compute));
                 KVPR_HIP(hipStreamWaitEvent(c->copy, go, 0));
-                KVPR_HIP(hipMemcpyAsync(dtmp, c->hkv[0], x_bytes, hipMemcpyHostToDevice, c->copy));
+                KVPR_HIP(hipMemcpyAsync(dtmp, c->hx[0], x_bytes, hipMemcpyHostToDevice, c->copy));
                 KVPR_HIP(hipEventRecord(ev_x, c->copy));
                 if (rest_bytes)
-                    KVPR_HIP(hipMemcpyAsync((char*)dtmp + x_bytes, c->hkv[0] + x_bytes, rest_bytes, hipMemcpyHostToDevice, c->copy));
+                    KVPR_HIP(hipMemcpyAsync((char*)dtmp + x_bytes, c->hkv[0] + (size_t)l * kv_bpp, rest_bytes, hipMemcpyHostToDevice, c->copy));
                 if (c->keep_warm > 0.0 && t_act * c->keep_warm > 200e-6)
                     if (int q = kvpr::launch_keep_warm(wtmp, (size_t)2 * h * h, t_act * c->keep_warm, c->wall_clock_hz, c->q32, c->compute))
                         return q;

@@ -268,7 +268,8 @@ def test_profile_step_refines_only_the_gemm_rate(k):
     """The step rehearsal replaces v_gpu by a sane figure, leaves every other field alone, works with and without the
     clock keep-alive, on both architectures and on a packed store, and refuses what it cannot measure."""
     import ctypes
-    for arch, flags in ((k.KVPR_ARCH_OPT, 0), (k.KVPR_ARCH_LLAMA, 0), (k.KVPR_ARCH_OPT, k.KVPR_KV_INT4 | k.KVPR_X_INT4)):
+    for arch, flags in ((k.KVPR_ARCH_OPT, 0), (k.KVPR_ARCH_LLAMA, 0), (k.KVPR_ARCH_OPT, k.KVPR_KV_INT4 | k.KVPR_X_INT4),
+                        (k.KVPR_ARCH_OPT, k.KVPR_KV_INT4)):     # cache-only packing: X rows are the larger ones
         ctx = k.kvpr_create(1, 1024, 8, 128, 0, 16, 1026, dtype=k.KVPR_F16 | flags, arch=arch)
         try:
             p = k.kvpr_profile(ctx, 16, 1024)
