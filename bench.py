@@ -786,8 +786,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=None,
-                    help="untimed decodes before the timed ones; the first two to three dozen decodes of a fresh context are disturbed "
-                         "(single copies and kernels several times slower, host calls of 10-30 ms).  Default max(25, steps); 2 tokens in --stack / --columns mode")
+                    help="untimed decodes before the timed ones, enqueued like them: the first burst of a given size makes the runtime grow its "
+                         "pools, and work running meanwhile takes up to twice as long.  Default max(25, steps); 2 tokens in --stack / --columns mode")
     ap.add_argument("--model", default=None,
                     help="opt-6.7b | opt-13b | opt-30b | llama2-7b | llama2-13b | tiny: run this one layer shape; default = every configuration")
     ap.add_argument("--batch", type=int, default=32)
