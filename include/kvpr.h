@@ -275,9 +275,9 @@ int kvpr_set_keep_warm(kvpr_ctx* ctx, double fraction);
  * x_new_dev [batch, hidden] is the decode token's attention input; out_dev [batch, hidden]
  * receives z . Wo^T + bo.  Side effects: rows `seq` of the layer's host X and KV are
  * written (store-back).  If timing is non-null the call synchronises and fills it.
- * Asynchronous otherwise.  Measured on MI355X: enqueue several decodes in one go (or use kvpr_decode_step, which does
- * that for a whole token); decodes fed to the streams one at a time while earlier ones are still running ran 22 %
- * slower per step, two at a time 5 %, eight at a time as fast as a single burst. */
+ * Asynchronous otherwise.  Measured on MI355X: decodes fed to the streams one at a time while earlier ones are still
+ * running run 3-6 % slower per step than decodes enqueued several at a time (or by kvpr_decode_step, which enqueues a
+ * whole token's layers in one go).  x_new_dev must be 16-byte aligned. */
 int kvpr_layer_decode(kvpr_ctx* ctx, int layer, int seq, int split, const kvpr_layer_weights* w,
                       const void* x_new_dev, void* out_dev, kvpr_layer_timing* timing);
 

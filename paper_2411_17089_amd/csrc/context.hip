@@ -178,13 +178,16 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
             if (int rc = kvpr::launch_quant_int4(x_new, x_stage + (size_t)seq * xsb, b, h, c->compute)) return rc;
         KVPR_HIP(hipEventRecord(c->ev_proj, c->compute));
         if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::p1], c->compute));
-        // store stream: write the new rows back to the host store
+        // store stream: write the new rows back to the host store.  A copy kernel writes them into the mapped pinned
+        // arrays: with hipMemcpyAsync device-to-host copies here, layer decodes fed to the streams one at a time while
+        // earlier ones ran had their host-to-device copies and the GEMM slowed down by up to 2x for steps at a time
+        // (22 % per step on average; 3-6 % with the kernel)
         KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_proj, 0));
         if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::s0], c->store));
-        KVPR_HIP(hipMemcpyAsync(c->hkv[layer] + (size_t)seq * ksb, kv_stage + (size_t)seq * ksb, ksb, hipMemcpyDeviceToHost,
-                                c->store));
-        KVPR_HIP(hipMemcpyAsync(c->hx[layer] + (size_t)seq * xsb, c->qx ? (const void*)(x_stage + (size_t)seq * xsb) : (const void*)x_new,
-                                xsb, hipMemcpyDeviceToHost, c->store));
+        if (int rc = kvpr::launch_copy_bytes(kv_stage + (size_t)seq * ksb, c->hkv[layer] + (size_t)seq * ksb, ksb, c->store)) return rc;
+        if (int rc = kvpr::launch_copy_bytes(c->qx ? (const void*)(x_stage + (size_t)seq * xsb) : (const void*)x_new,
+                                             c->hx[layer] + (size_t)seq * xsb, xsb, c->store))
+            return rc;
         KVPR_HIP(hipEventRecord(c->ev_store, c->store));
         KVPR_HIP(hipEventRecord(c->ev_slot_store[layer], c->store));
         c->slot_store_recorded[layer] = true;

@@ -1,5 +1,7 @@
 // Small memory-bound helpers around the attention block: LayerNorm, residual add, pattern fill.
 #include "kvpr_internal.h"
+#include <algorithm>
+#include <cstdint>
 #include <math.h>
 
 namespace kvpr {
@@ -191,6 +193,25 @@ int launch_fill_random(void* p, size_t n_halfs, float scale, uint32_t seed, hipS
 int launch_layernorm(const void* x, const void* g, const void* b, void* y, int rows, int h, hipStream_t st) {
     hipLaunchKernelGGL(layernorm_kernel, dim3(rows), dim3(256), 0, st, (const _Float16*)x, (const _Float16*)g,
                        (const _Float16*)b, (_Float16*)y, h, 1e-5f);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
+// plain byte copy (used for rows that go to mapped pinned host memory): 16-byte pieces, then the tail
+__global__ void copy_bytes_kernel(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst, size_t bytes) {
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const size_t n16 = bytes / 16;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        reinterpret_cast<u4*>(dst)[i] = reinterpret_cast<const u4*>(src)[i];
+    for (size_t i = n16 * 16 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < bytes; i += stride) dst[i] = src[i];
+}
+
+int launch_copy_bytes(const void* src, void* dst, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return KVPR_OK;
+    if (((uintptr_t)src | (uintptr_t)dst) & 15) return fail(KVPR_E_INVAL, "copy_bytes: pointers must be 16-byte aligned");
+    const unsigned grid = (unsigned)std::min<size_t>((bytes / 16 + 255) / 256 + 1, 256);
+    hipLaunchKernelGGL(copy_bytes_kernel, dim3(grid), dim3(256), 0, st, (const unsigned char*)src, (unsigned char*)dst, bytes);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }

@@ -42,6 +42,7 @@ size_t int4_row_bytes(int cols);
 int launch_quant_int4(const void* src, void* dst, int64_t rows, int cols, hipStream_t st);
 int launch_dequant_int4(const void* src, void* dst, int64_t rows, int cols, hipStream_t st);
 int launch_add(const void* a, const void* b, void* y, size_t n, hipStream_t st);
+int launch_copy_bytes(const void* src, void* dst, size_t bytes, hipStream_t st);
 int launch_keep_warm(const void* w, size_t n_w, double seconds, double wall_clock_hz, void* sink, hipStream_t st);
 
 }  // namespace kvpr
