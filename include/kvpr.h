@@ -146,7 +146,7 @@ typedef struct {
     float ms_proj;       /* new-token q/k/v projection (Eq. 1, Eq. 5)                  */
     float ms_attn;       /* decode attention (Eq. 2): both phases when it ran in two           */
     float ms_out;        /* output projection (Eq. 3)                                  */
-    float ms_store;      /* D2H of the new X / KV rows                                 */
+    float ms_store;      /* the new X / KV rows written into the pinned host store    */
     float ms_assemble;   /* first enqueue -> both KV halves resident: what Eq. 10 models */
     float ms_total;      /* first enqueue -> output projection and store-back done     */
     double t_bound_s;    /* cost-model prediction for the split used (0 if no profile) */
