@@ -198,7 +198,9 @@ def run_columns(args):
     rng = np.random.default_rng(0)
     torch.manual_seed(0)
     qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
-    ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + 2 * (gen + args.warmup) + 2, nb, dtype=k.KVPR_F16 | qflags,
+    also_pipe = cm == k.KVPR_COST_EQ10 and args.extension_chunks > 0
+    passes = 3 if also_pipe else 2
+    ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + passes * (gen + args.warmup) + 2, nb, dtype=k.KVPR_F16 | qflags,
                                 arch=k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT)
     rh = lambda shape, sc: (rng.standard_normal(shape, dtype=np.float32) * np.float32(sc)).astype(np.float16)
     t0 = time.perf_counter()
@@ -227,7 +229,12 @@ def run_columns(args):
     x_out = torch.empty_like(x)
     seq = s
     results = {}
-    for name, splits in (("kvpr", None), ("no_recompute", [0] * S)):
+    runs = [("kvpr", None), ("no_recompute", [0] * S)]
+    if also_pipe:
+        runs.append(("steady_state_cost_form", None))     # extension, not the paper's objective: see run_stack
+    for name, splits in runs:
+        if name == "steady_state_cost_form":
+            k.kvpr_set_profile(ctx, prof, k.KVPR_COST_PIPE, args.granularity)
         for _ in range(args.warmup):
             k.kvpr_decode_step_columns(ctx, seq, S, x, x_out, splits)
             seq += 1
@@ -253,8 +260,11 @@ def run_columns(args):
         "kvpr": r, "no_recompute": results["no_recompute"],
         "speedup_over_no_recompute": results["no_recompute"]["ms_per_token_step"] / r["ms_per_token_step"],
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12},
-        "pinned_GiB": (S * (s + 2 * (gen + args.warmup) + 2) * (x_bpp + kv_bpp) + L * blob_bytes) / 2 ** 30, "setup_s": setup_s,
+        "pinned_GiB": (S * (s + passes * (gen + args.warmup) + 2) * (x_bpp + kv_bpp) + L * blob_bytes) / 2 ** 30, "setup_s": setup_s,
     }
+    if also_pipe:
+        out["extension_steady_state_cost_form"] = dict(results["steady_state_cost_form"],
+            note="KVPR_COST_PIPE = max(link time, recompute + rest of the layer's GPU work); not in the paper")
     k.kvpr_destroy(ctx)
     del dev_w, wdev
     torch.cuda.empty_cache()
@@ -904,6 +914,8 @@ def main():
         co = run_columns(ca)
         configs.append({"workload": co["config"]["workload"], "tokens_per_s": co["value"], "kvpr": co["kvpr"],
                         "no_recompute": co["no_recompute"], "speedup_over_no_recompute": co["speedup_over_no_recompute"]})
+        if "extension_steady_state_cost_form" in co:
+            configs[-1]["extension_steady_state_cost_form"] = co["extension_steady_state_cost_form"]
     result["configs"] = configs
     result["bench_wall_s"] = time.perf_counter() - t_start
     print(json.dumps(result))
