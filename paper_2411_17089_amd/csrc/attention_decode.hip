@@ -562,10 +562,10 @@ int launch_packed(const void* q, const void* kvq, float* ws_acc, float* ws_ml, i
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)d));
     dim3 grid(groups, batch, sp.splits);
     if (d == 128)
-        hipLaunchKernelGGL((attention_partial_packed<128, 4>), grid, dim3(256), 0, st, (const float*)q, (const uint8_t*)kvq,
+        hipLaunchKernelGGL((attention_partial_packed<128, 8>), grid, dim3(512), 0, st, (const float*)q, (const uint8_t*)kvq,
                            ws_acc, ws_ml, pos0, n_pos, batch, hidden, sp.chunk, split_base, scale_log2, fuse_slot, (_Float16*)z);
     else
-        hipLaunchKernelGGL((attention_partial_packed<64, 4>), grid, dim3(256), 0, st, (const float*)q, (const uint8_t*)kvq,
+        hipLaunchKernelGGL((attention_partial_packed<64, 8>), grid, dim3(512), 0, st, (const float*)q, (const uint8_t*)kvq,
                            ws_acc, ws_ml, pos0, n_pos, batch, hidden, sp.chunk, split_base, scale_log2, fuse_slot, (_Float16*)z);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
