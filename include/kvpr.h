@@ -277,7 +277,7 @@ int kvpr_set_keep_warm(kvpr_ctx* ctx, double fraction);
  * written (store-back).  If timing is non-null the call synchronises and fills it.
  * Asynchronous otherwise.  Measured on MI355X: decodes fed to the streams one at a time while earlier ones are still
  * running run 3-6 % slower per step than decodes enqueued several at a time (or by kvpr_decode_step, which enqueues a
- * whole token's layers in one go).  x_new_dev must be 16-byte aligned. */
+ * whole token's layers in one go). */
 int kvpr_layer_decode(kvpr_ctx* ctx, int layer, int seq, int split, const kvpr_layer_weights* w,
                       const void* x_new_dev, void* out_dev, kvpr_layer_timing* timing);
 

@@ -197,21 +197,31 @@ int launch_layernorm(const void* x, const void* g, const void* b, void* y, int r
     return KVPR_OK;
 }
 
-// plain byte copy (used for rows that go to mapped pinned host memory): 16-byte pieces, then the tail
+// plain copy (used for rows that go to mapped pinned host memory) in pieces of sizeof(T) bytes, then the tail byte-wise
+template <class T>
 __global__ void copy_bytes_kernel(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst, size_t bytes) {
-    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-    const size_t n16 = bytes / 16;
+    const size_t n = bytes / sizeof(T);
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
-        reinterpret_cast<u4*>(dst)[i] = reinterpret_cast<const u4*>(src)[i];
-    for (size_t i = n16 * 16 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < bytes; i += stride) dst[i] = src[i];
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        reinterpret_cast<T*>(dst)[i] = reinterpret_cast<const T*>(src)[i];
+    for (size_t i = n * sizeof(T) + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < bytes; i += stride) dst[i] = src[i];
 }
 
 int launch_copy_bytes(const void* src, void* dst, size_t bytes, hipStream_t st) {
     if (bytes == 0) return KVPR_OK;
-    if (((uintptr_t)src | (uintptr_t)dst) & 15) return fail(KVPR_E_INVAL, "copy_bytes: pointers must be 16-byte aligned");
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u2 __attribute__((ext_vector_type(2)));
     const unsigned grid = (unsigned)std::min<size_t>((bytes / 16 + 255) / 256 + 1, 256);
-    hipLaunchKernelGGL(copy_bytes_kernel, dim3(grid), dim3(256), 0, st, (const unsigned char*)src, (unsigned char*)dst, bytes);
+    // widest piece both pointers are aligned to (packed 4-bit rows are multiples of 8 bytes, not always of 16)
+    const uintptr_t both = (uintptr_t)src | (uintptr_t)dst;
+    if ((both & 15) == 0)
+        hipLaunchKernelGGL(copy_bytes_kernel<u4>, dim3(grid), dim3(256), 0, st, (const unsigned char*)src, (unsigned char*)dst, bytes);
+    else if ((both & 7) == 0)
+        hipLaunchKernelGGL(copy_bytes_kernel<u2>, dim3(grid), dim3(256), 0, st, (const unsigned char*)src, (unsigned char*)dst, bytes);
+    else if ((both & 3) == 0)
+        hipLaunchKernelGGL(copy_bytes_kernel<unsigned int>, dim3(grid), dim3(256), 0, st, (const unsigned char*)src, (unsigned char*)dst, bytes);
+    else
+        hipLaunchKernelGGL(copy_bytes_kernel<unsigned char>, dim3(grid), dim3(256), 0, st, (const unsigned char*)src, (unsigned char*)dst, bytes);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }
