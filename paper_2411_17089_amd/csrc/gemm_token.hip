@@ -21,7 +21,16 @@
 //     buffering), so a wave always has one slab in flight; per-wave partial tiles are summed through LDS;
 //   - the epilogue adds the bias, optionally applies ReLU and writes float32 for the first
 //     `out_f32_cols` features (q) and float16 for the rest (k|v row of the cache, o, FFN).
+//
+// Second kernel for wide weight matrices (token_gemm_wide): once N is large enough for 128 (or 64) output features
+// per workgroup to give well over a hundred workgroups, a workgroup of 4 waves owns RB = 128 / 64 output features over
+// the whole of K.  Per 128 columns of K it brings in RB rows x 256 bytes of W and the M rows x 256 bytes of x by direct
+// global->LDS DMA (a wave instruction covers 4 rows x 256 contiguous bytes; x then costs M / RB of the weight bytes
+// instead of 2 / TPW), two stages in LDS, fragments read back in the MFMA operand layout (16-byte chunks of a row
+// XOR-swizzled by the row number on the global-address side so that the 16 rows of a fragment read hit 16 different
+// bank groups).  A wave owns RB / 4 output features for all of K: no cross-wave reduction.
 #include "kvpr_internal.h"
+#include <mutex>
 
 namespace kvpr {
 namespace {
@@ -134,7 +143,132 @@ __global__ __launch_bounds__(TG_WAVES * 64) void token_gemm(const _Float16* __re
     }
 }
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+constexpr int WIDE_KB = 128;                    // K columns per stage
+constexpr int WIDE_ROW_BYTES = WIDE_KB * 2;     // one LDS row of a stage
+
+template <int RB, int MT>
+__global__ __launch_bounds__(256) void token_gemm_wide(const _Float16* __restrict__ x, const _Float16* __restrict__ W,
+                                                       const _Float16* __restrict__ bias, float* __restrict__ y32,
+                                                       _Float16* __restrict__ y16, int M, int N, int K, int out_f32_cols,
+                                                       int64_t ld16, int relu) {
+    constexpr int RT = RB / 64;                             // 16-row tiles of W per wave
+    constexpr int WI = RB / 16;                             // W DMA instructions per wave and stage (4 rows each, 4 waves)
+    constexpr int WBYTES = RB * WIDE_ROW_BYTES, XBYTES = MT * 16 * WIDE_ROW_BYTES, STAGE = WBYTES + XBYTES;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n0 = blockIdx.x * RB;
+
+    // DMA sources.  Instruction q covers stage rows [4q, 4q+4); lane L lands at row 4q + L/16, physical 16-byte chunk L%16,
+    // and therefore fetches logical chunk (L%16) ^ (row%16).
+    const _Float16* srcw[WI];
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+        const int row = (wave + 4 * i) * 4 + (lane >> 4);
+        srcw[i] = W + (int64_t)min(n0 + row, N - 1) * K + (((lane & 15) ^ (row & 15)) << 3);
+    }
+    const _Float16* srcx[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const int row = (wave + 4 * i) * 4 + (lane >> 4);
+        srcx[i] = x + (int64_t)min(row, M - 1) * K + (((lane & 15) ^ (row & 15)) << 3);
+    }
+    auto issue = [&](int s, int buf) {
+        unsigned char* base = lds + buf * STAGE + wave * 1024;
+        const int k0 = s * WIDE_KB;
+#pragma unroll
+        for (int i = 0; i < WI; ++i)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(srcw[i] + k0), (lds_ptr_t)(base + i * 4096), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(srcx[i] + k0), (lds_ptr_t)(base + WBYTES + i * 4096), 16, 0, 0);
+    };
+
+    // fragment addresses: lane (r, c) of MFMA k-step j reads logical chunk 4j + c of row r of its tile
+    const int r = lane & 15, c = lane >> 4;
+    int foff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) foff[j] = r * WIDE_ROW_BYTES + (((4 * j + c) ^ r) << 4);   // every tile starts at a multiple of 16 rows
+
+    floatx4 acc[RT][MT];
+#pragma unroll
+    for (int p = 0; p < RT; ++p)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[p][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int stages = K / WIDE_KB;
+    issue(0, 0);
+    if (stages > 1) issue(1, 1);
+    for (int s = 0; s < stages; ++s) {
+        const int buf = s & 1;
+        // this wave's share of stage s has landed (stage s + 1 may still be in flight), then everybody's
+        if (s + 1 < stages) __builtin_amdgcn_s_waitcnt(0x0F70 | ((WI + MT) & 15) | (((WI + MT) >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+        const unsigned char* wb = lds + buf * STAGE + (wave * RT) * 16 * WIDE_ROW_BYTES;
+        const unsigned char* xb = lds + buf * STAGE + WBYTES;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            half8 wf[RT], xf[MT];
+#pragma unroll
+            for (int p = 0; p < RT; ++p) wf[p] = *reinterpret_cast<const half8*>(wb + p * 16 * WIDE_ROW_BYTES + foff[j]);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) xf[t] = *reinterpret_cast<const half8*>(xb + t * 16 * WIDE_ROW_BYTES + foff[j]);
+#pragma unroll
+            for (int p = 0; p < RT; ++p)
+#pragma unroll
+                for (int t = 0; t < MT; ++t) acc[p][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[p], xf[t], acc[p][t], 0, 0, 0);
+        }
+        if (s + 2 < stages) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): this wave has read what it needs of the buffer
+            __builtin_amdgcn_s_barrier();                // ... and so has everybody else: refill it
+            issue(s + 2, buf);
+        }
+    }
+
+    // element i of (tile p, m-tile t) in lane L is  n = n0 + 16*(wave*RT + p) + 4*(L/16) + i,  m = 16*t + L%16
+#pragma unroll
+    for (int p = 0; p < RT; ++p)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int n = n0 + 16 * (wave * RT + p) + 4 * c + i;
+                const int m = 16 * t + r;
+                if (n >= N || m >= M) continue;
+                float v = acc[p][t][i];
+                if (bias) v += (float)bias[n];
+                if (relu) v = fmaxf(v, 0.f);
+                if (n < out_f32_cols)
+                    y32[(int64_t)m * out_f32_cols + n] = v;
+                else
+                    y16[(int64_t)m * ld16 + (n - out_f32_cols)] = (_Float16)v;
+            }
+}
+
+template <int RB, int MT>
+int launch_wide(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
+                int out_f32_cols, int64_t ld16, int relu, hipStream_t st) {
+    auto kern = token_gemm_wide<RB, MT>;
+    constexpr int lds_bytes = 2 * (RB + MT * 16) * WIDE_ROW_BYTES;
+    static std::once_flag configured;
+    static hipError_t configure_status = hipSuccess;
+    std::call_once(configured, [&] {
+        configure_status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    });
+    KVPR_HIP(configure_status);
+    const unsigned grid = (unsigned)((N + RB - 1) / RB);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, (const _Float16*)x, (const _Float16*)w,
+                       (const _Float16*)bias, (float*)y32, (_Float16*)y16, M, N, K, out_f32_cols, ld16, relu);
+    KVPR_HIP(hipGetLastError());
+    return KVPR_OK;
+}
+
 int g_token_tpw = 0;   // 0 = choose from N; tests and sweeps can force 1..8
+int g_token_wide = -1; // -1 = choose from N; 0 = never, 64 / 128 = force that many features per workgroup (tests, sweeps)
 
 template <int MT, int TPW>
 int launch_t(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
@@ -165,6 +299,13 @@ int compute_units() {
 template <int MT>
 int launch_mt(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
               int out_f32_cols, int64_t ld16, int relu, hipStream_t st) {
+    // wide matrices: 128 (or 64) features per workgroup once that still gives about 150 workgroups
+    if (K % WIDE_KB == 0 && g_token_tpw <= 0) {
+        int rb = g_token_wide;
+        if (rb < 0) rb = (N + 127) / 128 >= 144 ? 128 : (N + 63) / 64 >= 144 ? 64 : 0;
+        if (rb == 128) return launch_wide<128, MT>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+        if (rb == 64) return launch_wide<64, MT>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+    }
     const int tiles = (N + 15) / 16;
     const int cap = 8 / MT;
     int tpw = g_token_tpw;
@@ -200,7 +341,11 @@ int launch_token_gemm_flags(const void* x, const void* w, const void* bias, void
 
 }  // namespace kvpr
 
+// v in 0..8: tiles per workgroup of the narrow kernel (0 = automatic choice of kernel and tiles);
+// v = 0x100 + rb (rb = 0, 64, 128): features per workgroup of the wide kernel (0 = narrow kernel only); v = -1: all automatic
 extern "C" int kvpr_debug_set_token_gemm_cfg(int v) {
+    if (v < 0) { kvpr::g_token_tpw = 0; kvpr::g_token_wide = -1; return KVPR_OK; }
+    if (v >= 0x100) { kvpr::g_token_tpw = 0; kvpr::g_token_wide = v - 0x100; return KVPR_OK; }
     kvpr::g_token_tpw = v;
     return KVPR_OK;
 }

@@ -119,10 +119,12 @@ def test_decode_attention_peaked_softmax(k):
 
 
 # ---- token GEMM (Eq. 1 / 3 / 5 for the decode token) ---------------------------
+# cfg: -1 = the library's own choice of kernel; 0x100 + 64 / 128 = the wide kernel with that many features per workgroup
+@pytest.mark.parametrize("cfg", [-1, 0x100 + 64, 0x100 + 128])
 @pytest.mark.parametrize("M,N,K,f32", [(1, 2304, 768, 768), (32, 768, 768, 0), (3, 96, 128, 32), (16, 520, 256, 8),
-                                       (33, 256, 384, 0), (64, 1056, 256, 256)])
-def test_token_gemm_matches_oracle(k, M, N, K, f32):
-    print(f"token gemm M={M} N={N} K={K} f32={f32}", flush=True)
+                                       (33, 256, 384, 0), (64, 1056, 256, 256), (48, 1300, 1152, 0)])
+def test_token_gemm_matches_oracle(k, M, N, K, f32, cfg):
+    print(f"token gemm M={M} N={N} K={K} f32={f32} cfg={cfg:#x}", flush=True)
     rng = np.random.default_rng(M + N)
     x = rng.standard_normal((M, K)).astype(np.float16)
     W = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
@@ -130,8 +132,12 @@ def test_token_gemm_matches_oracle(k, M, N, K, f32):
     ld16 = (N - f32) + 16
     y32 = torch.full((M, max(f32, 1)), float("nan"), dtype=torch.float32, device="cuda")
     y16 = torch.full((M, ld16), float("nan"), dtype=torch.float16, device="cuda")
-    k.kvpr_token_gemm(dev(x), dev(W), dev(bias), y32, y16, M, N, K, f32, ld16)
-    torch.cuda.synchronize()
+    k.lib.kvpr_debug_set_token_gemm_cfg(cfg)
+    try:
+        k.kvpr_token_gemm(dev(x), dev(W), dev(bias), y32, y16, M, N, K, f32, ld16)
+        torch.cuda.synchronize()
+    finally:
+        k.lib.kvpr_debug_set_token_gemm_cfg(-1)
     ref = ko.project(x, W.T, bias)
     if f32:
         assert rel_err(y32.cpu().numpy()[:, :f32], ref[:, :f32]) <= 1e-5
