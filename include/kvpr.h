@@ -372,6 +372,19 @@ int kvpr_decode_attention_mixed(const void* q_dev, const void* kv16_dev, const v
 int kvpr_token_gemm(const void* x_dev, const void* w_dev, const void* bias_dev, void* y32_dev, void* y16_dev,
                     int M, int N, int K, int out_f32_cols, int64_t ld16, void* stream);
 
+/* The same operation (Eq. 1 / 3 / 4 / 5 for the decode token) with a device workspace.  When the output has too few
+ * features to give every compute unit a block of them (the output projection and the FFN's second matrix: N = hidden),
+ * the sum over K is cut into up to 8 slices computed by different workgroups; the float32 partial tiles meet in the
+ * workspace and are added in slice order, so a given (shape, workspace size) always rounds the same way.
+ * ws_dev: 16-byte aligned device memory of ws_bytes, owned by the caller; kvpr_token_gemm_workspace_bytes(M, N) is
+ * enough for 8 slices (less workspace: fewer slices; null or at most 4096 bytes: exactly kvpr_token_gemm).  Its first
+ * 4096 bytes (arrival counters) must be zero before the first call and are zero again when a call has finished;
+ * calls that share a workspace must run one after the other (same stream, or ordered by events).
+ * kvpr_token_gemm_workspace_bytes returns 0 for M outside 1..64 or N < 1. */
+size_t kvpr_token_gemm_workspace_bytes(int M, int N);
+int kvpr_token_gemm_ws(const void* x_dev, const void* w_dev, const void* bias_dev, void* y32_dev, void* y16_dev,
+                       int M, int N, int K, int out_f32_cols, int64_t ld16, void* ws_dev, size_t ws_bytes, void* stream);
+
 /* ---- rotary models (KVPR_ARCH_LLAMA), exposed for parity tests ----
  * kvpr_rope_table: host arithmetic only.  out_host [n_pos, head_dim/2, 2] float32 = (cos, sin) of
  * p * base^(-2i/head_dim), evaluated in double.  head_dim 64 or 128.

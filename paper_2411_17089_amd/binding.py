@@ -101,6 +101,8 @@ _SIGS = {
     "kvpr_decode_attention_static": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "kvpr_decode_attention_mixed": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "kvpr_token_gemm": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _vp]),
+    "kvpr_token_gemm_workspace_bytes": (_sz, [_i, _i]),
+    "kvpr_token_gemm_ws": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _vp, _sz, _vp]),
     "kvpr_rope_table": (_i, [_vp, _i, _i, C.c_double]),
     "kvpr_recompute_gemm_rope": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i64, _vp, _i, _i, _i, _i, _i, _vp]),
     "kvpr_rope_token": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _i64, _vp]),
@@ -314,6 +316,15 @@ def kvpr_decode_attention_static(q_dev, kv_dev, z_dev, S, batch, hidden, n_heads
 def kvpr_token_gemm(x_dev, w_dev, bias_dev, y32_dev, y16_dev, M, N, K, out_f32_cols, ld16, stream=None):
     _check(lib.kvpr_token_gemm(_ptr(x_dev), _ptr(w_dev), _ptr(bias_dev), _ptr(y32_dev), _ptr(y16_dev), M, N, K,
                                out_f32_cols, ld16, _stream(stream)))
+
+
+def kvpr_token_gemm_workspace_bytes(M, N) -> int:
+    return lib.kvpr_token_gemm_workspace_bytes(M, N)
+
+
+def kvpr_token_gemm_ws(x_dev, w_dev, bias_dev, y32_dev, y16_dev, M, N, K, out_f32_cols, ld16, ws_dev, ws_bytes, stream=None):
+    _check(lib.kvpr_token_gemm_ws(_ptr(x_dev), _ptr(w_dev), _ptr(bias_dev), _ptr(y32_dev), _ptr(y16_dev), M, N, K,
+                                  out_f32_cols, ld16, _ptr(ws_dev), ws_bytes, _stream(stream)))
 
 
 def kvpr_int4_row_bytes(cols) -> int:

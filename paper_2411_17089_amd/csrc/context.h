@@ -43,6 +43,8 @@ struct kvpr_ctx {
     float* qk32 = nullptr;
     float2* rope_tab = nullptr;          // [max_seq][head_dim / 2]
     void* attn_ws = nullptr;
+    void* tok_ws = nullptr;              // token GEMM K-slice workspace (tickets, then partial tiles)
+    size_t tok_ws_bytes = 0;
     // hidden-state scratch of the full decoder layer
     half *hid = nullptr, *xn = nullptr, *attn_out = nullptr, *ffn1 = nullptr, *ffn2 = nullptr;
     // fences (timing disabled)

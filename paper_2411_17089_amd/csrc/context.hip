@@ -162,13 +162,13 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
         if (c->llama) {
             // q and k stay float32 until they are rotated with position seq; v goes straight into the cache row
             if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->qk32, dkv + (size_t)seq * kr + h, b, 3 * h, h,
-                                                       2 * h, 2 * (int64_t)h, 0, c->compute))
+                                                       2 * h, 2 * (int64_t)h, 0, c->compute, c->tok_ws, c->tok_ws_bytes))
                 return rc;
             if (int rc = kvpr::launch_rope_token(c->qk32, c->rope_tab, seq, b, h, c->d.head_dim, c->q32, dkv + (size_t)seq * kr,
                                                  2 * (int64_t)h, c->compute))
                 return rc;
         } else if (int rc = kvpr::launch_token_gemm_flags(x_new, w->wqkv, w->bqkv, c->q32, dkv + (size_t)seq * kr, b, 3 * h, h, h,
-                                                          2 * (int64_t)h, 0, c->compute)) {
+                                                          2 * (int64_t)h, 0, c->compute, c->tok_ws, c->tok_ws_bytes)) {
             return rc;
         }
         // a compressed store receives the new rows packed (Sec. 4.4); attention below still reads the exact row
@@ -265,7 +265,7 @@ int enqueue_layer(kvpr_ctx* c, int layer, int seq, int l, const kvpr_layer_weigh
     if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::a1], c->compute));
 
     // ---- output projection (Eq. 3) ----
-    if (int rc = kvpr::launch_token_gemm_flags(c->z16, w->wo, w->bo, nullptr, out, b, h, h, 0, h, 0, c->compute))
+    if (int rc = kvpr::launch_token_gemm_flags(c->z16, w->wo, w->bo, nullptr, out, b, h, h, 0, h, 0, c->compute, c->tok_ws, c->tok_ws_bytes))
         return rc;
     if (ev) KVPR_HIP(hipEventRecord(ev->at[LayerEvents::o1], c->compute));
     KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_store, 0));
@@ -388,7 +388,7 @@ void destroy_impl(kvpr_ctx* c) {
         for (hipEvent_t e : we) if (e) (void)hipEventDestroy(e);
     }
     if (c->wstream) (void)hipStreamDestroy(c->wstream);
-    void* dev[] = {c->qk32, c->rope_tab, c->q32, c->z16, c->attn_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2, c->dw[0], c->dw[1], c->hid_all};
+    void* dev[] = {c->qk32, c->rope_tab, c->q32, c->z16, c->attn_ws, c->tok_ws, c->hid, c->xn, c->attn_out, c->ffn1, c->ffn2, c->dw[0], c->dw[1], c->hid_all};
     for (void* p : dev) if (p) (void)hipFree(p);
     hipEvent_t evs[] = {c->ev_proj, c->ev_store, c->ev_begin};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
@@ -407,6 +407,69 @@ void destroy_impl(kvpr_ctx* c) {
 extern "C" const char* kvpr_last_error(void) { return kvpr::g_err; }
 
 namespace {
+
+// The runtime binds streams to a few hardware queues (four per process by default), the least used one first, and a
+// queue runs its packets in order.  When two streams share a queue, the marker that follows a long host-to-device copy
+// on one of them holds back whatever the other enqueues after it: measured on the column schedule, the recomputation of
+// a layer's first batch started 19 ms late, after the whole layer's weights instead of after [Wk;Wv], whenever the
+// compute stream happened to share its queue with the weight stream (which depends on how many streams the process made
+// before the context).  So every stream made here is checked against the streams it must run beside: a small kernel
+// on the one has to finish while a 0.4 ms kernel is still running on the other.  (A copy would be the more direct
+// blocker, but a lone copy at creation leaves both streams with the same preferred DMA engine, and the first step then
+// runs its activation copy behind the weights: measured.)  A stream that fails is replaced; the rejected ones stay
+// alive until the end so that the next one lands on another queue.  Best effort: after a few attempts the last stream
+// is kept as it is.
+int g_streams_replaced = 0;   // over the life of the process; read by tests through kvpr_debug_streams_replaced
+int settle_streams(kvpr_ctx* c) {
+    // the blocker: a register-only loop that runs for 0.4 ms of wall clock (bounded by an iteration count as well)
+    const half* blk = (const half*)((char*)c->tok_ws + 4096);               // the partial-tile area: scratch, any contents
+    const size_t blk_n = (c->tok_ws_bytes - 4096) / sizeof(half);
+    if (!c->tok_ws || blk_n < 8192 || !(c->wall_clock_hz > 0.0)) return KVPR_OK;
+    hipEvent_t e_busy = nullptr, e_probe = nullptr;
+    KVPR_HIP(hipEventCreateWithFlags(&e_busy, hipEventDisableTiming));
+    KVPR_HIP(hipEventCreateWithFlags(&e_probe, hipEventDisableTiming));
+    std::vector<hipStream_t> rejected;
+    // held: a small kernel on `probe` did not finish before the blocker running on `busy` did
+    auto held_back = [&](hipStream_t busy, hipStream_t probe, bool* held) -> int {
+        // first use binds a stream to its queue, which takes longer than the blocker runs: do that before the measurement
+        for (hipStream_t st : {busy, probe}) {
+            if (int rc = kvpr::launch_fill_u16(c->z16, 64, 0, st)) return rc;
+            KVPR_HIP(hipStreamSynchronize(st));
+        }
+        if (int rc = kvpr::launch_keep_warm(blk, blk_n, 0.4e-3, c->wall_clock_hz, c->q32, busy)) return rc;
+        KVPR_HIP(hipEventRecord(e_busy, busy));
+        if (int rc = kvpr::launch_fill_u16(c->z16, 64, 0, probe)) return rc;
+        KVPR_HIP(hipEventRecord(e_probe, probe));
+        KVPR_HIP(hipEventSynchronize(e_probe));
+        *held = hipEventQuery(e_busy) == hipSuccess;
+        (void)hipGetLastError();                                             // "not ready" is the good answer here
+        KVPR_HIP(hipEventSynchronize(e_busy));
+        return KVPR_OK;
+    };
+    // `mine` carries copies (or, for the store stream, must not queue behind them): none of `beside` may share its queue
+    auto settle = [&](hipStream_t* mine, bool mine_is_busy_side, std::initializer_list<hipStream_t> beside) -> int {
+        for (int attempt = 0; attempt < 6; ++attempt) {
+            bool shared = false;
+            for (hipStream_t other : beside) {
+                bool held = false;
+                if (int rc = mine_is_busy_side ? held_back(*mine, other, &held) : held_back(other, *mine, &held)) return rc;
+                shared = shared || held;
+            }
+            if (!shared || attempt == 5) break;
+            rejected.push_back(*mine);
+            ++g_streams_replaced;
+            KVPR_HIP(hipStreamCreateWithFlags(mine, hipStreamNonBlocking));
+        }
+        return KVPR_OK;
+    };
+    int rc = settle(&c->copy, true, {c->compute});
+    if (!rc && c->wstream) rc = settle(&c->wstream, true, {c->compute, c->copy});
+    if (!rc) rc = c->wstream ? settle(&c->store, false, {c->copy, c->wstream}) : settle(&c->store, false, {c->copy});
+    for (hipStream_t st : rejected) (void)hipStreamDestroy(st);
+    (void)hipEventDestroy(e_busy);
+    (void)hipEventDestroy(e_probe);
+    return rc;
+}
 
 // element offsets (in halfs) of one layer's parameters inside a weight blob; the host (pinned) and
 // device blobs share the layout so that a range of the blob is one contiguous copy.  [Wk;Wv], the
@@ -534,6 +597,11 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     if ((e = hipMalloc((void**)&c->z16, bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "z buffer", e);
     if ((e = hipMalloc(&c->attn_ws, kvpr::attention_workspace_bytes(d->batch, d->hidden, d->n_heads, d->max_seq))) != hipSuccess)
         return bail(KVPR_E_NOMEM, "attention workspace", e);
+    // K-slice partials of the token GEMMs with few output features (output projection, FFN down); its arrival
+    // counters start at zero and every launch leaves them at zero
+    c->tok_ws_bytes = kvpr::token_gemm_workspace_bytes(d->batch, d->hidden);
+    if ((e = hipMalloc(&c->tok_ws, c->tok_ws_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "token GEMM workspace", e);
+    if ((e = hipMemset(c->tok_ws, 0, 4096)) != hipSuccess) return bail(KVPR_E_HIP, "token GEMM workspace", e);
     if (c->llama) {
         if ((e = hipMalloc((void**)&c->qk32, 2 * bh * sizeof(float))) != hipSuccess) return bail(KVPR_E_NOMEM, "q|k buffer", e);
         // (cos, sin)(p * theta_i), theta_i = base^(-2i/d): evaluated in double on the host, stored as float
@@ -570,11 +638,17 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
         }
         if ((e = hipMalloc((void**)&c->hid_all, (size_t)c->nb * bh * sizeof(half))) != hipSuccess) return bail(KVPR_E_NOMEM, "hidden states", e);
     }
+    if (int rc = settle_streams(c)) {
+        destroy_impl(c);
+        return rc;
+    }
     *out = c;
     return KVPR_OK;
 }
 
 }  // namespace
+
+extern "C" int kvpr_debug_streams_replaced(void) { return g_streams_replaced; }
 
 extern "C" int kvpr_destroy(kvpr_ctx* c) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
@@ -700,13 +774,13 @@ int residual_and_ffn(kvpr_ctx* c, const kvpr_layer_weights* w, const half* hid_i
     if (c->llama) {
         half* prod = c->ffn1 + (size_t)b * 2 * f;
         if (int rc = kvpr::launch_rmsnorm(c->ffn2, w->ln2_g, c->xn, b, h, c->compute)) return rc;
-        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, nullptr, nullptr, c->ffn1, b, 2 * f, h, 0, 2 * (int64_t)f, 0, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, nullptr, nullptr, c->ffn1, b, 2 * f, h, 0, 2 * (int64_t)f, 0, c->compute, c->tok_ws, c->tok_ws_bytes)) return rc;
         if (int rc = kvpr::launch_silu_mul(c->ffn1, prod, b, f, c->compute)) return rc;
-        if (int rc = kvpr::launch_token_gemm_flags(prod, w->w2, nullptr, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(prod, w->w2, nullptr, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute, c->tok_ws, c->tok_ws_bytes)) return rc;
     } else {
         if (int rc = kvpr::launch_layernorm(c->ffn2, w->ln2_g, w->ln2_b, c->xn, b, h, c->compute)) return rc;
-        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, w->b1, nullptr, c->ffn1, b, f, h, 0, f, 1, c->compute)) return rc;
-        if (int rc = kvpr::launch_token_gemm_flags(c->ffn1, w->w2, w->b2, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->xn, w->w1, w->b1, nullptr, c->ffn1, b, f, h, 0, f, 1, c->compute, c->tok_ws, c->tok_ws_bytes)) return rc;
+        if (int rc = kvpr::launch_token_gemm_flags(c->ffn1, w->w2, w->b2, nullptr, c->attn_out, b, h, f, 0, h, 0, c->compute, c->tok_ws, c->tok_ws_bytes)) return rc;
     }
     return kvpr::launch_add(c->ffn2, c->attn_out, hid_out, bh, c->compute);
 }

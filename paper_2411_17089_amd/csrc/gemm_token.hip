@@ -147,13 +147,14 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
 constexpr int WIDE_KB = 128;                    // K columns per stage
+constexpr size_t TOKEN_WS_TICKET_BYTES = 4096;  // head of the workspace: one arrival counter per block of output features
 constexpr int WIDE_ROW_BYTES = WIDE_KB * 2;     // one LDS row of a stage
 
 template <int RB, int MT>
 __global__ __launch_bounds__(256) void token_gemm_wide(const _Float16* __restrict__ x, const _Float16* __restrict__ W,
                                                        const _Float16* __restrict__ bias, float* __restrict__ y32,
                                                        _Float16* __restrict__ y16, int M, int N, int K, int out_f32_cols,
-                                                       int64_t ld16, int relu) {
+                                                       int64_t ld16, int relu, float* part, unsigned* ticket) {
     constexpr int RT = RB / 64;                             // 16-row tiles of W per wave
     constexpr int WI = RB / 16;                             // W DMA instructions per wave and stage (4 rows each, 4 waves)
     constexpr int WBYTES = RB * WIDE_ROW_BYTES, XBYTES = MT * 16 * WIDE_ROW_BYTES, STAGE = WBYTES + XBYTES;
@@ -176,9 +177,8 @@ __global__ __launch_bounds__(256) void token_gemm_wide(const _Float16* __restric
         const int row = (wave + 4 * i) * 4 + (lane >> 4);
         srcx[i] = x + (int64_t)min(row, M - 1) * K + (((lane & 15) ^ (row & 15)) << 3);
     }
-    auto issue = [&](int s, int buf) {
+    auto issue = [&](int k0, int buf) {
         unsigned char* base = lds + buf * STAGE + wave * 1024;
-        const int k0 = s * WIDE_KB;
 #pragma unroll
         for (int i = 0; i < WI; ++i)
             __builtin_amdgcn_global_load_lds((gbl_ptr_t)(srcw[i] + k0), (lds_ptr_t)(base + i * 4096), 16, 0, 0);
@@ -199,9 +199,25 @@ __global__ __launch_bounds__(256) void token_gemm_wide(const _Float16* __restric
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[p][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const int stages = K / WIDE_KB;
-    issue(0, 0);
-    if (stages > 1) issue(1, 1);
+    // gridDim.y workgroups share a block of output features: each takes a contiguous run of the K stages
+    const int ks = gridDim.y, kz = blockIdx.y;
+    const int all_stages = K / WIDE_KB;
+    const int first = (int)((int64_t)all_stages * kz / ks);
+    const int stages = (int)((int64_t)all_stages * (kz + 1) / ks) - first;
+#pragma unroll
+    for (int i = 0; i < WI; ++i) srcw[i] += (int64_t)first * WIDE_KB;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) srcx[i] += (int64_t)first * WIDE_KB;
+    // workgroups walk their stages from different starting points (the sum over k has no order): with every workgroup
+    // at the same k all concurrent reads would share their low address bits (rows are K*2 bytes apart) and crowd a few
+    // HBM channels
+    int next = stages > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)stages) : 0;
+    auto issue_next = [&](int buf) {
+        issue(next * WIDE_KB, buf);
+        if (++next == stages) next = 0;
+    };
+    if (stages > 0) issue_next(0);
+    if (stages > 1) issue_next(1);
     for (int s = 0; s < stages; ++s) {
         const int buf = s & 1;
         // this wave's share of stage s has landed (stage s + 1 may still be in flight), then everybody's
@@ -225,8 +241,55 @@ __global__ __launch_bounds__(256) void token_gemm_wide(const _Float16* __restric
         if (s + 2 < stages) {
             __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): this wave has read what it needs of the buffer
             __builtin_amdgcn_s_barrier();                // ... and so has everybody else: refill it
-            issue(s + 2, buf);
+            issue_next(buf);
         }
+    }
+
+    if (ks > 1) {
+        // Partial tiles go to the workspace in register layout; the workgroup that arrives last at the block's ticket
+        // adds the ks slices in slice order (so the sum does not depend on which one that is) and writes the outputs.
+        // Device-wide fences would write back and invalidate a whole L2 per workgroup (measured: 4 times slower than
+        // no split at all); instead every partial is stored and loaded as a relaxed device-scope atomic, which goes
+        // through to the level all L2s share, and the ticket is taken only after this wave's stores have been
+        // acknowledged (vmcnt(0)) and, by the barrier, everybody else's in the workgroup.
+        const size_t per_slice = (size_t)gridDim.x * (4 * RT * MT * 4 * 64);
+        float* mine = part + (size_t)blockIdx.x * (4 * RT * MT * 4 * 64) + (size_t)wave * (RT * MT * 4 * 64) + lane;
+#pragma unroll
+        for (int p = 0; p < RT; ++p)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    __hip_atomic_store(mine + (size_t)kz * per_slice + ((p * MT + t) * 4 + i) * 64, acc[p][t][i],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the stores have been acknowledged
+        __shared__ unsigned arrived;
+        __syncthreads();
+        if (threadIdx.x == 0) arrived = __hip_atomic_fetch_add(ticket + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (arrived != (unsigned)(ks - 1)) return;       // uniform over the workgroup
+#pragma unroll
+        for (int p = 0; p < RT; ++p)
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                // all loads of a tile first (a slice beyond ks re-reads the last one and counts as zero), then the sums
+                float v[8][4];
+#pragma unroll
+                for (int z = 0; z < 8; ++z)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        v[z][i] = __hip_atomic_load(mine + (size_t)min(z, ks - 1) * per_slice + ((p * MT + t) * 4 + i) * 64,
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float sum = v[0][i];
+#pragma unroll
+                    for (int z = 1; z < 8; ++z) sum += z < ks ? v[z][i] : 0.f;
+                    acc[p][t][i] = sum;
+                }
+            }
+        if (threadIdx.x == 0) ticket[blockIdx.x] = 0;    // ready for the next launch on this stream
     }
 
     // element i of (tile p, m-tile t) in lane L is  n = n0 + 16*(wave*RT + p) + 4*(L/16) + i,  m = 16*t + L%16
@@ -251,7 +314,7 @@ __global__ __launch_bounds__(256) void token_gemm_wide(const _Float16* __restric
 
 template <int RB, int MT>
 int launch_wide(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
-                int out_f32_cols, int64_t ld16, int relu, hipStream_t st) {
+                int out_f32_cols, int64_t ld16, int relu, int ks, void* ws, hipStream_t st) {
     auto kern = token_gemm_wide<RB, MT>;
     constexpr int lds_bytes = 2 * (RB + MT * 16) * WIDE_ROW_BYTES;
     static std::once_flag configured;
@@ -261,14 +324,21 @@ int launch_wide(const void* x, const void* w, const void* bias, void* y32, void*
     });
     KVPR_HIP(configure_status);
     const unsigned grid = (unsigned)((N + RB - 1) / RB);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, (const _Float16*)x, (const _Float16*)w,
-                       (const _Float16*)bias, (float*)y32, (_Float16*)y16, M, N, K, out_f32_cols, ld16, relu);
+    hipLaunchKernelGGL(kern, dim3(grid, (unsigned)ks), dim3(256), lds_bytes, st, (const _Float16*)x, (const _Float16*)w,
+                       (const _Float16*)bias, (float*)y32, (_Float16*)y16, M, N, K, out_f32_cols, ld16, relu,
+                       (float*)((unsigned char*)ws + TOKEN_WS_TICKET_BYTES), (unsigned*)ws);
     KVPR_HIP(hipGetLastError());
     return KVPR_OK;
 }
 
 int g_token_tpw = 0;   // 0 = choose from N; tests and sweeps can force 1..8
 int g_token_wide = -1; // -1 = choose from N; 0 = never, 64 / 128 = force that many features per workgroup (tests, sweeps)
+int g_token_ks = 0;    // 0 = choose; 1..8 = force that many K slices (needs a workspace; tests, sweeps)
+
+// workspace bytes of a launch with `ks` K slices: the tickets, then ks partial tiles of float32 per block of RB features
+size_t wide_ws_bytes(int rb, int mt, int N, int ks) {
+    return TOKEN_WS_TICKET_BYTES + (size_t)ks * ((N + rb - 1) / rb) * rb * mt * 16 * sizeof(float);
+}
 
 template <int MT, int TPW>
 int launch_t(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
@@ -298,13 +368,31 @@ int compute_units() {
 
 template <int MT>
 int launch_mt(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
-              int out_f32_cols, int64_t ld16, int relu, hipStream_t st) {
-    // wide matrices: 128 (or 64) features per workgroup once that still gives about 150 workgroups
+              int out_f32_cols, int64_t ld16, int relu, void* ws, size_t ws_bytes, hipStream_t st) {
+    // wide kernel: 128 (or 64) features per workgroup once that gives about 150 workgroups, over all of K; with a
+    // workspace also for narrower outputs, K cut into slices until there are about two workgroups per compute unit
     if (K % WIDE_KB == 0 && g_token_tpw <= 0) {
-        int rb = g_token_wide;
-        if (rb < 0) rb = (N + 127) / 128 >= 144 ? 128 : (N + 63) / 64 >= 144 ? 64 : 0;
-        if (rb == 128) return launch_wide<128, MT>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-        if (rb == 64) return launch_wide<64, MT>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+        const int stages = K / WIDE_KB;
+        int rb, ks = 1;
+        if (g_token_wide >= 0) {                         // forced by a test or a sweep
+            rb = g_token_wide;
+            if (g_token_ks > 0) ks = g_token_ks;
+        } else {
+            rb = (N + 127) / 128 >= 144 ? 128 : (N + 63) / 64 >= 144 ? 64 : 0;
+            if (rb == 0 && ws) {
+                rb = 64;
+                const int nb = (N + 63) / 64;
+                while (ks < 8 && nb * ks < 2 * compute_units() && stages / (2 * ks) >= 4) ks *= 2;
+            }
+        }
+        if (rb) {
+            if (ks > stages) ks = stages;
+            if (!ws || (size_t)((N + rb - 1) / rb) * sizeof(unsigned) > TOKEN_WS_TICKET_BYTES) ks = 1;
+            while (ks > 1 && wide_ws_bytes(rb, MT, N, ks) > ws_bytes) --ks;
+            if (ks == 1 && g_token_wide < 0 && (N + rb - 1) / rb < 144) rb = 0;   // nothing to split after all: the narrow kernel
+        }
+        if (rb == 128) return launch_wide<128, MT>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, ks, ws, st);
+        if (rb == 64) return launch_wide<64, MT>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, ks, ws, st);
     }
     const int tiles = (N + 15) / 16;
     const int cap = 8 / MT;
@@ -329,23 +417,33 @@ int launch_mt(const void* x, const void* w, const void* bias, void* y32, void* y
 
 }  // namespace
 
-// flags bit 0: ReLU
+// flags bit 0: ReLU.  ws (optional, device): workspace that lets a narrow output split K over several workgroups; its
+// first 4096 bytes must be zero before the first launch that uses it and are zero again when a launch ends; launches
+// that share a workspace must not overlap.
 int launch_token_gemm_flags(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
-                            int out_f32_cols, int64_t ld16, int flags, hipStream_t st) {
+                            int out_f32_cols, int64_t ld16, int flags, hipStream_t st, void* ws, size_t ws_bytes) {
     const int relu = flags & 1;
-    if (M <= 16) return launch_mt<1>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-    if (M <= 32) return launch_mt<2>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-    if (M <= 48) return launch_mt<3>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
-    return launch_mt<4>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, st);
+    if (ws_bytes <= TOKEN_WS_TICKET_BYTES) ws = nullptr;
+    if (M <= 16) return launch_mt<1>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, ws, ws_bytes, st);
+    if (M <= 32) return launch_mt<2>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, ws, ws_bytes, st);
+    if (M <= 48) return launch_mt<3>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, ws, ws_bytes, st);
+    return launch_mt<4>(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, relu, ws, ws_bytes, st);
+}
+
+// enough for 8 K slices of an output of `N` features and `M` rows
+size_t token_gemm_workspace_bytes(int M, int N) {
+    return wide_ws_bytes(128, (M + 15) / 16, N, 8);
 }
 
 }  // namespace kvpr
 
-// v in 0..8: tiles per workgroup of the narrow kernel (0 = automatic choice of kernel and tiles);
-// v = 0x100 + rb (rb = 0, 64, 128): features per workgroup of the wide kernel (0 = narrow kernel only); v = -1: all automatic
+// v = -1: all automatic.  v in 0..8: tiles per workgroup of the narrow kernel (0 = automatic).
+// v >= 0x100: bits 0..7 = features per workgroup of the wide kernel (0 = narrow kernel only, 64, 128),
+// bits 12..15 = K slices (0 = one, or as many as the automatic choice takes when bits 0..7 are 0).
 extern "C" int kvpr_debug_set_token_gemm_cfg(int v) {
-    if (v < 0) { kvpr::g_token_tpw = 0; kvpr::g_token_wide = -1; return KVPR_OK; }
-    if (v >= 0x100) { kvpr::g_token_tpw = 0; kvpr::g_token_wide = v - 0x100; return KVPR_OK; }
+    kvpr::g_token_tpw = 0; kvpr::g_token_wide = -1; kvpr::g_token_ks = 0;
+    if (v < 0) return KVPR_OK;
+    if (v >= 0x100) { kvpr::g_token_wide = v & 0xFF; kvpr::g_token_ks = (v >> 12) & 15; return KVPR_OK; }
     kvpr::g_token_tpw = v;
     return KVPR_OK;
 }

@@ -49,6 +49,22 @@ extern "C" int kvpr_token_gemm(const void* x, const void* w, const void* bias, v
     return kvpr::launch_token_gemm_flags(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, 0, (hipStream_t)stream);
 }
 
+extern "C" size_t kvpr_token_gemm_workspace_bytes(int M, int N) {
+    if (M < 1 || M > 64 || N < 1) return 0;
+    return kvpr::token_gemm_workspace_bytes(M, N);
+}
+
+extern "C" int kvpr_token_gemm_ws(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N, int K,
+                                  int out_f32_cols, int64_t ld16, void* ws, size_t ws_bytes, void* stream) {
+    if (M < 1 || M > 64 || N < 1 || K < 1) return fail(KVPR_E_RANGE, "M=%d (1..64) N=%d K=%d out of range", M, N, K);
+    if (K % 128) return fail(KVPR_E_INVAL, "K must be a multiple of 128");
+    if (out_f32_cols < 0 || out_f32_cols > N) return fail(KVPR_E_RANGE, "out_f32_cols outside [0, N]");
+    if (!x || !w || (out_f32_cols > 0 && !y32) || (out_f32_cols < N && !y16)) return fail(KVPR_E_INVAL, "null pointer");
+    if (out_f32_cols < N && ld16 < N - out_f32_cols) return fail(KVPR_E_INVAL, "ld16 too small");
+    if (ws && ((uintptr_t)ws & 15)) return fail(KVPR_E_INVAL, "workspace must be 16-byte aligned");
+    return kvpr::launch_token_gemm_flags(x, w, bias, y32, y16, M, N, K, out_f32_cols, ld16, 0, (hipStream_t)stream, ws, ws ? ws_bytes : 0);
+}
+
 // ---- rotary models ----
 extern "C" int kvpr_rope_table(float* out_host, int n_pos, int head_dim, double base) {
     if (!out_host) return fail(KVPR_E_INVAL, "out_host is null");

@@ -26,7 +26,9 @@ size_t attention_workspace_bytes(int batch, int hidden, int n_heads, int S);
 int launch_attention_mixed(const void* q, const void* kv16, const void* kvq, void* z, void* ws, int S, int split, int batch,
                            int hidden, int n_heads, int phase, hipStream_t st);
 int launch_token_gemm_flags(const void* x, const void* w, const void* bias, void* y32, void* y16, int M, int N,
-                            int K, int out_f32_cols, int64_t ld16, int flags /*bit0: ReLU*/, hipStream_t st);
+                            int K, int out_f32_cols, int64_t ld16, int flags /*bit0: ReLU*/, hipStream_t st,
+                            void* ws = nullptr, size_t ws_bytes = 0);
+size_t token_gemm_workspace_bytes(int M, int N);
 int launch_fill_u16(void* p, size_t n_halfs, uint16_t pattern, hipStream_t st);
 int launch_fill_random(void* p, size_t n_halfs, float scale, uint32_t seed, hipStream_t st);
 int launch_layernorm(const void* x, const void* g, const void* b, void* y, int rows, int h, hipStream_t st);

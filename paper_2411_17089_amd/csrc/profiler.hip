@@ -149,14 +149,14 @@ extern "C" int kvpr_profile(kvpr_ctx* c, int batch, int seq, kvpr_profile_t* out
         // the rest of a layer's GPU work besides the recomputation: projections, attention, FFN (random weights)
         if (!rc) rc = time_median(c->compute, 5, [&]() -> int {
                 const int b = c->d.batch, f = c->d.ffn_dim;
-                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, c->q32, dkv, b, 3 * h, h, h, 2 * (int64_t)h, 0, c->compute)) return r;
+                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, c->q32, dkv, b, 3 * h, h, h, 2 * (int64_t)h, 0, c->compute, c->tok_ws, c->tok_ws_bytes)) return r;
                 if (int r = kvpr::launch_attention(c->q32, dkv, c->z16, c->attn_ws, S, b, h, c->d.n_heads, c->compute)) return r;
-                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, dkv, b, h, h, 0, h, 0, c->compute)) return r;
+                if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, dkv, b, h, h, 0, h, 0, c->compute, c->tok_ws, c->tok_ws_bytes)) return r;
                 if (f > 0) {
                     const int f1 = (int)ffn_rows;
                     half* prod = c->ffn1 + (c->llama ? (size_t)b * 2 * f : 0);
-                    if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, c->ffn1, b, f1, h, 0, f1, 1, c->compute)) return r;
-                    if (int r = kvpr::launch_token_gemm_flags(prod, wtmp, nullptr, nullptr, dkv, b, h, f, 0, h, 0, c->compute)) return r;
+                    if (int r = kvpr::launch_token_gemm_flags(c->z16, wtmp, nullptr, nullptr, c->ffn1, b, f1, h, 0, f1, 1, c->compute, c->tok_ws, c->tok_ws_bytes)) return r;
+                    if (int r = kvpr::launch_token_gemm_flags(prod, wtmp, nullptr, nullptr, dkv, b, h, f, 0, h, 0, c->compute, c->tok_ws, c->tok_ws_bytes)) return r;
                 }
                 return KVPR_OK; }, &t);
         if (!rc) p.layer_other_s = t;

@@ -216,7 +216,47 @@ def test_full_size_column_schedule_sampled_sequences(k):
             ref, _ = ko.decoder_stack_decode(sub, x_in[q, n:n + 1], [splits[j * nb + q] for j in range(n_layers)])
             assert rel_err(got[q, n:n + 1], ref) <= 5e-3, (q, n)
         # the first batch of layer 0 recomputes 832 positions: its GEMM is released by [Wk;Wv] (100 MiB), not by the 600 MiB blob
+        print({i: {n: round(v, 3) for n, v in tim[i].as_dict().items()} for i in range(n_layers * nb)}, flush=True)
         assert tim[0].weights_landed_valid and tim[0].ms_recompute_start < tim[0].ms_weights_landed
+    finally:
+        k.kvpr_destroy(ctx)
+
+
+@pytest.mark.parametrize("other_streams", [3, 4, 5])
+def test_column_schedule_keeps_its_streams_on_separate_queues(k, other_streams):
+    """The runtime shares a few hardware queues among all streams of the process.  Whatever number of streams the
+    application made before the context, the recomputation of a layer's first batch must be released by [Wk;Wv], not by
+    the whole layer's weights (with four other streams and no check at creation it started 19 ms late)."""
+    (h, H, d), b, s, n_layers, nb = kvpr_inputs.SHAPES["opt-13b"], 32, 1024, 2, 2
+    ffn = 4 * h
+    held = []
+    for _ in range(other_streams):
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            torch.zeros(16, device="cuda").add_(1)
+        held.append(st)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    r16 = lambda *shape, sc=0.02: (rng.standard_normal(shape, dtype=np.float32) * sc).astype(np.float16)
+    host = {"wqkv": r16(3 * h, h), "bqkv": r16(3 * h), "wo": r16(h, h), "bo": r16(h), "w1": r16(ffn, h), "b1": r16(ffn),
+            "w2": r16(h, ffn), "b2": r16(h), "ln1_g": np.ones(h, np.float16), "ln1_b": np.zeros(h, np.float16),
+            "ln2_g": np.ones(h, np.float16), "ln2_b": np.zeros(h, np.float16)}
+    X, KV = r16(s, b, h, sc=1.0), r16(s, b, 2 * h, sc=1.0)
+    print(f"column schedule beside {other_streams} other streams", flush=True)
+    ctx = k.kvpr_create_offload(n_layers, h, H, d, ffn, b, s + 2, nb)
+    try:
+        for j in range(n_layers):
+            k.kvpr_weights_write(ctx, j, k.make_weights(**host))
+            for q in range(nb):
+                k.kvpr_store_write(ctx, j * nb + q, 0, s, X, KV)
+        x_in = torch.from_numpy(r16(nb, b, h, sc=1.0)).cuda()
+        x_out = torch.empty((nb, b, h), dtype=torch.float16, device="cuda")
+        for step in range(2):   # a process's very first step is disturbed by the runtime growing its pools: judge the second
+            _, tim = k.kvpr_decode_step_columns(ctx, s, n_layers * nb, x_in, x_out, [832, 0, 1024, 576], timing=True)
+            torch.cuda.synchronize()
+        print("streams replaced so far:", k.lib.kvpr_debug_streams_replaced(), {n: round(v, 2) for n, v in tim[0].as_dict().items()}, flush=True)
+        assert tim[0].weights_landed_valid and 0 < tim[0].ms_recompute_start < tim[0].ms_weights_landed
+        assert tim[0].ms_act_copy < tim[0].ms_weights_landed      # the activations did not queue behind the weights either
     finally:
         k.kvpr_destroy(ctx)
 

@@ -144,3 +144,75 @@ def test_token_gemm_matches_oracle(k, M, N, K, f32, cfg):
     got16 = y16.cpu().numpy()
     assert np.isnan(got16[:, N - f32:]).all()
     assert rel_err(got16[:, :N - f32], ref[:, f32:]) <= TIGHT
+
+
+# The workspace form: K cut into slices over several workgroups, partial tiles added by the last one to arrive.
+# cfg: -1 = automatic (narrow outputs split, wide ones do not); else 0x100 + features per workgroup + (slices << 12).
+@pytest.mark.parametrize("cfg", [-1, 0x100 + 64 + (2 << 12), 0x100 + 64 + (3 << 12), 0x100 + 64 + (8 << 12), 0x100 + 128 + (4 << 12)])
+@pytest.mark.parametrize("M,N,K,f32", [(1, 2304, 768, 768), (32, 768, 2048, 0), (3, 96, 128, 32), (16, 520, 1024, 8),
+                                       (33, 256, 4096, 0), (64, 1056, 1280, 256), (48, 1300, 1152, 0)])
+def test_token_gemm_with_workspace_matches_oracle(k, M, N, K, f32, cfg):
+    print(f"token gemm ws M={M} N={N} K={K} f32={f32} cfg={cfg:#x}", flush=True)
+    rng = np.random.default_rng(M + N + 1)
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    bias = (rng.standard_normal(N) * 0.1).astype(np.float16)
+    ld16 = (N - f32) + 16
+    ws_bytes = k.kvpr_token_gemm_workspace_bytes(M, N)
+    assert ws_bytes > 4096
+    ws = torch.full((ws_bytes,), 0xFF, dtype=torch.uint8, device="cuda")   # partial area poisoned (NaN pattern)
+    ws[:4096] = 0
+    ref = ko.project(x, W.T, bias)
+    xd, Wd, bd = dev(x), dev(W), dev(bias)
+    k.lib.kvpr_debug_set_token_gemm_cfg(cfg)
+    try:
+        for call in range(2):                                    # the second call finds the counters as the first left them
+            y32 = torch.full((M, max(f32, 1)), float("nan"), dtype=torch.float32, device="cuda")
+            y16 = torch.full((M, ld16), float("nan"), dtype=torch.float16, device="cuda")
+            k.kvpr_token_gemm_ws(xd, Wd, bd, y32, y16, M, N, K, f32, ld16, ws, ws_bytes)
+            torch.cuda.synchronize()
+            assert int(ws[:4096].to(torch.int32).sum()) == 0
+            if f32:
+                assert rel_err(y32.cpu().numpy()[:, :f32], ref[:, :f32]) <= 1e-5
+            got16 = y16.cpu().numpy()
+            assert np.isnan(got16[:, N - f32:]).all()
+            assert rel_err(got16[:, :N - f32], ref[:, f32:]) <= TIGHT
+    finally:
+        k.lib.kvpr_debug_set_token_gemm_cfg(-1)
+
+
+def test_token_gemm_workspace_reused_by_different_products(k):
+    """Launches that share a workspace one after the other, as the layer's output projection and second FFN matrix do:
+    every launch must read the partial tiles of its own slices, not what an earlier launch left at the same addresses."""
+    M = 32
+    shapes = [(1024, 4096), (768, 8192), (1024, 4096), (1024, 2048), (520, 4096)]
+    ws_bytes = k.kvpr_token_gemm_workspace_bytes(M, 1024)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(77)
+    cases = []
+    for N, K in shapes:
+        x = rng.standard_normal((M, K)).astype(np.float16)
+        W = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+        cases.append((N, K, x, W, dev(x), dev(W), torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")))
+    for rounds in range(3):                                      # enqueued back to back, checked afterwards
+        for N, K, x, W, xd, Wd, y in cases:
+            y.fill_(float("nan"))
+            k.kvpr_token_gemm_ws(xd, Wd, None, None, y, M, N, K, 0, N, ws, ws_bytes)
+        torch.cuda.synchronize()
+        for N, K, x, W, xd, Wd, y in cases:
+            assert rel_err(y.cpu().numpy(), ko.project(x, W.T, np.zeros(N, np.float16))) <= TIGHT, (rounds, N, K)
+    assert int(ws[:4096].to(torch.int32).sum()) == 0
+
+
+def test_token_gemm_workspace_too_small_falls_back(k):
+    M, N, K = 32, 512, 2048
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    ref = ko.project(x, W.T, np.zeros(N, np.float16))
+    for ws_bytes in (0, 4096, 4096 + 2 * N * 32 * 4):            # none, counters only, room for two slices
+        ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+        y16 = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        k.kvpr_token_gemm_ws(dev(x), dev(W), None, None, y16, M, N, K, 0, N, ws, ws_bytes)
+        torch.cuda.synchronize()
+        assert rel_err(y16.cpu().numpy(), ref) <= TIGHT
