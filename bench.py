@@ -379,7 +379,7 @@ def run_power_probe(args):
 def run_kernels(args):
     """Standalone launches of the path's kernels at the bench shape, for rocprofv3 counter runs:
     a plain device copy of known size (reference for scaling FETCH_SIZE / WRITE_SIZE), the recompute
-    GEMM at M = split*batch, decode attention over seq+1 positions, and the two token GEMMs."""
+    GEMM at M = split*batch, decode attention over seq+1 positions, and the four token GEMMs of a decoder layer."""
     import torch
     import kvpr_inputs
     import paper_2411_17089_amd as k
@@ -415,8 +415,18 @@ def run_kernels(args):
     timed("copy_512MiB_ms", lambda: dst.copy_(src))
     timed("recompute_gemm_ms", lambda: k.kvpr_recompute_gemm(A, W[h:], bias[h:], kv, M, 2 * h, h, 2 * h))
     timed("attention_ms", lambda: k.kvpr_decode_attention(q, kv, z, ws, s + 1, b, h, H))
-    timed("token_gemm_qkv_ms", lambda: k.kvpr_token_gemm(x, W, bias, q, y16, b, 3 * h, h, h, 2 * h))
-    timed("token_gemm_out_ms", lambda: k.kvpr_token_gemm(x, W, bias, None, y16, b, h, h, 0, h))
+    # the four token GEMMs of a decoder layer as a context launches them (with its K-slice workspace)
+    W4 = (torch.randn((4 * h, h), device="cuda") * 0.02).half()
+    x4 = torch.randn((b, 4 * h), device="cuda", dtype=torch.float16)
+    y4 = torch.empty((b, 4 * h), device="cuda", dtype=torch.float16)
+    tws_bytes = k.kvpr_token_gemm_workspace_bytes(b, h)
+    tws = torch.zeros(tws_bytes, dtype=torch.uint8, device="cuda")
+    timed("token_gemm_qkv_ms", lambda: k.kvpr_token_gemm_ws(x, W, bias, q, y16, b, 3 * h, h, h, 2 * h, tws, tws_bytes))
+    timed("token_gemm_out_ms", lambda: k.kvpr_token_gemm_ws(x, W, bias, None, y16, b, h, h, 0, h, tws, tws_bytes))
+    timed("token_gemm_ffn_up_ms", lambda: k.kvpr_token_gemm_ws(x, W4, None, None, y4, b, 4 * h, h, 0, 4 * h, tws, tws_bytes))
+    timed("token_gemm_ffn_down_ms", lambda: k.kvpr_token_gemm_ws(x4, W4, None, None, y16, b, h, 4 * h, 0, h, tws, tws_bytes))
+    for name, n_w in (("qkv", 3), ("out", 1), ("ffn_up", 4), ("ffn_down", 4)):
+        out[f"token_gemm_{name}_GBps"] = n_w * h * h * 2 / out[f"token_gemm_{name}_ms"] / 1e6
     out["recompute_gemm_TFLOPs"] = 4.0 * M * h * h / out["recompute_gemm_ms"] / 1e9
     out["attention_GBps"] = 2.0 * b * (s + 1) * h * 2 / out["attention_ms"] / 1e6
     out["shape"] = {"model": args.model, "batch": b, "seq": s, "split": split, "M": M, "N": 2 * h, "K": h}
