@@ -171,7 +171,12 @@ const char* kvpr_last_error(void);
  * an array kept 4-bit compressed), and device staging buffers for min(n_layers, 2)
  * layers (float16 X and KV, plus packed copies of the arrays kept compressed).
  * KVPR_E_NOMEM if that fails.  kvpr_destroy waits for the context's streams and
- * frees everything the context owns. */
+ * frees everything the context owns.
+ * The context makes its own copy and store streams (and a weight stream in kvpr_create_offload).  The runtime
+ * shares a few hardware queues among all streams of a process, and two streams on one queue run in order, so
+ * creation launches a few short kernels (about 3 ms in all) on compute_stream and on its own streams and replaces
+ * any of its streams that turns out to sit behind one it has to overlap with; compute_stream must be idle or
+ * short of work at that time for the check to mean anything, and is synchronised by it. */
 int kvpr_create(const kvpr_model_desc* desc, void* compute_stream, kvpr_ctx** out);
 int kvpr_destroy(kvpr_ctx* ctx);
 /* Debug modes (KVPR_DEBUG_*), results are unchanged by them. */
