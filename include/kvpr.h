@@ -364,7 +364,8 @@ int kvpr_decode_attention_static(const void* q_dev, const void* kv_dev, void* z_
 /* The same attention (Eq. 2) over a cache whose rows [split, S-1) are still in the packed 4-bit form of the
  * host store (Sec. 4.4): rows [0, split) and row S-1 are read from kv16_dev (float16 [S, batch, 2*hidden]),
  * rows [split, S-1) from kvq_dev ([S, batch, kvpr_int4_row_bytes(2*hidden)], indexed by position) and
- * dequantised in registers to exactly the values kvpr_dequant_int4 gives.  Same workspace size as above.
+ * used as the codec's code * scale + minimum without kvpr_dequant_int4's final rounding to float16 (at most 2^-11
+ * relative per element; the affine map is applied to the sums, not per element).  Same workspace size as above.
  * split in [0, S-1].  With kvq_dev null every row comes from kv16_dev: the same two launches (rows [0, split)
  * and S-1, then rows [split, S-1)) and one combine, which is how kvpr_layer_decode overlaps the attention
  * over the recomputed rows with the tail of the cache copy. */

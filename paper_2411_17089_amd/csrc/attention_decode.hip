@@ -305,15 +305,26 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_ranged(
     *reinterpret_cast<float2*>(ml) = make_float2(m_run, l_run);
 }
 
-// The value the 4-bit codec defines for one element: float16(code * scale + mn), code = nibble e of the code words
-__device__ __forceinline__ float dequant_nibble(uint32_t word, int e, float scale, float mn) {
-    return (float)(_Float16)((float)((word >> (4 * e)) & 15u) * scale + mn);
+// The 8 codes of one word as floats: nibble e of the word is element e.  Even and odd nibbles are separated first so that
+// every element is one byte-to-float conversion.
+__device__ __forceinline__ void unpack_codes(uint32_t word, float (&c)[8]) {
+    const uint32_t lo = word & 0x0F0F0F0Fu, hi = (word >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        c[2 * b] = (float)((lo >> (8 * b)) & 0xFFu);
+        c[2 * b + 1] = (float)((hi >> (8 * b)) & 0xFFu);
+    }
 }
 
 // Packed rows of kvq [*, batch, 9h/8] (h bytes of codes: K then V, then h/32 + h/32 (scale, mn) float16 pairs, one per
 // 64 columns), positions pos0 .. pos0 + n_pos - 1.  A lane owns 32 consecutive columns of one head: its K codes and its
-// V codes are 16 bytes each, so every wave load is one contiguous KiB of codes (2048 columns), dequantised in registers.
+// V codes are 16 bytes each, so every wave load is one contiguous KiB of codes (2048 columns).
 // The first version read 4 bytes of codes per lane (256-byte segments) and reached 1.8 TB/s.
+// The codec's value of an element is code * scale + mn with one (scale, mn) per 64 columns, i.e. per lane here, so the
+// affine map is taken out of the sums: q . k = scale * sum_e q_e code_e + mn * sum_e q_e, and
+// sum_t p_t v_te = sum_t (p_t scale_t) code_te + sum_t p_t mn_t.  That is a conversion and one fma per element where
+// dequantising first (with the codec's rounding to float16) cost six instructions, and the kernel is bound by those.
+// The values differ from kvpr_dequant_int4's by that rounding: at most 2^-11 relative per element.
 template <int D, int ATT_WAVES>
 __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_packed(
     const float* __restrict__ q, const uint8_t* __restrict__ kvq, float* __restrict__ ws_acc, float* __restrict__ ws_ml,
@@ -338,7 +349,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_packed(
     const int k_code = ccol / 2, v_code = (h + ccol) / 2;
     const int k_meta = h + (ccol / 64) * 4, v_meta = h + ((h + ccol) / 64) * 4;
 
-    float m_run = -INFINITY, l_run = 0.f;
+    float qsum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) qsum += qf[e];
+    float m_run = -INFINITY, l_run = 0.f, pm_run = 0.f;      // pm_run: sum_t p_t mn_t, the same for the lane's 32 columns
     float acc[32];
 #pragma unroll
     for (int e = 0; e < 32; ++e) acc[e] = 0.f;
@@ -360,10 +374,15 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_packed(
             union { uint32_t w; _Float16 hh[2]; } a;
             a.w = km[u];
             const float ks = (float)a.hh[0], kmn = (float)a.hh[1];
-            const uint32_t kw[4] = {kc[u][0], kc[u][1], kc[u][2], kc[u][3]};
-            float d = 0.f;
+            float dc = 0.f;
 #pragma unroll
-            for (int e = 0; e < 32; ++e) d = fmaf(dequant_nibble(kw[e >> 3], e & 7, ks, kmn), qf[e], d);
+            for (int w = 0; w < 4; ++w) {
+                float c8[8];
+                unpack_codes(kc[u][w], c8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dc = fmaf(c8[e], qf[8 * w + e], dc);
+            }
+            float d = fmaf(ks, dc, kmn * qsum);
             // sum over the D/32 consecutive lanes of the head
             d = dpp_xchg_add<0xB1>(d);
             if (D == 128) d = dpp_xchg_add<0x4E>(d);
@@ -372,6 +391,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_packed(
         }
         const float rescale = exp2f(m_run - m_new);
         l_run *= rescale;
+        pm_run *= rescale;
 #pragma unroll
         for (int e = 0; e < 32; ++e) acc[e] *= rescale;
 #pragma unroll
@@ -379,14 +399,22 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attention_partial_packed(
             union { uint32_t w; _Float16 hh[2]; } b;
             b.w = vm[u];
             const float vs = (float)b.hh[0], vmn = (float)b.hh[1];
-            const uint32_t vw[4] = {vc[u][0], vc[u][1], vc[u][2], vc[u][3]};
             const float p = exp2f(sc[u] - m_new);
             l_run += p;
+            pm_run = fmaf(p, vmn, pm_run);
+            const float ps = p * vs;
 #pragma unroll
-            for (int e = 0; e < 32; ++e) acc[e] = fmaf(p, dequant_nibble(vw[e >> 3], e & 7, vs, vmn), acc[e]);
+            for (int w = 0; w < 4; ++w) {
+                float c8[8];
+                unpack_codes(vc[u][w], c8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[8 * w + e] = fmaf(ps, c8[e], acc[8 * w + e]);
+            }
         }
         m_run = m_new;
     }
+#pragma unroll
+    for (int e = 0; e < 32; ++e) acc[e] += pm_run;
     // ---- merge the waves (wave 0 always has at least one position)
     __shared__ float sm[ATT_WAVES][34][64];
     sm[wave][0][lane] = m_run;
