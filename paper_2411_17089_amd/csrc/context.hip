@@ -601,7 +601,8 @@ int create_impl(const kvpr_model_desc* d, int n_gpu_batches, void* compute_strea
     // counters start at zero and every launch leaves them at zero
     c->tok_ws_bytes = kvpr::token_gemm_workspace_bytes(d->batch, d->hidden);
     if ((e = hipMalloc(&c->tok_ws, c->tok_ws_bytes)) != hipSuccess) return bail(KVPR_E_NOMEM, "token GEMM workspace", e);
-    if ((e = hipMemset(c->tok_ws, 0, 4096)) != hipSuccess) return bail(KVPR_E_HIP, "token GEMM workspace", e);
+    if ((e = hipMemset(c->tok_ws, 0, 4096)) != hipSuccess || (e = hipStreamSynchronize(nullptr)) != hipSuccess)
+        return bail(KVPR_E_HIP, "token GEMM workspace", e);
     if (c->llama) {
         if ((e = hipMalloc((void**)&c->qk32, 2 * bh * sizeof(float))) != hipSuccess) return bail(KVPR_E_NOMEM, "q|k buffer", e);
         // (cos, sin)(p * theta_i), theta_i = base^(-2i/d): evaluated in double on the host, stored as float
