@@ -28,7 +28,11 @@
 // global->LDS DMA (a wave instruction covers 4 rows x 256 contiguous bytes; x then costs M / RB of the weight bytes
 // instead of 2 / TPW), two stages in LDS, fragments read back in the MFMA operand layout (16-byte chunks of a row
 // XOR-swizzled by the row number on the global-address side so that the 16 rows of a fragment read hit 16 different
-// bank groups).  A wave owns RB / 4 output features for all of K: no cross-wave reduction.
+// bank groups).  A wave owns RB / 4 output features for the workgroup's whole K range: no cross-wave reduction.
+// Outputs with too few features to give every compute unit a block (N = hidden: the output projection of Eq. 3 and the
+// second FFN matrix of Eq. 4) are cut along K instead: gridDim.y workgroups share a block of features, each takes a run
+// of K stages, the float32 partial tiles meet in a workspace and the workgroup that arrives last adds them in slice order
+// and writes the outputs.
 #include "kvpr_internal.h"
 #include <mutex>
 

@@ -206,8 +206,11 @@ def test_full_size_column_schedule_sampled_sequences(k):
         x_out = torch.empty((nb, b, h), dtype=torch.float16, device="cuda")
         splits = [832, 0, 1024, 576]                                       # slot = layer * nb + batch
         print("full-size column schedule", flush=True)
-        got_splits, tim = k.kvpr_decode_step_columns(ctx, s, n_layers * nb, torch.from_numpy(x_in).cuda(), x_out, splits, timing=True)
-        torch.cuda.synchronize()
+        x_in_dev = torch.from_numpy(x_in).cuda()
+        for step in range(2):   # the same token twice (same inputs, same outputs): the timing of a process's very first
+            # large step is disturbed by the runtime growing its pools, so the second one is judged
+            got_splits, tim = k.kvpr_decode_step_columns(ctx, s, n_layers * nb, x_in_dev, x_out, splits, timing=True)
+            torch.cuda.synchronize()
         assert got_splits == splits
         got = x_out.cpu().numpy()
         assert np.isfinite(got).all()
