@@ -187,6 +187,18 @@ def test_kernel_entry_points_validate_before_touching_the_gpu(k):
         k.kvpr_token_gemm(1, 1, None, 1, 1, 65, 64, 128, 0, 64, stream=0)     # M > 64
     assert e.value.code == k.KVPR_E_RANGE
     assert k.kvpr_attention_workspace_bytes(32, 4096, 32, 1025) > 0
+    # token GEMM workspace: 4096 bytes of arrival counters + 8 K slices of float32 partial tiles, N rounded up to whole
+    # blocks of 128 features, M to whole tiles of 16 rows
+    assert k.kvpr_token_gemm_workspace_bytes(32, 7168) == 4096 + 8 * 7168 * 32 * 4
+    assert k.kvpr_token_gemm_workspace_bytes(33, 100) == 4096 + 8 * 128 * 48 * 4
+    assert k.kvpr_token_gemm_workspace_bytes(0, 128) == 0 and k.kvpr_token_gemm_workspace_bytes(65, 128) == 0
+    assert k.kvpr_token_gemm_workspace_bytes(1, 0) == 0
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_token_gemm_ws(1, 1, None, 1, 1, 32, 64, 100, 0, 64, 16, 8192, stream=0)   # K % 128
+    assert e.value.code == k.KVPR_E_INVAL
+    with pytest.raises(k.KvprError) as e:
+        k.kvpr_token_gemm_ws(1, 1, None, 1, 1, 32, 64, 128, 0, 64, 8, 8192, stream=0)    # workspace not 16-byte aligned
+    assert e.value.code == k.KVPR_E_INVAL
     for fn in (k.kvpr_quant_int4, k.kvpr_dequant_int4):
         with pytest.raises(k.KvprError) as e:
             fn(1, 1, 4, 100, stream=0)                                         # cols % 64
