@@ -726,6 +726,43 @@ def mfma_ceiling(seconds=1.5):
                     "with no data movement at all"}
 
 
+def token_gemm_rooflines(model, b, launches=30):
+    """The four weight-streaming GEMMs of a decoder layer for the decode token (q|k|v, output projection, FFN up, FFN
+    down) at `model`'s width, launched as a context launches them (with its K-slice workspace), back to back over
+    rotating copies of the weights (more than the 256 MiB memory-side cache holds) between one pair of events.
+    Algorithmic bytes = the weight matrix once."""
+    import torch
+    import kvpr_inputs
+    import paper_2411_17089_amd as k
+    h = kvpr_inputs.SHAPES[model][0]
+    g = torch.Generator(device="cuda").manual_seed(1)
+    ws_bytes = k.kvpr_token_gemm_workspace_bytes(b, h)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device="cuda")
+    out = []
+    for name, N, K in (("q|k|v", 3 * h, h), ("output projection", h, h), ("FFN up", 4 * h, h), ("FFN down", h, 4 * h)):
+        x = torch.randn((b, K), device="cuda", dtype=torch.float32, generator=g).half()
+        copies = max(2, int(600e6 // (N * K * 2)) + 1)
+        Ws = [(torch.randn((N, K), device="cuda", dtype=torch.float32, generator=g) * 0.02).half() for _ in range(copies)]
+        y = torch.empty((b, N), device="cuda", dtype=torch.float16)
+        def launch(i):
+            k.kvpr_token_gemm_ws(x, Ws[i % copies], None, None, y, b, N, K, 0, N, ws, ws_bytes)
+        for i in range(5):
+            launch(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(launches):
+            launch(i)
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) / launches * 1e3
+        byt = N * K * 2
+        out.append({"gemm": name, "M": b, "N": N, "K": K, "bytes": byt, "avg_us": us, "achieved_GBps": byt / us / 1e3,
+                    "frac_of_hbm_peak": byt / us / 1e3 / PEAK_HBM_GBPS})
+        del Ws
+    return {"bound": "hbm", "peak": PEAK_HBM_GBPS, "unit": "GB/s", "launches_back_to_back": launches, "shape": model, "gemms": out}
+
+
 def headline(args, r):
     """The one-line record of the driver's contract, from the figures of one layer case."""
     pf = profile_figures(r["model"], r["batch"], r["context"])
@@ -842,7 +879,7 @@ def main():
                          "register-only MFMA loop, so that the recompute GEMM does not start with the clocks down (0 = off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32)
-    ap.add_argument("--skip", default="", help="comma list of parts to leave out: ceiling; in the default run also sweep, stack, columns")
+    ap.add_argument("--skip", default="", help="comma list of parts to leave out: ceiling, token_gemm; in the default run also sweep, stack, columns")
     args = ap.parse_args()
     if args.warmup is None:
         args.warmup = 2 if (args.stack or args.columns) else max(25, args.steps)
@@ -873,6 +910,8 @@ def main():
         r = run_layer(args, args.model, args.batch, args.seq, args.split, attention=True, extension=True,
                       cpu=not args.no_cpu_baseline)
         result = headline(args, r)
+        if "token_gemm" not in args.skip.split(","):
+            result["roofline_token_gemm"] = token_gemm_rooflines(args.model, args.batch)
         if "ceiling" not in args.skip.split(","):
             ceil = mfma_ceiling()
             result["roofline"]["power_limited_mfma_ceiling"] = ceil
@@ -896,6 +935,9 @@ def main():
             say(f"OPT-30B shape, batch 16, context {s}")
             configs.append(compact(run_layer(args, "opt-30b", 16, s)))
     result = headline(args, c4)
+    if "token_gemm" not in skip:
+        say("token GEMMs of a decoder layer at the headline width")
+        result["roofline_token_gemm"] = token_gemm_rooflines("opt-30b", 32)
     if "ceiling" not in skip:
         say("register-only MFMA loop (what the power limit grants on this data)")
         ceil = mfma_ceiling()
