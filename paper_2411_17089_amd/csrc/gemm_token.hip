@@ -384,9 +384,16 @@ int launch_mt(const void* x, const void* w, const void* bias, void* y32, void* y
         } else {
             rb = (N + 127) / 128 >= 144 ? 128 : (N + 63) / 64 >= 144 ? 64 : 0;
             if (rb == 0 && ws) {
+                // the fewest slices that give about one workgroup per compute unit, doubled when a slice would still be
+                // longer than 64 stages, and never shorter than 4 stages: over hidden 4096 / 5120 / 7168 and K = h / 4h
+                // this picks the best or second-best measured count (4, 3, 2 for K = h; 4, 3, 4 for K = 4h)
                 rb = 64;
-                const int nb = (N + 63) / 64;
-                while (ks < 8 && nb * ks < 2 * compute_units() && stages / (2 * ks) >= 4) ks *= 2;
+                const int nb = (N + 63) / 64, cus = compute_units();
+                ks = 8;
+                for (int c : {1, 2, 3, 4, 6, 8})
+                    if (nb * c * 100 >= 85 * cus) { ks = c; break; }
+                if (stages / ks > 64 && ks <= 4) ks *= 2;
+                while (ks > 1 && stages / ks < 4) --ks;
             }
         }
         if (rb) {
