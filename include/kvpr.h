@@ -176,7 +176,8 @@ const char* kvpr_last_error(void);
  * shares a few hardware queues among all streams of a process, and two streams on one queue run in order, so
  * creation launches a few short kernels (about 3 ms in all) on compute_stream and on its own streams and replaces
  * any of its streams that turns out to sit behind one it has to overlap with; compute_stream must be idle or
- * short of work at that time for the check to mean anything, and is synchronised by it. */
+ * short of work at that time for the check to mean anything, and is synchronised by it (so a context cannot be
+ * created while compute_stream is being captured into a graph). */
 int kvpr_create(const kvpr_model_desc* desc, void* compute_stream, kvpr_ctx** out);
 int kvpr_destroy(kvpr_ctx* ctx);
 /* Debug modes (KVPR_DEBUG_*), results are unchanged by them. */
