@@ -264,6 +264,38 @@ def test_column_schedule_keeps_its_streams_on_separate_queues(k, other_streams):
         k.kvpr_destroy(ctx)
 
 
+def test_full_size_headline_configuration_sampled_sequences(k):
+    """The configuration the bench quotes its headline on, launched as the bench launches it: OPT-30B-shaped layer
+    (hidden 7168, 56 heads), batch 32, context 1024, split 768, clock keep-alive on, through the timed entry point
+    (several decodes in flight, as in the bench's timed loop); whole sequences against the oracle."""
+    (h, H, d), b, s, split = kvpr_inputs.SHAPES["opt-30b"], 32, 1024, 768
+    layer = kvpr_inputs.make_layer(6, b, s, h, H)
+    dv = upload_layer(layer)
+    w = k.make_weights(wqkv=dv["wqkv"], bqkv=dv["bqkv"], wo=dv["wo"], bo=dv["bo"])
+    ctx = k.kvpr_create(1, h, H, d, 0, b, s + 2)
+    try:
+        k.kvpr_store_write(ctx, 0, 0, s, layer["X"], None)
+        k.kvpr_store_prefill_kv(ctx, 0, s, w)
+        k.kvpr_set_keep_warm(ctx, 0.85)
+        prof = k.kvpr_profile_step(ctx, b, s, k.kvpr_profile(ctx, b, s))
+        k.kvpr_set_profile(ctx, prof, k.KVPR_COST_EQ10, 64)
+        outs = [torch.empty((b, h), dtype=torch.float16, device="cuda") for _ in range(4)]
+        print("full-size headline configuration", flush=True)
+        for i, out in enumerate(outs):                          # enqueued without waiting in between
+            k.kvpr_layer_decode_timed(ctx, 0, s, split, w, dv["x_new"], out, i)
+        torch.cuda.synchronize()
+        tim = k.kvpr_timing_read(ctx, 3)
+        assert tim.split == split and tim.ms_recompute > 0
+        got = [o.cpu().numpy() for o in outs]
+        for g in got[1:]:
+            assert np.array_equal(g, got[0])                    # the same decode four times
+        for n in (0, 13, 31):
+            sub = dict(layer, X=np.ascontiguousarray(layer["X"][:, n:n + 1]), x_new=layer["x_new"][n:n + 1])
+            assert rel_err(got[0][n:n + 1], ko.layer_decode(sub, split)["o"]) <= 3e-3, n
+    finally:
+        k.kvpr_destroy(ctx)
+
+
 def test_full_size_longest_context_sampled_sequences(k):
     """The longest context of the sweep: OPT-30B-shaped layer (hidden 7168, 56 heads), batch 16, context 4096
     (1.75 GiB of cache in the host store); whole sequences against the oracle at three splits."""
