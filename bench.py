@@ -225,6 +225,8 @@ def run_columns(args):
     prof = k.kvpr_profile(ctx, b, s)
     k.kvpr_set_profile(ctx, prof, cm, args.granularity)
     k.kvpr_set_adaptive(ctx, args.adaptive)
+    if args.hidden_offload:
+        k.kvpr_set_hidden_offload(ctx, True)      # Algorithm 1's load_activation / store_activation of the layer inputs
     x = (torch.randn((nb, b, h), device="cuda") * 1.0).half()
     x_out = torch.empty_like(x)
     seq = s
@@ -855,6 +857,7 @@ def main():
     ap.add_argument("--columns", action="store_true",
                     help="throughput mode: column-by-column schedule with the weights offloaded too (use with --layers, --gpu-batches)")
     ap.add_argument("--gpu-batches", type=int, default=4)
+    ap.add_argument("--hidden-offload", action="store_true", help="--columns: keep the hidden states between layers in pinned host memory (Algorithm 1)")
     ap.add_argument("--kernels", action="store_true", help="launch each kernel of the path standalone (for rocprofv3 --pmc runs)")
     ap.add_argument("--power-probe", action="store_true",
                     help="clock / power evidence: the recompute GEMM and a register-only MFMA loop on normal, constant and zero operands under amd-smi sampling")

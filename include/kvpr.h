@@ -322,6 +322,14 @@ int kvpr_decode_step(kvpr_ctx* ctx, int seq, const kvpr_layer_weights* layers, c
  * projections that need Wq ("fine-grained MHA pipeline").  kvpr_decode_step is not available on
  * such a context. */
 int kvpr_create_offload(const kvpr_model_desc* desc, int n_gpu_batches, void* compute_stream, kvpr_ctx** out);
+
+/* Column schedule only, optional (off by default): keep the hidden states that pass from layer to layer in pinned host
+ * memory, as Algorithm 1 does with load_activation / store_activation.  After a batch's layer its output goes to the
+ * batch's host row (store stream); the next layer fetches it into one of two device staging buffers, one batch ahead
+ * of the computation when n_gpu_batches >= 2.  The device then holds the hidden states of four batches at most instead
+ * of n_gpu_batches.  Results are unchanged bit for bit.  x_in_dev / x_out_dev of kvpr_decode_step_columns stay device
+ * arrays.  KVPR_E_STATE on a context without offloaded weights. */
+int kvpr_set_hidden_offload(kvpr_ctx* ctx, int on);
 int kvpr_weights_write(kvpr_ctx* ctx, int layer, const kvpr_layer_weights* host);
 int kvpr_decode_step_columns(kvpr_ctx* ctx, int seq, const void* x_in_dev, void* x_out_dev,
                              const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_slot);

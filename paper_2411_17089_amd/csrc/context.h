@@ -58,6 +58,14 @@ struct kvpr_ctx {
     std::vector<half*> hw;                   // pinned weight blob per layer
     half* dw[2] = {nullptr, nullptr};        // device weight blobs (ping-pong across layers)
     half* hid_all = nullptr;                 // [nb, batch, hidden] hidden states of all GPU batches
+    // optional (kvpr_set_hidden_offload): the hidden states between layers live in pinned host memory, as Algorithm 1's
+    // load_activation / store_activation have it; the device then holds two input and two output batches at a time
+    bool hid_offload = false;
+    half* hhid = nullptr;                    // pinned [nb, batch, hidden]
+    half* hin[2] = {nullptr, nullptr};       // device: input of this slot and of the next one
+    half* hout[2] = {nullptr, nullptr};      // device: output of this slot and of the previous one
+    hipEvent_t ev_hin_loaded[2]{}, ev_hin_free[2]{}, ev_hout_ready[2]{}, ev_hout_free[2]{};
+    bool hin_free_rec[2] = {false, false}, hout_free_rec[2] = {false, false};
     hipEvent_t ev_wkv[2]{}, ev_wall[2]{}, ev_wfree[2]{};
     bool wfree_recorded[2] = {false, false};
     std::vector<bool> w_written;

@@ -383,6 +383,13 @@ void destroy_impl(kvpr_ctx* c) {
     }
     if (c->wstream) (void)hipStreamSynchronize(c->wstream);
     for (auto p : c->hw) if (p) (void)hipHostFree(p);
+    if (c->hhid) (void)hipHostFree(c->hhid);
+    for (int i = 0; i < 2; ++i) {
+        if (c->hin[i]) (void)hipFree(c->hin[i]);
+        if (c->hout[i]) (void)hipFree(c->hout[i]);
+        hipEvent_t he[] = {c->ev_hin_loaded[i], c->ev_hin_free[i], c->ev_hout_ready[i], c->ev_hout_free[i]};
+        for (hipEvent_t e : he) if (e) (void)hipEventDestroy(e);
+    }
     for (int i = 0; i < 2; ++i) {
         hipEvent_t we[] = {c->ev_wkv[i], c->ev_wall[i], c->ev_wfree[i]};
         for (hipEvent_t e : we) if (e) (void)hipEventDestroy(e);
@@ -664,6 +671,26 @@ extern "C" int kvpr_set_debug(kvpr_ctx* c, int flags) {
     return KVPR_OK;
 }
 
+extern "C" int kvpr_set_hidden_offload(kvpr_ctx* c, int on) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (c->nb <= 0) return fail(KVPR_E_STATE, "context was not created with kvpr_create_offload");
+    if (on && !c->hhid) {
+        const size_t bh = (size_t)c->d.batch * c->d.hidden;
+        KVPR_HIP(hipHostMalloc((void**)&c->hhid, (size_t)c->nb * bh * sizeof(half), hipHostMallocDefault));
+        for (int i = 0; i < 2; ++i) {
+            KVPR_HIP(hipMalloc((void**)&c->hin[i], bh * sizeof(half)));
+            KVPR_HIP(hipMalloc((void**)&c->hout[i], bh * sizeof(half)));
+            KVPR_HIP(hipEventCreateWithFlags(&c->ev_hin_loaded[i], hipEventDisableTiming));
+            KVPR_HIP(hipEventCreateWithFlags(&c->ev_hin_free[i], hipEventDisableTiming));
+            KVPR_HIP(hipEventCreateWithFlags(&c->ev_hout_ready[i], hipEventDisableTiming));
+            KVPR_HIP(hipEventCreateWithFlags(&c->ev_hout_free[i], hipEventDisableTiming));
+        }
+    }
+    // steps in flight keep the mode they were enqueued with; the staging buffers and events are reused across steps
+    c->hid_offload = on != 0;
+    return KVPR_OK;
+}
+
 extern "C" int kvpr_set_chunks(kvpr_ctx* c, int chunks) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
     if (chunks < 1 || chunks > kvpr_ctx::kMaxChunks) return fail(KVPR_E_RANGE, "chunks %d outside [1, %d]", chunks, kvpr_ctx::kMaxChunks);
@@ -924,6 +951,16 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
         }
         return KVPR_OK;
     };
+    // load_activation of slot t (layer t / nb >= 1, batch t % nb): host row -> device staging, on the store stream, behind
+    // the store that wrote the row one layer earlier
+    int next_hidden_load = nb;
+    auto hidden_load = [&](int t) -> int {
+        const int par = t & 1, k = t % nb;
+        if (c->hin_free_rec[par]) KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_hin_free[par], 0));
+        if (int rc = kvpr::launch_copy_bytes(c->hhid + (size_t)k * bh, c->hin[par], bh * sizeof(half), c->store)) return rc;
+        KVPR_HIP(hipEventRecord(c->ev_hin_loaded[par], c->store));
+        return KVPR_OK;
+    };
     if (int rc = load_weights(0)) return rc;
     for (int j = 0; j < L; ++j) {
         const int wb = j & 1;
@@ -932,9 +969,26 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
         const kvpr_layer_weights w = blob_weights(c->dw[wb], BL);
         const WeightFence wf{c->ev_wkv[wb], c->ev_wall[wb]};
         for (int k = 0; k < nb; ++k) {
-            const int slot = j * nb + k;
+            const int slot = j * nb + k, par = slot & 1;
             const half* hid_in = (j == 0) ? (const half*)x_in_dev + (size_t)k * bh : c->hid_all + (size_t)k * bh;
             half* hid_out = (j == L - 1) ? (half*)x_out_dev + (size_t)k * bh : c->hid_all + (size_t)k * bh;
+            if (c->hid_offload) {
+                // this slot's input, unless the previous slot already asked for it; then the next slot's, ahead of this
+                // slot's own stores in the stream (load_activation(k+1) before compute(k) before store_activation(k-1)
+                // in Algorithm 1): possible once the store that wrote it, one layer back, is already in the stream
+                while (next_hidden_load <= slot)
+                    if (int rc = hidden_load(next_hidden_load++)) return rc;
+                if (nb >= 2 && next_hidden_load == slot + 1 && slot + 1 < S)
+                    if (int rc = hidden_load(next_hidden_load++)) return rc;
+                if (j > 0) {
+                    KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_hin_loaded[par], 0));
+                    hid_in = c->hin[par];
+                }
+                if (j < L - 1) {
+                    if (c->hout_free_rec[par]) KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_hout_free[par], 0));
+                    hid_out = c->hout[par];
+                }
+            }
             // the norm's parameters arrive with [Wk;Wv]: neither the norm nor the recomputation that follows it
             // waits for Wq, Wo and the FFN matrices, which may still be on the link (Sec. 3.3 fine-grained MHA pipeline)
             KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_wkv[wb], 0));
@@ -943,6 +997,19 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
                                        per_slot ? &c->tev[slot] : nullptr, false, &wf))
                 return rc;
             if (int rc = residual_and_ffn(c, &w, hid_in, hid_out)) return rc;
+            if (c->hid_offload) {
+                if (j > 0) {
+                    KVPR_HIP(hipEventRecord(c->ev_hin_free[par], c->compute));
+                    c->hin_free_rec[par] = true;
+                }
+                if (j < L - 1) {                                  // store_activation: this batch's output to its host row
+                    KVPR_HIP(hipEventRecord(c->ev_hout_ready[par], c->compute));
+                    KVPR_HIP(hipStreamWaitEvent(c->store, c->ev_hout_ready[par], 0));
+                    if (int rc = kvpr::launch_copy_bytes(c->hout[par], c->hhid + (size_t)k * bh, bh * sizeof(half), c->store)) return rc;
+                    KVPR_HIP(hipEventRecord(c->ev_hout_free[par], c->store));
+                    c->hout_free_rec[par] = true;
+                }
+            }
         }
         KVPR_HIP(hipEventRecord(c->ev_wfree[wb], c->compute));
         c->wfree_recorded[wb] = true;

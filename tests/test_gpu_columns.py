@@ -91,6 +91,47 @@ def test_columns_match_oracle(k, n_layers, nb, b, s, h, H, ffn):
         st.close()
 
 
+@pytest.mark.parametrize("n_layers,nb,b,s,h,H,ffn", [(4, 5, 4, 40, 256, 2, 1024), (3, 2, 32, 24, 512, 4, 2048), (4, 1, 2, 33, 768, 12, 3072),
+                                                      (2, 3, 3, 20, 256, 4, 512)])
+def test_hidden_states_through_the_host_change_nothing(k, n_layers, nb, b, s, h, H, ffn):
+    """Algorithm 1's load_activation / store_activation: with the hidden states of the batches kept in pinned host memory
+    between layers (two device staging buffers each way, so with five batches the data has to come back from the host),
+    the outputs equal those of the device-resident mode bit for bit, step after step, and match the oracle."""
+    st = Columns(k, n_layers, nb, b, s, h, H, ffn, seed0=500)
+    try:
+        S = n_layers * nb
+        rng = np.random.default_rng(11)
+        x_in = dev(st.x_in)
+        for trial in range(2):
+            splits = [int(v) for v in rng.integers(0, s + 1, S)]
+            print(f"hidden offload layers={n_layers} nb={nb} b={b} s={s} h={h} splits={splits}", flush=True)
+            k.kvpr_set_hidden_offload(st.ctx, False)
+            k.kvpr_decode_step_columns(st.ctx, s, S, x_in, st.x_out, splits)
+            torch.cuda.synchronize()
+            plain = st.x_out.cpu().numpy().copy()
+            k.kvpr_set_hidden_offload(st.ctx, True)
+            outs = [torch.full_like(st.x_out, float("nan")) for _ in range(3)]
+            for o in outs:                                       # three steps enqueued without waiting in between
+                k.kvpr_decode_step_columns(st.ctx, s, S, x_in, o, splits)
+            torch.cuda.synchronize()
+            for o in outs:
+                assert np.array_equal(o.cpu().numpy(), plain)
+            assert rel_err(plain, st.oracle(splits)) <= 5e-3
+        k.kvpr_set_hidden_offload(st.ctx, False)
+    finally:
+        st.close()
+
+
+def test_hidden_offload_needs_an_offload_context(k):
+    ctx = k.kvpr_create(1, 256, 2, 128, 1024, 2, 16)
+    try:
+        with pytest.raises(k.KvprError) as e:
+            k.kvpr_set_hidden_offload(ctx, True)
+        assert e.value.code == k.KVPR_E_STATE
+    finally:
+        k.kvpr_destroy(ctx)
+
+
 def test_recompute_runs_while_the_rest_of_the_layer_is_on_the_link(k):
     """Fine-grained MHA pipeline (Sec. 3.3, Table 2): [Wk;Wv] travel first, and the recomputation of the first batch of
     a layer is released by them alone.  With 10 h^2 further weights (Wq, Wo, FFN: 84 MB here) behind them on the link,
