@@ -199,7 +199,7 @@ def run_columns(args):
     torch.manual_seed(0)
     qflags, x_bpp, kv_bpp = store_sizes(k, args.store_int4, b, h)
     also_pipe = cm == k.KVPR_COST_EQ10 and args.extension_chunks > 0
-    passes = 3 if also_pipe else 2
+    passes = (3 if also_pipe else 2) + (1 if getattr(args, "weight_pipeline_ablation", False) else 0)
     ctx = k.kvpr_create_offload(L, h, H, d, ffn, b, s + passes * (gen + args.warmup) + 2, nb, dtype=k.KVPR_F16 | qflags,
                                 arch=k.KVPR_ARCH_LLAMA if llama else k.KVPR_ARCH_OPT)
     rh = lambda shape, sc: (rng.standard_normal(shape, dtype=np.float32) * np.float32(sc)).astype(np.float16)
@@ -232,9 +232,12 @@ def run_columns(args):
     seq = s
     results = {}
     runs = [("kvpr", None), ("no_recompute", [0] * S)]
+    if getattr(args, "weight_pipeline_ablation", False):
+        runs.append(("kvpr_without_weight_pipeline", None))   # Table 2's "without hiding" arm: recompute waits for the whole layer
     if also_pipe:
         runs.append(("steady_state_cost_form", None))     # extension, not the paper's objective: see run_stack
     for name, splits in runs:
+        k.kvpr_set_weight_pipeline(ctx, name != "kvpr_without_weight_pipeline")
         if name == "steady_state_cost_form":
             k.kvpr_set_profile(ctx, prof, k.KVPR_COST_PIPE, args.granularity)
         for _ in range(args.warmup):
@@ -260,6 +263,7 @@ def run_columns(args):
                                f"context {s}, {gen} tokens, weights ({blob_bytes / 2**20:.0f} MiB/layer), X and KV in pinned host memory",
                    "cost_model": args.cost_model, "granularity": args.granularity, "store_int4": args.store_int4},
         "kvpr": r, "no_recompute": results["no_recompute"],
+        **({"kvpr_without_weight_pipeline": results["kvpr_without_weight_pipeline"]} if "kvpr_without_weight_pipeline" in results else {}),
         "speedup_over_no_recompute": results["no_recompute"]["ms_per_token_step"] / r["ms_per_token_step"],
         "profile": {"v_com_GBps": prof.h2d_bytes_per_s / 1e9, "v_gpu_TFLOPs": prof.gemm_flops_per_s / 1e12},
         "pinned_GiB": (S * (s + passes * (gen + args.warmup) + 2) * (x_bpp + kv_bpp) + L * blob_bytes) / 2 ** 30, "setup_s": setup_s,
@@ -728,6 +732,28 @@ def mfma_ceiling(seconds=1.5):
                     "with no data movement at all"}
 
 
+def run_small_batch_sweep(args):
+    """The setting of the paper's ablation on hiding the recomputation (Sec. 4.5, Table 2): OPT-6.7B shape, prompt 256,
+    small batches, weights offloaded, one GPU batch, so that a layer's weights (384 MiB) arrive long after its cache.
+    Three arms per batch size: no recomputation (l = 0), the planned split with the recomputation waiting for the whole
+    layer's weights, and with the fine-grained pipeline ([Wk;Wv] first)."""
+    say = lambda msg: print("bench: " + msg, file=sys.stderr, flush=True)
+    rows = []
+    layers = 8 if args.layers == 40 else args.layers      # 8 layers (3 GiB of pinned weights) unless --layers says otherwise
+    for b in (1, 2, 4, 8, 16, 32):
+        say(f"small-batch sweep: batch {b}")
+        a = argparse.Namespace(**vars(args))
+        a.model, a.batch, a.seq, a.layers, a.gpu_batches, a.gen, a.warmup = "opt-6.7b", b, 256, layers, 1, args.gen, 2
+        a.weight_pipeline_ablation, a.extension_chunks = True, 0
+        r = run_columns(a)
+        rows.append({"batch": b, "kv_cache_MiB_per_layer": 2 * b * 256 * 4096 * 2 / 2**20, "split": r["kvpr"]["split"],
+                     "tokens_per_s": {"no_recompute": r["no_recompute"]["tokens_per_s"],
+                                      "kvpr_without_weight_pipeline": r["kvpr_without_weight_pipeline"]["tokens_per_s"],
+                                      "kvpr": r["kvpr"]["tokens_per_s"]}})
+    print(json.dumps({"what": "decode tokens/s, OPT-6.7B-shaped layers with offloaded weights, context 256, one GPU batch (the setting of the "
+                              "paper's Table 2)", "layers": layers, "tokens": args.gen, "rows": rows}))
+
+
 def token_gemm_rooflines(model, b, launches=30):
     """The four weight-streaming GEMMs of a decoder layer for the decode token (q|k|v, output projection, FFN up, FFN
     down) at `model`'s width, launched as a context launches them (with its K-slice workspace), back to back over
@@ -857,6 +883,8 @@ def main():
     ap.add_argument("--columns", action="store_true",
                     help="throughput mode: column-by-column schedule with the weights offloaded too (use with --layers, --gpu-batches)")
     ap.add_argument("--gpu-batches", type=int, default=4)
+    ap.add_argument("--small-batch-sweep", action="store_true", help="column schedule at batch 1..32, context 256, OPT-6.7B shape: no recomputation / planned split without / with the fine-grained weight pipeline (the setting of the paper's Table 2); --layers and --gen apply")
+    ap.add_argument("--weight-pipeline-ablation", action="store_true", help="--columns: also time the planned split with the recomputation waiting for the whole layer's weights")
     ap.add_argument("--hidden-offload", action="store_true", help="--columns: keep the hidden states between layers in pinned host memory (Algorithm 1)")
     ap.add_argument("--kernels", action="store_true", help="launch each kernel of the path standalone (for rocprofv3 --pmc runs)")
     ap.add_argument("--power-probe", action="store_true",
@@ -906,6 +934,8 @@ def main():
     if args.power_probe:
         args.model = args.model or "opt-6.7b"
         return run_power_probe(args)
+    if args.small_batch_sweep:
+        return run_small_batch_sweep(args)
     if args.columns:
         args.model = args.model or "opt-13b"
         return print(json.dumps(run_columns(args)))

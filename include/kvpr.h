@@ -330,6 +330,12 @@ int kvpr_create_offload(const kvpr_model_desc* desc, int n_gpu_batches, void* co
  * of n_gpu_batches.  Results are unchanged bit for bit.  x_in_dev / x_out_dev of kvpr_decode_step_columns stay device
  * arrays.  KVPR_E_STATE on a context without offloaded weights. */
 int kvpr_set_hidden_offload(kvpr_ctx* ctx, int on);
+
+/* Column schedule only.  fine_grained != 0 (the default) is the paper's fine-grained MHA pipeline (Sec. 3.3 "Hiding KV
+ * cache partial recomputation"): the recomputation of a layer's batches is released by [Wk;Wv] and runs while Wq, Wo
+ * and the FFN matrices are still on the link.  0 makes every batch wait for the layer's whole weight blob first: the
+ * "without hiding" arm of the paper's ablation (Table 2), for measurements.  Results are the same either way. */
+int kvpr_set_weight_pipeline(kvpr_ctx* ctx, int fine_grained);
 int kvpr_weights_write(kvpr_ctx* ctx, int layer, const kvpr_layer_weights* host);
 int kvpr_decode_step_columns(kvpr_ctx* ctx, int seq, const void* x_in_dev, void* x_out_dev,
                              const int32_t* splits_in, int32_t* splits_out, kvpr_layer_timing* per_slot);

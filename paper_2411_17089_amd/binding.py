@@ -80,6 +80,7 @@ _SIGS = {
     "kvpr_cost": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_double)]),
     "kvpr_set_chunks": (_i, [_vp, _i]),
     "kvpr_set_hidden_offload": (_i, [_vp, _i]),
+    "kvpr_set_weight_pipeline": (_i, [_vp, _i]),
     "kvpr_cost_chunked": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_double)]),
     "kvpr_plan_split_chunked": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i, _i, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "kvpr_cost_linear": (_i, [C.POINTER(kvpr_profile_t), _i, _i, _i, _i, _i64, _i64, _i64, C.POINTER(C.c_double)]),
@@ -206,6 +207,10 @@ def kvpr_cost(prof, cost_model, split, batch, seq, hidden, elem_bytes=2):
     t = C.c_double()
     _check(lib.kvpr_cost(C.byref(prof), cost_model, split, batch, seq, hidden, elem_bytes, C.byref(t)))
     return t.value
+
+
+def kvpr_set_weight_pipeline(ctx, fine_grained):
+    _check(lib.kvpr_set_weight_pipeline(ctx, int(fine_grained)))
 
 
 def kvpr_set_hidden_offload(ctx, on):

@@ -60,6 +60,7 @@ struct kvpr_ctx {
     half* hid_all = nullptr;                 // [nb, batch, hidden] hidden states of all GPU batches
     // optional (kvpr_set_hidden_offload): the hidden states between layers live in pinned host memory, as Algorithm 1's
     // load_activation / store_activation have it; the device then holds two input and two output batches at a time
+    bool weight_pipeline = true;             // recompute released by [Wk;Wv] alone (Sec. 3.3); false: by the whole layer's weights
     bool hid_offload = false;
     half* hhid = nullptr;                    // pinned [nb, batch, hidden]
     half* hin[2] = {nullptr, nullptr};       // device: input of this slot and of the next one

@@ -671,6 +671,13 @@ extern "C" int kvpr_set_debug(kvpr_ctx* c, int flags) {
     return KVPR_OK;
 }
 
+extern "C" int kvpr_set_weight_pipeline(kvpr_ctx* c, int fine_grained) {
+    if (!c) return fail(KVPR_E_INVAL, "ctx is null");
+    if (c->nb <= 0) return fail(KVPR_E_STATE, "context was not created with kvpr_create_offload");
+    c->weight_pipeline = fine_grained != 0;
+    return KVPR_OK;
+}
+
 extern "C" int kvpr_set_hidden_offload(kvpr_ctx* c, int on) {
     if (!c) return fail(KVPR_E_INVAL, "ctx is null");
     if (c->nb <= 0) return fail(KVPR_E_STATE, "context was not created with kvpr_create_offload");
@@ -991,7 +998,7 @@ extern "C" int kvpr_decode_step_columns(kvpr_ctx* c, int seq, const void* x_in_d
             }
             // the norm's parameters arrive with [Wk;Wv]: neither the norm nor the recomputation that follows it
             // waits for Wq, Wo and the FFN matrices, which may still be on the link (Sec. 3.3 fine-grained MHA pipeline)
-            KVPR_HIP(hipStreamWaitEvent(c->compute, c->ev_wkv[wb], 0));
+            KVPR_HIP(hipStreamWaitEvent(c->compute, c->weight_pipeline ? c->ev_wkv[wb] : c->ev_wall[wb], 0));
             if (int rc = pre_attention_norm(c, &w, hid_in)) return rc;
             if (int rc = enqueue_layer(c, slot, seq, ls[slot], &w, c->xn, c->attn_out, slot % c->nbuf,
                                        per_slot ? &c->tev[slot] : nullptr, false, &wf))

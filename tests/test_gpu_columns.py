@@ -151,6 +151,16 @@ def test_recompute_runs_while_the_rest_of_the_layer_is_on_the_link(k):
         assert t0.ms_recompute > 0
         assert t0.ms_recompute_start < t0.ms_weights_landed
         assert rel_err(st.x_out.cpu().numpy(), st.oracle(splits)) <= 5e-3
+        # the "without hiding" arm of the ablation: same outputs, but now the GEMM waits for the whole layer
+        with_pipeline = st.x_out.cpu().numpy().copy()
+        k.kvpr_set_weight_pipeline(st.ctx, False)
+        _, tim = k.kvpr_decode_step_columns(st.ctx, s, n_layers * nb, dev(st.x_in), st.x_out, splits, timing=True)
+        torch.cuda.synchronize()
+        print("without the pipeline: recompute starts at %.3f ms, weights landed at %.3f ms" %
+              (tim[0].ms_recompute_start, tim[0].ms_weights_landed), flush=True)
+        assert tim[0].ms_recompute_start >= tim[0].ms_weights_landed
+        assert np.array_equal(st.x_out.cpu().numpy(), with_pipeline)
+        k.kvpr_set_weight_pipeline(st.ctx, True)
     finally:
         st.close()
 
